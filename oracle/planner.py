@@ -1,0 +1,224 @@
+"""Integer re-derivation of the workload balancer.  TEST INFRASTRUCTURE ONLY.
+
+Follows Sec. 5 of the paper: per-node cost from a profiled table with
+interpolation (Sec. 5.2, Eq. 6-7), no split along the query dimension beyond a
+row-tile cap (Sec. 5.1 fixes b_q = 1; the cap is this build's addition for
+query sets that do not fit one workgroup), a lower bound cost_l of the makespan
+found by binary search on the average-load inequality (Eq. 4), the per-node
+upper bound on the number of KV slices (Eq. 5), a grid search over each node's
+slice count, and greedy longest-first scheduling onto m slots (Eq. 3).
+
+The paper gives the solver in prose; where it is silent this file fixes:
+integer costs; round-half-up bilinear interpolation, clamped below the grid
+and linearly extrapolated above it; slice boundaries on multiples of
+``align`` tokens with equal-length slices except the last; one pass of the
+grid search in order of decreasing node cost with ties to the smaller slice
+count; ties in the schedule to the lower slot id.  Python integers are
+unbounded, so no intermediate can overflow.
+"""
+from __future__ import annotations
+
+import heapq
+from typing import Dict, List, Sequence
+
+
+def _ceil_div(a: int, b: int) -> int:
+    return -((-a) // b)
+
+
+def locate(grid: Sequence[int], x: int):
+    """Bracket x on an ascending grid -> (i0, i1, num, den); weight of i1 is num/den."""
+    k = len(grid)
+    if k == 1 or x <= grid[0]:
+        return 0, 0, 0, 1
+    if x >= grid[k - 1]:
+        return k - 2, k - 1, x - grid[k - 2], grid[k - 1] - grid[k - 2]
+    i = 0
+    while grid[i + 1] <= x:
+        i += 1
+    return i, i + 1, x - grid[i], grid[i + 1] - grid[i]
+
+
+def c_est(table: Dict, rows: int, n: int) -> int:
+    """C_est(rows, n): estimated cost of one partial attention task (Eq. 6)."""
+    r0, r1, ar, dr = locate(table["row_grid"], rows)
+    n0, n1, an, dn = locate(table["len_grid"], n)
+    c = table["cost"]
+    num = ((dr - ar) * (dn - an) * c[r0][n0] + ar * (dn - an) * c[r1][n0]
+           + (dr - ar) * an * c[r0][n1] + ar * an * c[r1][n1])
+    den = dr * dn
+    if num <= 0:
+        return 1
+    return max(1, (num + den // 2) // den)
+
+
+def slices(n: int, b: int, align: int):
+    """Cut n tokens into about b slices on multiples of align -> (count, length, last length)."""
+    length = align * _ceil_div(_ceil_div(n, b), align)
+    count = _ceil_div(n, length)
+    return count, length, n - (count - 1) * length
+
+
+def division_cost(table, rows: int, n: int, b: int, align: int) -> int:
+    count, length, last = slices(n, b, align)
+    return (count - 1) * c_est(table, rows, length) + c_est(table, rows, last)
+
+
+def lpt(sub: List[tuple], m: int):
+    """Greedy longest-first schedule of (cost, item, chunk) onto m slots.
+
+    Returns (makespan, slot of each subtask in input order, per-slot lists of
+    input indices in assignment order).
+    """
+    order = sorted(range(len(sub)), key=lambda i: (-sub[i][0], sub[i][1], sub[i][2]))
+    heap = [(0, s) for s in range(m)]
+    slot_of = [0] * len(sub)
+    lists: List[List[int]] = [[] for _ in range(m)]
+    for i in order:
+        load, s = heapq.heappop(heap)
+        slot_of[i] = s
+        lists[s].append(i)
+        heapq.heappush(heap, (load + sub[i][0], s))
+    return max(l for l, _ in heap), slot_of, lists
+
+
+def build_index(parent, node_len, req_node):
+    """Prefix paths (root first) and per-node ascending request lists; validates the forest."""
+    n_nodes = len(parent)
+    for i in range(n_nodes):
+        if not (-1 <= parent[i] < n_nodes) or parent[i] == i:
+            raise ValueError("bad parent")
+        if node_len[i] < 1:
+            raise ValueError("empty node")
+    paths, node_q = [], [[] for _ in range(n_nodes)]
+    for r, leaf in enumerate(req_node):
+        if not (0 <= leaf < n_nodes):
+            raise ValueError("bad req_node")
+        p, n = [], int(leaf)
+        while n != -1:
+            if len(p) >= n_nodes:
+                raise ValueError("cycle")
+            p.append(n)
+            n = int(parent[n])
+        p.reverse()
+        paths.append(p)
+        for n in p:
+            node_q[n].append(r)
+    return paths, node_q
+
+
+def plan(parent, node_len, req_node, group: int, num_slots: int, align: int,
+         max_rows: int, share: bool, table: Dict) -> Dict:
+    parent = [int(x) for x in parent]
+    node_len = [int(x) for x in node_len]
+    req_node = [int(x) for x in req_node]
+    m = num_slots
+    paths, node_q = build_index(parent, node_len, req_node)
+    n_nodes = len(parent)
+
+    node_q_off = [0]
+    node_q_flat: List[int] = []
+    for n in range(n_nodes):
+        node_q_flat += node_q[n]
+        node_q_off.append(len(node_q_flat))
+
+    # work items: (node, request range); a flat plan gives every request its own item
+    qpt = max(1, max_rows // group) if share else 1
+    items = []
+    first_item_of_node = [0] * n_nodes
+    for n in range(n_nodes):
+        first_item_of_node[n] = len(items)
+        nq = len(node_q[n])
+        for a in range(0, nq, qpt):
+            cnt = min(qpt, nq - a)
+            items.append({"node": n, "q_off": node_q_off[n] + a, "n_req": cnt,
+                          "rows": cnt * group, "len": node_len[n]})
+    for it in items:
+        it["cost"] = c_est(table, it["rows"], it["len"])
+        it["max_b"] = _ceil_div(it["len"], align)
+
+    def b_of(it, T):
+        return min(_ceil_div(it["cost"], T), it["max_b"])
+
+    def ok(T):
+        tot = sum(division_cost(table, it["rows"], it["len"], b_of(it, T), align) for it in items)
+        return tot <= m * T
+
+    cost_l = 0
+    if items:
+        lo = 1
+        hi = max(max(it["cost"] for it in items),
+                 _ceil_div(sum(it["cost"] for it in items), m))
+        while lo < hi:
+            mid = (lo + hi) // 2
+            if ok(mid):
+                hi = mid
+            else:
+                lo = mid + 1
+        cost_l = lo
+
+    for it in items:
+        it["ub"] = slices(it["len"], b_of(it, cost_l), align)[0]
+        it["b"] = it["ub"]
+
+    def subtasks():
+        sub = []
+        for j, it in enumerate(items):
+            count, length, last = slices(it["len"], it["b"], align)
+            for c in range(count):
+                ln = length if c < count - 1 else last
+                sub.append((c_est(table, it["rows"], ln), j, c, c * length, ln))
+        return sub
+
+    order = sorted((j for j in range(len(items)) if items[j]["ub"] > 1),
+                   key=lambda j: (-items[j]["cost"], j))
+    for j in order:
+        it = items[j]
+        best_b, best_ms, seen = None, None, set()
+        for b in range(1, it["ub"] + 1):
+            count = slices(it["len"], b, align)[0]
+            if count in seen:
+                continue
+            seen.add(count)
+            it["b"] = count
+            ms = lpt(subtasks(), m)[0]
+            if best_ms is None or ms < best_ms:
+                best_b, best_ms = count, ms
+        it["b"] = best_b
+
+    sub = subtasks()
+    makespan, slot_of, lists = lpt(sub, m) if sub else (0, [], [[] for _ in range(m)])
+
+    tasks = []
+    base = 0
+    first_task_of_item = []
+    for i, (cost, j, c, kv_begin, kv_len) in enumerate(sub):
+        it = items[j]
+        if c == 0:
+            first_task_of_item.append(i)
+        tasks.append({"item": j, "node": it["node"], "kv_begin": kv_begin, "kv_len": kv_len,
+                      "q_off": it["q_off"], "n_req": it["n_req"], "part_row_base": base,
+                      "cost": cost, "slot": slot_of[i]})
+        base += it["rows"]
+
+    slot_off, slot_tasks = [0], []
+    for s in range(m):
+        slot_tasks += lists[s]
+        slot_off.append(len(slot_tasks))
+
+    req_part_off, req_part = [0], []
+    for r, p in enumerate(paths):
+        for n in p:
+            qi = node_q[n].index(r)
+            j = first_item_of_node[n] + qi // qpt
+            it = items[j]
+            t0 = first_task_of_item[j]
+            for c in range(it["b"]):
+                req_part.append(tasks[t0 + c]["part_row_base"] + (qi % qpt) * group)
+        req_part_off.append(len(req_part))
+
+    return {"items": items, "cost_l": cost_l, "tasks": tasks, "makespan": makespan,
+            "slot_off": slot_off, "slot_tasks": slot_tasks,
+            "node_q_off": node_q_off, "node_q": node_q_flat,
+            "req_part_off": req_part_off, "req_part": req_part,
+            "part_rows": base, "paths": paths}

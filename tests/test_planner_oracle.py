@@ -1,0 +1,238 @@
+"""Pins for the integer planner oracle (oracle/planner.py), Sec. 5 of the paper.
+
+Pinned against: the paper's Table 2 at its grid points, hand-worked
+interpolation and a hand-worked three-node plan, Eq. 4-5 as inequalities,
+brute-force optimal schedules on tiny instances (the 4/3 - 1/(3m) bound of
+longest-first list scheduling), exact-tiling invariants, and a CPU replay of
+the emitted task list that must reproduce the definition oracle.
+"""
+import itertools
+import random
+
+import numpy as np
+import pytest
+
+from oracle import attention as A
+from oracle import method as M
+from oracle import planner as P
+from golden_tables import load_table2
+from workloads import (HeadConfig, make_workload, two_level_forest, three_level_forest,
+                       random_forest, unshared_forest, concat_forests, Forest, DTYPE_BF16, DTYPE_FP16)
+
+TABLE2 = load_table2()
+LINEAR = {"row_grid": [1], "len_grid": [100, 200], "cost": [[100, 200]]}   # cost = max(n, 100)
+
+
+def test_table2_values_at_grid_points():
+    """Sec. 5.2, Table 2: every printed entry is returned at its own (n_q, n)."""
+    assert TABLE2["row_grid"] == [1, 2, 5, 10, 20, 50, 100]
+    assert TABLE2["len_grid"] == [512, 1024, 2048, 4096, 8192, 16384]
+    assert P.c_est(TABLE2, 1, 512) == 36 and P.c_est(TABLE2, 100, 16384) == 746
+    assert P.c_est(TABLE2, 10, 4096) == 126 and P.c_est(TABLE2, 50, 1024) == 109
+    for ri, r in enumerate(TABLE2["row_grid"]):
+        for ni, n in enumerate(TABLE2["len_grid"]):
+            assert P.c_est(TABLE2, r, n) == TABLE2["cost"][ri][ni]
+
+
+def test_interpolation_lies_between_neighbours_and_clamps():
+    rng = random.Random(0)
+    rg, ng, c = TABLE2["row_grid"], TABLE2["len_grid"], TABLE2["cost"]
+    for _ in range(500):
+        ri, ni = rng.randrange(len(rg) - 1), rng.randrange(len(ng) - 1)
+        r, n = rng.randint(rg[ri], rg[ri + 1]), rng.randint(ng[ni], ng[ni + 1])
+        corners = [c[ri][ni], c[ri + 1][ni], c[ri][ni + 1], c[ri + 1][ni + 1]]
+        assert min(corners) <= P.c_est(TABLE2, r, n) <= max(corners)
+    assert P.c_est(TABLE2, 1, 16) == 36            # below the grid: launch-dominated, clamped
+    assert P.c_est(TABLE2, 1, 32768) == 283 + 2 * (283 - 156)   # above: continue the last segment
+
+
+def test_interpolation_hand_worked_rounding():
+    t = {"row_grid": [1, 3], "len_grid": [10, 20], "cost": [[10, 20], [30, 41]]}
+    assert P.c_est(t, 2, 15) == 25                 # 505/20 = 25.25
+    t["cost"][1][1] = 42
+    assert P.c_est(t, 2, 15) == 26                 # 510/20 = 25.5, half rounds up
+    assert P.c_est(t, 1, 30) == 30                 # extrapolated along n
+    assert P.c_est(t, 5, 10) == 50                 # extrapolated along rows
+    assert P.c_est(t, 1, 5) == 10                  # clamped
+    assert P.c_est({"row_grid": [4], "len_grid": [8], "cost": [[7]]}, 99, 1) == 7
+
+
+def test_slices_tile_exactly():
+    for n in list(range(1, 200)) + [4096, 131072, 32769]:
+        for align in (16, 32, 256):
+            for b in (1, 2, 3, 5, 8, 33, 1000):
+                count, length, last = P.slices(n, b, align)
+                assert length % align == 0 and 0 < last <= length
+                assert (count - 1) * length + last == n
+                assert count <= max(1, b)
+                assert P.slices(n, count, align)[0] == count      # normal form is stable
+
+
+def _brute_opt(costs, m):
+    best = None
+    for assign in itertools.product(range(m), repeat=len(costs)):
+        loads = [0] * m
+        for c, s in zip(costs, assign):
+            loads[s] += c
+        ms = max(loads)
+        best = ms if best is None else min(best, ms)
+    return best
+
+
+def test_longest_first_schedule_against_brute_force_optimum():
+    rng = random.Random(1)
+    for _ in range(120):
+        m = rng.randint(2, 3)
+        t = rng.randint(1, 7)
+        costs = [rng.randint(1, 30) for _ in range(t)]
+        sub = [(c, i, 0) for i, c in enumerate(costs)]
+        ms, slot_of, lists = P.lpt(sub, m)
+        opt = _brute_opt(costs, m)
+        assert opt <= ms
+        assert 3 * m * ms <= (4 * m - 1) * opt
+        assert ms >= max(max(costs), -(-sum(costs) // m))
+        assert sorted(i for l in lists for i in l) == list(range(t))
+        for s, l in enumerate(lists):
+            assert all(slot_of[i] == s for i in l)
+    # ties go to the lowest slot id and the order inside a slot is assignment order
+    ms, slot_of, lists = P.lpt([(5, 0, 0), (5, 1, 0), (5, 2, 0), (1, 3, 0)], 3)
+    assert slot_of == [0, 1, 2, 0] and lists[0] == [0, 3] and ms == 6
+
+
+def test_hand_worked_three_node_plan():
+    """Root of 1200 tokens under two requests, two 100-token leaves, 4 slots, cost = tokens.
+
+    Total load 1400 -> cost_l = 350 (Eq. 4); root bound ceil(1200/350) = 4 slices (Eq. 5);
+    makespans for 1..4 root slices: 1200, 600, 400, 400 -> 3 slices (tie to the coarser).
+    """
+    f = two_level_forest(1200, [100, 100])
+    p = P.plan(f.parent, f.node_len, f.req_node, group=1, num_slots=4, align=100,
+               max_rows=64, share=True, table=LINEAR)
+    assert p["cost_l"] == 350
+    assert [it["ub"] for it in p["items"]] == [4, 1, 1]
+    assert [it["b"] for it in p["items"]] == [3, 1, 1]
+    assert p["makespan"] == 400
+    assert [(t["node"], t["kv_begin"], t["kv_len"]) for t in p["tasks"]] == \
+        [(0, 0, 400), (0, 400, 400), (0, 800, 400), (1, 0, 100), (2, 0, 100)]
+    assert [t["slot"] for t in p["tasks"]] == [0, 1, 2, 3, 3]
+    assert [t["part_row_base"] for t in p["tasks"]] == [0, 2, 4, 6, 7]
+    assert p["slot_off"] == [0, 1, 2, 3, 5] and p["slot_tasks"] == [0, 1, 2, 3, 4]
+    assert p["node_q"] == [0, 1, 0, 1] and p["node_q_off"] == [0, 2, 3, 4]
+    assert p["req_part_off"] == [0, 4, 8]
+    assert p["req_part"] == [0, 2, 4, 6, 1, 3, 5, 7]
+    assert p["part_rows"] == 8
+
+
+def _check_invariants(f, p, group, m, align):
+    n_q = np.zeros(f.num_nodes, dtype=np.int64)
+    for r in range(f.num_requests):
+        for n in f.path(r):
+            n_q[n] += 1
+    # slices of one item tile [0, len) in order, on aligned boundaries
+    by_item = {}
+    for t in p["tasks"]:
+        by_item.setdefault(t["item"], []).append(t)
+    for j, ts in by_item.items():
+        pos = 0
+        for t in ts:
+            assert t["kv_begin"] == pos and t["kv_begin"] % align == 0 and t["kv_len"] > 0
+            pos += t["kv_len"]
+        assert pos == f.node_len[p["items"][j]["node"]]
+    # every (request, head-of-group, token) is covered once
+    covered = sum(t["n_req"] * group * t["kv_len"] for t in p["tasks"])
+    assert covered == int((f.node_len.astype(np.int64) * n_q).sum()) * group
+    # schedule: each task in exactly one slot, loads give the makespan, lower bounds hold
+    assert sorted(p["slot_tasks"]) == list(range(len(p["tasks"])))
+    loads = [sum(p["tasks"][i]["cost"] for i in p["slot_tasks"][p["slot_off"][s]:p["slot_off"][s + 1]])
+             for s in range(m)]
+    assert max(loads) == p["makespan"]
+    total = sum(t["cost"] for t in p["tasks"])
+    assert p["makespan"] >= max(-(-total // m), max(t["cost"] for t in p["tasks"]))
+    # Eq. 5: slice counts stay within the bound derived from cost_l
+    for it in p["items"]:
+        assert 1 <= it["b"] <= it["ub"] <= max(1, -(-it["cost"] // p["cost_l"]))
+    # Eq. 4 at cost_l: the division it induces fits m slots on average, the next finer T does not
+    def tot(T):
+        return sum(P.division_cost(p["table"], it["rows"], it["len"],
+                                   min(-(-it["cost"] // T), it["max_b"]), align) for it in p["items"])
+    assert tot(p["cost_l"]) <= m * p["cost_l"]
+    if p["cost_l"] > 1:
+        assert tot(p["cost_l"] - 1) > m * (p["cost_l"] - 1)
+    # partial rows: disjoint, dense
+    rows = sorted((t["part_row_base"], t["n_req"] * group) for t in p["tasks"])
+    pos = 0
+    for base, cnt in rows:
+        assert base == pos
+        pos += cnt
+    assert pos == p["part_rows"]
+
+
+FORESTS = {
+    "docqa": lambda: two_level_forest(10000, [50] * 24),
+    "three": lambda: three_level_forest(2048, [8192] * 4, 5, [37 + 13 * i for i in range(20)]),
+    "random": lambda: random_forest(40, 5, 2.0, 512, 1.0, 16, 32768, seed=8),
+    "mixed": lambda: concat_forests(two_level_forest(30000, [100] * 9), unshared_forest([7000, 8000, 50])),
+}
+
+
+@pytest.mark.parametrize("name", sorted(FORESTS))
+@pytest.mark.parametrize("share", [True, False])
+@pytest.mark.parametrize("m,align,max_rows,group", [(8, 256, 64, 4), (3, 32, 16, 8), (64, 64, 64, 1)])
+def test_plan_invariants(name, share, m, align, max_rows, group):
+    f = FORESTS[name]()
+    p = P.plan(f.parent, f.node_len, f.req_node, group, m, align, max_rows, share, TABLE2)
+    p["table"] = TABLE2
+    _check_invariants(f, p, group, m, align)
+
+
+def test_docqa_leaves_are_not_divided():
+    """Sec. 5.1: Eq. 5 leaves tasks far below the average cost (the per-request questions) whole."""
+    f = FORESTS["docqa"]()
+    p = P.plan(f.parent, f.node_len, f.req_node, 4, 16, 32, 64, True, LINEAR)
+    assert all(it["b"] == 1 for it in p["items"] if it["len"] == 50)
+    assert max(it["b"] for it in p["items"] if it["len"] == 10000) > 1
+
+
+def test_flat_plan_gives_every_request_its_own_tasks():
+    f = two_level_forest(640, [33, 70, 5])
+    p = P.plan(f.parent, f.node_len, f.req_node, 4, 4, 32, 64, False, LINEAR)
+    assert all(it["n_req"] == 1 for it in p["items"])
+    assert sum(1 for it in p["items"] if it["node"] == 0) == 3
+
+
+def test_requests_ending_inside_the_tree_and_unused_nodes():
+    f = Forest(np.array([-1, 0, 0, -1]), np.array([300, 40, 50, 77]), np.array([1, 0, 1]))
+    p = P.plan(f.parent, f.node_len, f.req_node, 2, 2, 32, 64, True, LINEAR)
+    assert {it["node"] for it in p["items"]} == {0, 1}        # nodes 2 and 3 have no request
+    assert p["node_q"] == [0, 1, 2, 0, 2]
+    p["table"] = LINEAR
+    _check_invariants(f, p, 2, 2, 32)
+
+
+@pytest.mark.parametrize("bad", [
+    (np.array([0]), np.array([4]), np.array([0])),           # self parent
+    (np.array([1, 0]), np.array([4, 4]), np.array([0])),     # cycle
+    (np.array([-1]), np.array([0]), np.array([0])),          # empty node
+    (np.array([-1]), np.array([4]), np.array([1])),          # request beyond the forest
+    (np.array([5]), np.array([4]), np.array([0])),           # parent out of range
+])
+def test_malformed_forests_are_rejected(bad):
+    with pytest.raises(ValueError):
+        P.plan(bad[0], bad[1], bad[2], 1, 2, 32, 64, True, LINEAR)
+
+
+@pytest.mark.parametrize("share", [True, False])
+@pytest.mark.parametrize("dtype,hq,hkv,max_rows", [(DTYPE_BF16, 8, 2, 8), (DTYPE_FP16, 2, 2, 64)])
+def test_cpu_replay_of_the_task_list_equals_the_definition(share, dtype, hq, hkv, max_rows):
+    """Run the emitted tasks (PAC per task, POR per request) in fp64: must be the oracle's output."""
+    f = three_level_forest(90, [130, 40], 3, [5, 33, 64, 1, 17, 48])
+    head = HeadConfig(hq, hkv, 16, dtype, page_size=16)
+    w = make_workload("replay", f, head, seed=77, poison=True)
+    table = {"row_grid": [1, 64], "len_grid": [16, 256], "cost": [[20, 100], [40, 300]]}
+    p = P.plan(f.parent, f.node_len, f.req_node, head.group, 40, 16, max_rows, share, table)
+    assert any(it["b"] > 1 for it in p["items"])
+    tasks = [(t["node"], t["kv_begin"], t["kv_len"], t["q_off"], t["n_req"], t["part_row_base"])
+             for t in p["tasks"]]
+    got = M.replay_tasks(w, tasks, p["node_q"], p["req_part_off"], p["req_part"])
+    ref, _ = A.decode_attention_workload(w)
+    assert np.max(np.abs(got - ref)) < 1e-13

@@ -1,0 +1,180 @@
+"""Prefix forests: which KV-cache node is a prefix of which, and where requests end.
+
+A forest is three int32 arrays.  ``parent[i]`` is the node whose tokens come
+directly before node ``i``'s tokens (-1 for a top-level prefix, i.e. a child of
+the virtual root that joins unrelated prefixes), ``node_len[i]`` is the number
+of tokens the node holds and ``req_node[r]`` is the last node on request
+``r``'s root-to-leaf path.  Shapes follow the workloads the paper evaluates
+(two-level document-QA trees, full k-ary trees, a degenerate left-spine tree)
+and the configurations this build is measured on.
+"""
+from __future__ import annotations
+
+from dataclasses import dataclass
+from typing import List, Sequence
+
+import numpy as np
+
+
+@dataclass
+class Forest:
+    parent: np.ndarray      # int32 [N]
+    node_len: np.ndarray    # int32 [N]
+    req_node: np.ndarray    # int32 [B]
+
+    def __post_init__(self):
+        self.parent = np.ascontiguousarray(self.parent, dtype=np.int32)
+        self.node_len = np.ascontiguousarray(self.node_len, dtype=np.int32)
+        self.req_node = np.ascontiguousarray(self.req_node, dtype=np.int32)
+        assert self.parent.shape == self.node_len.shape
+
+    @property
+    def num_nodes(self) -> int:
+        return int(self.parent.shape[0])
+
+    @property
+    def num_requests(self) -> int:
+        return int(self.req_node.shape[0])
+
+    def path(self, r: int) -> List[int]:
+        """Root-to-leaf node ids of request r (input plumbing for generators and reports)."""
+        out = []
+        n = int(self.req_node[r])
+        while n >= 0:
+            out.append(n)
+            n = int(self.parent[n])
+        return out[::-1]
+
+
+def two_level_forest(root_len: int, leaf_lens: Sequence[int]) -> Forest:
+    """One shared prefix, one private suffix per request (document QA)."""
+    b = len(leaf_lens)
+    parent = np.array([-1] + [0] * b, dtype=np.int32)
+    node_len = np.array([root_len] + list(leaf_lens), dtype=np.int32)
+    req_node = np.arange(1, b + 1, dtype=np.int32)
+    return Forest(parent, node_len, req_node)
+
+
+def three_level_forest(root_len: int, mid_lens: Sequence[int], leaves_per_mid: int,
+                       leaf_lens: Sequence[int]) -> Forest:
+    """Root shared by all, each mid node shared by ``leaves_per_mid`` requests."""
+    nm = len(mid_lens)
+    assert len(leaf_lens) == nm * leaves_per_mid
+    parent = [-1] + [0] * nm
+    node_len = [root_len] + list(mid_lens)
+    req_node = []
+    for m in range(nm):
+        for j in range(leaves_per_mid):
+            parent.append(1 + m)
+            node_len.append(int(leaf_lens[m * leaves_per_mid + j]))
+            req_node.append(len(parent) - 1)
+    return Forest(np.array(parent), np.array(node_len), np.array(req_node))
+
+
+def unshared_forest(lens: Sequence[int]) -> Forest:
+    """Every request has its own single node under the virtual root (no sharing)."""
+    b = len(lens)
+    return Forest(np.full(b, -1, dtype=np.int32), np.array(lens, dtype=np.int32),
+                  np.arange(b, dtype=np.int32))
+
+
+def full_kary_forest(k: int, depth: int, node_len_of_depth) -> Forest:
+    """Full k-ary tree with ``depth`` levels; one request per leaf.
+
+    ``node_len_of_depth(level)`` gives the token count of a node at ``level`` (1 = root).
+    """
+    parent, node_len, level_nodes = [-1], [int(node_len_of_depth(1))], [0]
+    for lvl in range(2, depth + 1):
+        nxt = []
+        for p in level_nodes:
+            for _ in range(k):
+                parent.append(p)
+                node_len.append(int(node_len_of_depth(lvl)))
+                nxt.append(len(parent) - 1)
+        level_nodes = nxt
+    return Forest(np.array(parent), np.array(node_len), np.array(level_nodes))
+
+
+def degenerate_forest(depth: int, spine_len: int, leaf_len: int) -> Forest:
+    """Left-spine tree: at every level only the left child has children.
+
+    Each spine node has a right child that is a leaf; the last spine node is
+    itself a leaf.  One request per leaf.
+    """
+    parent, node_len, req_node = [-1], [spine_len], []
+    spine = 0
+    for _ in range(depth - 1):
+        parent.append(spine); node_len.append(leaf_len); req_node.append(len(parent) - 1)
+        parent.append(spine); node_len.append(spine_len); spine = len(parent) - 1
+    req_node.append(spine)
+    return Forest(np.array(parent), np.array(node_len), np.array(req_node))
+
+
+def random_forest(num_leaves: int, max_depth: int, poisson_mean: float,
+                  median_len: int, sigma: float, min_len: int, max_len: int,
+                  seed: int) -> Forest:
+    """Seeded irregular forest: child count 1+Poisson(mean), log-normal node lengths.
+
+    Breadth-first growth.  A new top-level prefix is started whenever the
+    frontier is empty; a popped node below ``max_depth`` gets 1+Poisson
+    children, clipped so the number of leaves never exceeds ``num_leaves``;
+    growth stops when exactly ``num_leaves`` leaves exist.  One request per leaf.
+    """
+    rng = np.random.Generator(np.random.PCG64(seed))
+    parent: List[int] = []
+    depth: List[int] = []
+    nchild: List[int] = []
+    frontier: List[int] = []          # nodes that may still get children
+    leaves = 0                        # current number of childless nodes
+
+    def new_node(p: int, d: int) -> int:
+        parent.append(p); depth.append(d); nchild.append(0)
+        return len(parent) - 1
+
+    head = 0
+    while leaves < num_leaves:
+        if head >= len(frontier):
+            frontier.append(new_node(-1, 1))
+            leaves += 1
+            continue
+        n = frontier[head]; head += 1
+        if depth[n] >= max_depth:
+            continue
+        # giving c children to a childless node turns one leaf into c leaves
+        c = min(1 + int(rng.poisson(poisson_mean)), num_leaves - leaves + 1)
+        for _ in range(c):
+            frontier.append(new_node(n, depth[n] + 1))
+        nchild[n] = c
+        leaves += c - 1
+    n_nodes = len(parent)
+    z = rng.standard_normal(n_nodes)
+    lens = np.clip(np.rint(np.exp(np.log(float(median_len)) + sigma * z)), min_len, max_len)
+    req_node = [i for i in range(n_nodes) if nchild[i] == 0]
+    assert len(req_node) == num_leaves, (len(req_node), num_leaves)
+    return Forest(np.array(parent), lens.astype(np.int32), np.array(req_node))
+
+
+def concat_forests(a: Forest, b: Forest) -> Forest:
+    """Both forests under one virtual root; b's node ids are shifted by a.num_nodes."""
+    shift = a.num_nodes
+    pb = b.parent.copy()
+    pb[pb >= 0] += shift
+    return Forest(np.concatenate([a.parent, pb]),
+                  np.concatenate([a.node_len, b.node_len]),
+                  np.concatenate([a.req_node, b.req_node + shift]))
+
+
+def forest_stats(f: Forest) -> dict:
+    """Token counts used in reports: unique tokens, per-request-summed tokens, sharing ratio."""
+    n_q = np.zeros(f.num_nodes, dtype=np.int64)
+    for r in range(f.num_requests):
+        for n in f.path(r):
+            n_q[n] += 1
+    used = n_q > 0
+    unique = int(f.node_len[used].astype(np.int64).sum())
+    flat = int((f.node_len.astype(np.int64) * n_q).sum())
+    return {"num_nodes": f.num_nodes, "num_requests": f.num_requests,
+            "unique_tokens": unique, "flat_tokens": flat,
+            "mean_sharing": (flat / unique) if unique else 0.0,
+            "max_n_q": int(n_q.max()) if f.num_nodes else 0,
+            "max_node_len": int(f.node_len.max()) if f.num_nodes else 0}
