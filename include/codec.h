@@ -1,0 +1,231 @@
+/*
+ * codec.h - C ABI of the prefix-shared decode-attention library for MI355X (gfx950).
+ *
+ * The library computes, for a batch of decode requests whose contexts form a
+ * forest of shared KV-cache nodes, out[r, hq, :] = softmax(scale * q[r, hq] . K_r^T) V_r
+ * where K_r, V_r are the KV rows of the nodes on request r's prefix path,
+ * concatenated root to leaf (paper Sec. 2.2 Eq. 1-2 and Sec. 4.1).  Each node's
+ * KV rows are read from HBM once for the queries of all requests below the
+ * node (partial attention computation, Alg. 2), and the per-node partial
+ * results are merged per query (partial output reduction, Alg. 3; executor,
+ * Alg. 4).  A host-side planner estimates per-node cost from a profiled table,
+ * divides long nodes along the KV dimension and schedules the pieces onto
+ * persistent workgroups (Sec. 5, Eq. 3-7).
+ *
+ * Conventions
+ *  - Every function returns a status (0 = CODEC_OK, negative = error) unless
+ *    stated otherwise; nothing throws or aborts; output parameters are left
+ *    untouched on error.
+ *  - "host" pointers are ordinary memory, borrowed for the duration of the
+ *    call only.  "device" pointers are HIP device memory owned by the caller
+ *    (e.g. PyTorch tensors); the library allocates no device memory.
+ *  - Strides and offsets are in elements unless a name says bytes.
+ *  - Query head hq uses KV head hq / (num_q_heads / num_kv_heads).
+ */
+#ifndef CODEC_H
+#define CODEC_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum {
+    CODEC_OK = 0,
+    CODEC_ERR_INVALID_ARGUMENT = -1,    /* null pointer, non-positive count, bad option        */
+    CODEC_ERR_INVALID_TREE = -2,        /* bad parent/req_node index, cycle, empty node, short page list */
+    CODEC_ERR_UNSUPPORTED = -3,         /* head_dim != 128, unknown dtype, page size, group size */
+    CODEC_ERR_WORKSPACE_TOO_SMALL = -4,
+    CODEC_ERR_HIP = -5,                 /* a HIP runtime call failed                           */
+    CODEC_ERR_NOT_UPLOADED = -6,        /* decode called before codec_plan_upload              */
+    CODEC_ERR_OUT_OF_MEMORY = -7        /* host allocation failed                              */
+};
+
+enum { CODEC_DTYPE_FP16 = 0, CODEC_DTYPE_BF16 = 1 };
+
+typedef struct codec_plan codec_plan_t;         /* opaque, library-owned, immutable after create */
+
+/* Head layout (MHA / GQA / MQA; Sec. 6 "supports MHA, MQA and GQA"). */
+typedef struct {
+    int32_t num_q_heads;
+    int32_t num_kv_heads;       /* must divide num_q_heads; group = ratio, 1..64        */
+    int32_t head_dim;           /* 128                                                  */
+    int32_t dtype;              /* CODEC_DTYPE_*: type of q, K, V and out               */
+    int32_t page_size;          /* tokens per KV page, a multiple of 16                 */
+    float   scale;              /* softmax scale, 1/sqrt(head_dim) in Eq. 1             */
+} codec_head_config;
+
+/*
+ * KV-cache forest (Sec. 4.1): node i holds node_len[i] >= 1 tokens that follow
+ * the tokens of parent[i]; parent[i] = -1 makes i a child of the virtual root
+ * that joins unrelated prefixes.  Request r's context ends with node
+ * req_node[r] (a leaf or an internal node).  Node i owns the whole pages
+ * page_ids[node_page_off[i] .. node_page_off[i+1]) and fills them in order, so
+ * only its last page may be partly used.  All arrays are host memory.
+ */
+typedef struct {
+    int32_t        num_nodes;
+    const int32_t *parent;          /* [num_nodes]      */
+    const int32_t *node_len;        /* [num_nodes]      */
+    int32_t        num_requests;
+    const int32_t *req_node;        /* [num_requests]   */
+    const int32_t *node_page_off;   /* [num_nodes + 1]  */
+    const int32_t *page_ids;        /* [node_page_off[num_nodes]] */
+} codec_tree;
+
+/*
+ * Profiled cost table C_est (Sec. 5.2, Eq. 6; Table 2 is such a table):
+ * cost[i * num_len_points + j] is the measured cost, in any integer unit, of
+ * one workgroup running partial attention on row_grid[i] query rows (requests
+ * x heads of one group) against len_grid[j] tokens.  Grids ascend strictly;
+ * costs are > 0.  Between grid points the planner interpolates bilinearly in
+ * integers (round half up); below the grid it clamps, above it continues the
+ * last segment linearly.
+ */
+typedef struct {
+    int32_t        num_row_points;
+    int32_t        num_len_points;
+    const int32_t *row_grid;
+    const int32_t *len_grid;
+    const int64_t *cost;
+} codec_cost_table;
+
+typedef struct {
+    int32_t num_slots;      /* m of Eq. 3: persistent workgroups per KV head; 0 = 512 / num_kv_heads */
+    int32_t split_align;    /* KV slices start on multiples of this many tokens; a multiple of
+                               max(32, page_size); 0 = 256                                          */
+    int32_t max_rows;       /* most query rows (requests x group) one task may hold, 1..64,
+                               >= group; 0 = 64.  Larger query sets are cut into row tiles.        */
+    int32_t share;          /* 1 = prefix-shared plan; 0 = flat baseline: every request gets its
+                               own tasks for every node on its path, nothing shared across requests */
+    const codec_cost_table *cost;   /* NULL = built-in table                                        */
+} codec_plan_options;
+
+/* One work item of the division problem: a node (or a row tile of it) with its queries. */
+typedef struct {
+    int32_t node;
+    int32_t q_off;          /* first entry of this item's requests in node_q                      */
+    int32_t n_req;          /* requests in the item; rows = n_req * group                         */
+    int32_t rows;
+    int32_t len;            /* tokens of the node                                                 */
+    int32_t ub;             /* upper bound on KV slices from Eq. 5                                */
+    int32_t b;              /* chosen number of KV slices b_k                                     */
+    int32_t reserved;
+    int64_t cost;           /* C_est(rows, len)                                                   */
+} codec_item;
+
+/* One partial-attention task: a KV slice of an item. */
+typedef struct {
+    int32_t item;
+    int32_t node;
+    int32_t kv_begin;       /* first token of the slice inside the node                           */
+    int32_t kv_len;
+    int32_t q_off;
+    int32_t n_req;
+    int32_t part_row_base;  /* first of the task's n_req * group partial rows                     */
+    int32_t slot;           /* workgroup slot the task is scheduled on                            */
+    int64_t cost;           /* C_est(rows, kv_len)                                                */
+} codec_task;
+
+/*
+ * Read-only host view of a plan; pointers stay valid until codec_plan_destroy.
+ * node_q lists, per node, the requests whose path contains it (ascending);
+ * slot s runs tasks slot_tasks[slot_off[s] .. slot_off[s+1]) in that order;
+ * request r merges the partials whose first rows are
+ * req_part[req_part_off[r] .. req_part_off[r+1]) (root to leaf, slices in order).
+ */
+typedef struct {
+    int32_t           num_items;
+    const codec_item *items;
+    int32_t           num_tasks;
+    const codec_task *tasks;
+    int32_t           num_slots;
+    const int32_t    *slot_off;
+    const int32_t    *slot_tasks;
+    int32_t           num_nodes;
+    const int32_t    *node_q_off;
+    const int32_t    *node_q;
+    int32_t           num_requests;
+    const int32_t    *req_part_off;
+    const int32_t    *req_part;
+    int64_t           cost_l;       /* lower bound of the makespan from Eq. 4                     */
+    int64_t           makespan;     /* estimated cost of the most loaded slot                     */
+    int32_t           part_rows;    /* partial rows per KV head                                   */
+    int32_t           split_align;
+    int32_t           max_rows;
+    int32_t           share;
+} codec_plan_view;
+
+/*
+ * Layout of the K and V page pools (both pools share it): element (page, slot, kv head, c)
+ * lives at page * page_stride + slot * token_stride + kv head * head_stride + c.  The 128
+ * elements of a head are contiguous; strides are multiples of 8 elements.  num_pages is
+ * the pool size; every page id of the plan must be below it.
+ */
+typedef struct {
+    int64_t num_pages;
+    int64_t page_stride;
+    int64_t token_stride;
+    int64_t head_stride;
+} codec_kv_layout;
+
+/*
+ * Build a plan (Sec. 5): index the forest (per-node query sets, per-request
+ * paths; Sec. 4.1), estimate costs (Eq. 6-7), bound and choose the number of
+ * KV slices of every node (Eq. 4-5, grid search) and schedule the slices
+ * longest-first onto num_slots slots (Eq. 3).  Host only: no HIP call is made.
+ * All inputs are host memory and are copied.  *out receives the plan.
+ */
+int codec_plan_create(const codec_tree *tree, const codec_head_config *head,
+                      const codec_plan_options *options, codec_plan_t **out);
+
+/* Frees a plan (host memory only).  NULL is accepted. */
+int codec_plan_destroy(codec_plan_t *plan);
+
+/* Fills *view with pointers into the plan's own host arrays. */
+int codec_plan_export(const codec_plan_t *plan, codec_plan_view *view);
+
+/* C_est(rows, len) of Eq. 6 on `table` (NULL = built-in); returns the cost, or a negative status. */
+int64_t codec_cost_estimate(const codec_cost_table *table, int32_t rows, int32_t len);
+
+/* The built-in cost table (static storage). */
+const codec_cost_table *codec_default_cost_table(void);
+
+/* Bytes of device memory the plan's task lists and indexes need. */
+size_t codec_plan_device_bytes(const codec_plan_t *plan);
+
+/*
+ * Copies the plan's device-side metadata into `device_meta` (device memory,
+ * >= codec_plan_device_bytes, 256-byte aligned, caller-owned, must outlive all
+ * decode calls on this plan) on `stream` (a hipStream_t, may be NULL) and
+ * remembers the pointer.  Call once per plan before decoding.
+ */
+int codec_plan_upload(codec_plan_t *plan, void *device_meta, size_t device_meta_bytes, void *stream);
+
+/* Bytes of scratch (partial outputs with their softmax statistics) one decode call needs. */
+size_t codec_plan_workspace_bytes(const codec_plan_t *plan);
+
+/*
+ * One decode-attention step (Alg. 4): partial attention for every scheduled
+ * task, then per-query reduction, enqueued on `stream`; returns without
+ * synchronising.
+ *   q        device [num_requests][num_q_heads][128], dtype of the plan, 16-byte aligned
+ *   k_pages, v_pages   device page pools, laid out by `layout`, 16-byte aligned
+ *   out      device [num_requests][num_q_heads][128], same dtype
+ *   workspace  device scratch, >= codec_plan_workspace_bytes, 256-byte aligned;
+ *              contents are overwritten; calls sharing a workspace must not overlap
+ */
+int codec_decode_attention(const codec_plan_t *plan, const void *q,
+                           const void *k_pages, const void *v_pages,
+                           const codec_kv_layout *layout, void *out,
+                           void *workspace, size_t workspace_bytes, void *stream);
+
+/* Static, human-readable name of a status code. */
+const char *codec_status_string(int status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* CODEC_H */

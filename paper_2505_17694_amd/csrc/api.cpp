@@ -1,0 +1,227 @@
+// C ABI of the library (include/codec.h): argument checks, plan ownership, launches.
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <cstring>
+#include <new>
+
+#include "codec.h"
+#include "kernels.hpp"
+#include "planner.hpp"
+
+struct codec_plan {
+    codec::PlanData d;
+    void *device_meta = nullptr;
+    int32_t max_page_id = -1;
+    int32_t max_task_rows = 0;
+};
+
+namespace {
+
+size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+size_t part_o_bytes(const codec::PlanData &d)
+{
+    return align_up(size_t(d.head.num_kv_heads) * size_t(d.part_rows) * 128 * sizeof(float), 256);
+}
+
+size_t part_ml_bytes(const codec::PlanData &d)
+{
+    return align_up(size_t(d.head.num_kv_heads) * size_t(d.part_rows) * 2 * sizeof(float), 256);
+}
+
+bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+}  // namespace
+
+extern "C" {
+
+int codec_plan_create(const codec_tree *tree, const codec_head_config *head,
+                      const codec_plan_options *options, codec_plan_t **out)
+{
+    if (!tree || !head || !out) return CODEC_ERR_INVALID_ARGUMENT;
+    codec_plan_options opt{};
+    opt.share = 1;
+    if (options) opt = *options;
+    codec_plan *p = new (std::nothrow) codec_plan;
+    if (!p) return CODEC_ERR_OUT_OF_MEMORY;
+    int st;
+    try {
+        st = codec::build_plan(*tree, *head, opt, p->d);
+    } catch (const std::bad_alloc &) {
+        st = CODEC_ERR_OUT_OF_MEMORY;
+    }
+    if (st != CODEC_OK) {
+        delete p;
+        return st;
+    }
+    for (int32_t id : p->d.page_ids) p->max_page_id = id > p->max_page_id ? id : p->max_page_id;
+    for (const codec_task &t : p->d.tasks) {
+        const int32_t rows = t.n_req * p->d.group;
+        p->max_task_rows = rows > p->max_task_rows ? rows : p->max_task_rows;
+    }
+    *out = p;
+    return CODEC_OK;
+}
+
+int codec_plan_destroy(codec_plan_t *plan)
+{
+    delete plan;
+    return CODEC_OK;
+}
+
+int codec_plan_export(const codec_plan_t *plan, codec_plan_view *v)
+{
+    if (!plan || !v) return CODEC_ERR_INVALID_ARGUMENT;
+    const codec::PlanData &d = plan->d;
+    v->num_items = int32_t(d.items.size());
+    v->items = d.items.data();
+    v->num_tasks = int32_t(d.tasks.size());
+    v->tasks = d.tasks.data();
+    v->num_slots = d.num_slots;
+    v->slot_off = d.slot_off.data();
+    v->slot_tasks = d.slot_tasks.data();
+    v->num_nodes = d.num_nodes;
+    v->node_q_off = d.node_q_off.data();
+    v->node_q = d.node_q.data();
+    v->num_requests = d.num_requests;
+    v->req_part_off = d.req_part_off.data();
+    v->req_part = d.req_part.data();
+    v->cost_l = d.cost_l;
+    v->makespan = d.makespan;
+    v->part_rows = d.part_rows;
+    v->split_align = d.split_align;
+    v->max_rows = d.max_rows;
+    v->share = d.share;
+    return CODEC_OK;
+}
+
+int64_t codec_cost_estimate(const codec_cost_table *table, int32_t rows, int32_t len)
+{
+    if (rows < 1 || len < 1) return CODEC_ERR_INVALID_ARGUMENT;
+    if (!table) return codec::builtin_cost_table().estimate(rows, len);
+    if (table->num_row_points < 1 || table->num_len_points < 1 || !table->row_grid || !table->len_grid || !table->cost)
+        return CODEC_ERR_INVALID_ARGUMENT;
+    codec::CostTable t;
+    try {
+        t.row_grid.assign(table->row_grid, table->row_grid + table->num_row_points);
+        t.len_grid.assign(table->len_grid, table->len_grid + table->num_len_points);
+        t.cost.assign(table->cost, table->cost + size_t(table->num_row_points) * table->num_len_points);
+    } catch (const std::bad_alloc &) {
+        return CODEC_ERR_OUT_OF_MEMORY;
+    }
+    if (int st = t.validate()) return st;
+    return t.estimate(rows, len);
+}
+
+const codec_cost_table *codec_default_cost_table(void)
+{
+    static codec_cost_table view;
+    const codec::CostTable &t = codec::builtin_cost_table();
+    view.num_row_points = int32_t(t.row_grid.size());
+    view.num_len_points = int32_t(t.len_grid.size());
+    view.row_grid = t.row_grid.data();
+    view.len_grid = t.len_grid.data();
+    view.cost = t.cost.data();
+    return &view;
+}
+
+size_t codec_plan_device_bytes(const codec_plan_t *plan)
+{
+    return plan ? plan->d.layout.total : 0;
+}
+
+int codec_plan_upload(codec_plan_t *plan, void *device_meta, size_t device_meta_bytes, void *stream)
+{
+    if (!plan || !device_meta) return CODEC_ERR_INVALID_ARGUMENT;
+    if (device_meta_bytes < plan->d.layout.total) return CODEC_ERR_WORKSPACE_TOO_SMALL;
+    if (reinterpret_cast<uintptr_t>(device_meta) & 255u) return CODEC_ERR_INVALID_ARGUMENT;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (hipMemcpyAsync(device_meta, plan->d.blob.data(), plan->d.layout.total, hipMemcpyHostToDevice, s) != hipSuccess)
+        return CODEC_ERR_HIP;
+    // the source is pageable host memory owned by the plan: wait so that it may be freed any time after
+    if (hipStreamSynchronize(s) != hipSuccess) return CODEC_ERR_HIP;
+    plan->device_meta = device_meta;
+    return CODEC_OK;
+}
+
+size_t codec_plan_workspace_bytes(const codec_plan_t *plan)
+{
+    if (!plan) return 0;
+    const size_t n = part_o_bytes(plan->d) + part_ml_bytes(plan->d);
+    return n ? n : 256;
+}
+
+int codec_decode_attention(const codec_plan_t *plan, const void *q, const void *k_pages,
+                           const void *v_pages, const codec_kv_layout *layout, void *out,
+                           void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (!plan || !layout) return CODEC_ERR_INVALID_ARGUMENT;
+    const codec::PlanData &d = plan->d;
+    if (d.num_requests == 0) return CODEC_OK;               // nothing to compute
+    if (!q || !k_pages || !v_pages || !out || !workspace) return CODEC_ERR_INVALID_ARGUMENT;
+    if (!plan->device_meta) return CODEC_ERR_NOT_UPLOADED;
+    if (workspace_bytes < codec_plan_workspace_bytes(plan)) return CODEC_ERR_WORKSPACE_TOO_SMALL;
+    if (!aligned16(q) || !aligned16(k_pages) || !aligned16(v_pages) || !aligned16(out)) return CODEC_ERR_INVALID_ARGUMENT;
+    if (reinterpret_cast<uintptr_t>(workspace) & 255u) return CODEC_ERR_INVALID_ARGUMENT;
+    if (layout->num_pages <= plan->max_page_id) return CODEC_ERR_INVALID_ARGUMENT;
+    if (layout->page_stride < 1 || layout->token_stride < 128 || layout->head_stride < 128 ||
+        layout->page_stride % 8 || layout->token_stride % 8 || layout->head_stride % 8)
+        return CODEC_ERR_INVALID_ARGUMENT;
+
+    const char *meta = static_cast<const char *>(plan->device_meta);
+    const codec::DevLayout &L = d.layout;
+    char *ws = static_cast<char *>(workspace);
+
+    codec::PacParams pp{};
+    pp.q = q;
+    pp.k_pages = k_pages;
+    pp.v_pages = v_pages;
+    pp.page_stride = layout->page_stride;
+    pp.token_stride = layout->token_stride;
+    pp.head_stride = layout->head_stride;
+    pp.tasks = reinterpret_cast<const codec::DevTask *>(meta + L.tasks);
+    pp.slot_off = reinterpret_cast<const int32_t *>(meta + L.slot_off);
+    pp.slot_tasks = reinterpret_cast<const int32_t *>(meta + L.slot_tasks);
+    pp.node_q = reinterpret_cast<const int32_t *>(meta + L.node_q);
+    pp.page_ids = reinterpret_cast<const int32_t *>(meta + L.page_ids);
+    pp.part_o = reinterpret_cast<float *>(ws);
+    pp.part_ml = reinterpret_cast<float *>(ws + part_o_bytes(d));
+    pp.h_q = d.head.num_q_heads;
+    pp.h_kv = d.head.num_kv_heads;
+    pp.group = d.group;
+    pp.page_size = d.head.page_size;
+    pp.part_rows = d.part_rows;
+    pp.scale_log2e = d.head.scale * 1.4426950408889634f;
+    if (codec::launch_pac(pp, d.head.dtype, d.num_slots, plan->max_task_rows, stream) != 0) return CODEC_ERR_HIP;
+
+    codec::MergeParams mp{};
+    mp.part_o = pp.part_o;
+    mp.part_ml = pp.part_ml;
+    mp.req_part_off = reinterpret_cast<const int32_t *>(meta + L.req_part_off);
+    mp.req_part = reinterpret_cast<const int32_t *>(meta + L.req_part);
+    mp.out = out;
+    mp.num_requests = d.num_requests;
+    mp.h_q = d.head.num_q_heads;
+    mp.group = d.group;
+    mp.part_rows = d.part_rows;
+    if (codec::launch_merge(mp, d.head.dtype, stream) != 0) return CODEC_ERR_HIP;
+    return CODEC_OK;
+}
+
+const char *codec_status_string(int status)
+{
+    switch (status) {
+    case CODEC_OK: return "ok";
+    case CODEC_ERR_INVALID_ARGUMENT: return "invalid argument";
+    case CODEC_ERR_INVALID_TREE: return "invalid tree";
+    case CODEC_ERR_UNSUPPORTED: return "unsupported configuration";
+    case CODEC_ERR_WORKSPACE_TOO_SMALL: return "buffer too small";
+    case CODEC_ERR_HIP: return "HIP runtime error";
+    case CODEC_ERR_NOT_UPLOADED: return "plan metadata not uploaded";
+    case CODEC_ERR_OUT_OF_MEMORY: return "out of host memory";
+    default: return "unknown status";
+    }
+}
+
+}  // extern "C"

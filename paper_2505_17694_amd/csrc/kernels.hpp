@@ -1,0 +1,40 @@
+// Launch interface of the gfx950 kernels (partial attention and partial-output reduction).
+#pragma once
+
+#include <cstdint>
+
+#include "planner.hpp"
+
+namespace codec {
+
+struct PacParams {
+    const void *q;                  // [B][h_q][128], 16-bit
+    const void *k_pages;
+    const void *v_pages;
+    int64_t page_stride, token_stride, head_stride;     // elements
+    const DevTask *tasks;
+    const int32_t *slot_off;
+    const int32_t *slot_tasks;
+    const int32_t *node_q;
+    const int32_t *page_ids;
+    float *part_o;                  // [h_kv][part_rows][128] unnormalised partial outputs
+    float *part_ml;                 // [h_kv][part_rows][2]   (max in log2 units, sum of exponentials)
+    int32_t h_q, h_kv, group, page_size, part_rows;
+    float scale_log2e;              // scale * log2(e): scores are kept in log2 units
+};
+
+struct MergeParams {
+    const float *part_o;
+    const float *part_ml;
+    const int32_t *req_part_off;
+    const int32_t *req_part;
+    void *out;                      // [B][h_q][128], 16-bit
+    int32_t num_requests, h_q, group, part_rows;
+};
+
+// Both return a hipError_t value (0 = success) without synchronising.
+// `max_rows_in_plan` selects the register-budget variant of the attention kernel.
+int launch_pac(const PacParams &p, int dtype, int num_slots, int max_rows_in_plan, void *stream);
+int launch_merge(const MergeParams &p, int dtype, void *stream);
+
+}  // namespace codec

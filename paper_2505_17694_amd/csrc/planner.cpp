@@ -1,0 +1,426 @@
+// Host-side workload balancer (paper Sec. 5).  See planner.hpp.
+//
+// The paper states the solver in prose (Sec. 5.1): fix b_q = 1, find a lower
+// bound cost_l of the makespan by binary search on the average-load inequality
+// (Eq. 4), bound every node's slice count by ceil(C_est / cost_l) (Eq. 5), grid
+// search the slice counts and schedule greedily.  Everything it leaves open is
+// fixed here in integers so that the result can be re-derived bit for bit:
+// integer costs, round-half-up bilinear interpolation, slices of equal length
+// on aligned boundaries, one grid-search pass in order of decreasing node cost
+// with ties to fewer slices, longest-first scheduling with ties to the lower
+// slot id.
+#include "planner.hpp"
+
+#include <algorithm>
+#include <cstring>
+#include <queue>
+
+namespace codec {
+
+namespace {
+
+inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
+
+// Position of x on an ascending grid: neighbours i0, i1 and the weight num/den of i1.
+struct Bracket {
+    int i0, i1;
+    int64_t num, den;
+};
+
+Bracket bracket(const std::vector<int32_t> &grid, int64_t x)
+{
+    const int k = static_cast<int>(grid.size());
+    if (k == 1 || x <= grid[0]) return {0, 0, 0, 1};            // clamp below the grid
+    if (x >= grid[k - 1])                                        // continue the last segment
+        return {k - 2, k - 1, x - grid[k - 2], int64_t(grid[k - 1]) - grid[k - 2]};
+    int i = static_cast<int>(std::upper_bound(grid.begin(), grid.end(), x) - grid.begin()) - 1;
+    return {i, i + 1, x - grid[i], int64_t(grid[i + 1]) - grid[i]};
+}
+
+// A KV slice layout: `count` slices of `length` tokens, the last one `last` tokens.
+struct Slicing {
+    int32_t count, length, last;
+};
+
+Slicing slice_node(int64_t len, int64_t want, int64_t align)
+{
+    const int64_t length = align * ceil_div(ceil_div(len, want), align);
+    const int64_t count = ceil_div(len, length);
+    return {int32_t(count), int32_t(length), int32_t(len - (count - 1) * length)};
+}
+
+struct Sub {
+    int64_t cost;
+    int32_t item, chunk, begin, len;
+};
+
+struct Schedule {
+    int64_t makespan = 0;
+    std::vector<int32_t> slot_of;                   // per subtask
+    std::vector<std::vector<int32_t>> lists;        // per slot, assignment order
+};
+
+// Longest-processing-time-first list scheduling onto m slots.
+void schedule_lpt(const std::vector<Sub> &sub, int m, bool keep_lists, Schedule &out)
+{
+    std::vector<int32_t> order(sub.size());
+    for (size_t i = 0; i < sub.size(); ++i) order[i] = int32_t(i);
+    std::sort(order.begin(), order.end(), [&](int32_t a, int32_t b) {
+        if (sub[a].cost != sub[b].cost) return sub[a].cost > sub[b].cost;
+        if (sub[a].item != sub[b].item) return sub[a].item < sub[b].item;
+        return sub[a].chunk < sub[b].chunk;
+    });
+    using Load = std::pair<int64_t, int32_t>;       // (load, slot): smallest load, then lowest slot
+    std::priority_queue<Load, std::vector<Load>, std::greater<Load>> heap;
+    for (int s = 0; s < m; ++s) heap.push({0, s});
+    if (keep_lists) {
+        out.slot_of.assign(sub.size(), 0);
+        out.lists.assign(m, {});
+    }
+    int64_t makespan = 0;
+    for (int32_t i : order) {
+        Load l = heap.top();
+        heap.pop();
+        l.first += sub[i].cost;
+        makespan = std::max(makespan, l.first);
+        if (keep_lists) {
+            out.slot_of[i] = l.second;
+            out.lists[l.second].push_back(i);
+        }
+        heap.push(l);
+    }
+    out.makespan = makespan;
+}
+
+size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+}  // namespace
+
+int CostTable::validate() const
+{
+    if (row_grid.empty() || len_grid.empty()) return CODEC_ERR_INVALID_ARGUMENT;
+    if (cost.size() != row_grid.size() * len_grid.size()) return CODEC_ERR_INVALID_ARGUMENT;
+    for (size_t i = 0; i < row_grid.size(); ++i)
+        if (row_grid[i] < 1 || (i && row_grid[i] <= row_grid[i - 1])) return CODEC_ERR_INVALID_ARGUMENT;
+    for (size_t i = 0; i < len_grid.size(); ++i)
+        if (len_grid[i] < 1 || (i && len_grid[i] <= len_grid[i - 1])) return CODEC_ERR_INVALID_ARGUMENT;
+    for (int64_t c : cost)
+        if (c < 1 || c > (int64_t(1) << 40)) return CODEC_ERR_INVALID_ARGUMENT;
+    return CODEC_OK;
+}
+
+int64_t CostTable::estimate(int64_t rows, int64_t len) const
+{
+    const Bracket r = bracket(row_grid, rows), n = bracket(len_grid, len);
+    const size_t nl = len_grid.size();
+    auto c = [&](int ri, int ni) { return static_cast<__int128>(cost[ri * nl + ni]); };
+    const __int128 wr1 = r.num, wr0 = r.den - r.num, wn1 = n.num, wn0 = n.den - n.num;
+    const __int128 num = wr0 * wn0 * c(r.i0, n.i0) + wr1 * wn0 * c(r.i1, n.i0)
+                       + wr0 * wn1 * c(r.i0, n.i1) + wr1 * wn1 * c(r.i1, n.i1);
+    const __int128 den = static_cast<__int128>(r.den) * n.den;
+    if (num <= 0) return 1;
+    const __int128 v = (num + den / 2) / den;
+    return v < 1 ? 1 : static_cast<int64_t>(v);
+}
+
+// Bootstrap table (ns per workgroup) from a bandwidth model of the streaming
+// kernel: setup + tokens * (46 + 0.3 rows) + 95 per partial row.  Replaced by a
+// measured table through codec_plan_options.cost.
+const CostTable &builtin_cost_table()
+{
+    static const CostTable t = {
+        {1, 16, 32, 64},
+        {32, 256, 1024, 4096, 16384, 65536},
+        {4576, 14947, 50506, 192739, 761674, 3037411,
+         6145, 17524, 56539, 212596, 836827, 3333748,
+         7819, 20273, 62974, 233777, 916990, 3649841,
+         11166, 25771, 75844, 276139, 1077316, 4282027}};
+    return t;
+}
+
+int build_plan(const codec_tree &tree, const codec_head_config &head,
+               const codec_plan_options &opt, PlanData &p)
+{
+    // ---- argument checks ------------------------------------------------------------
+    if (tree.num_nodes < 0 || tree.num_requests < 0) return CODEC_ERR_INVALID_ARGUMENT;
+    if (tree.num_requests > 0 && tree.num_nodes == 0) return CODEC_ERR_INVALID_TREE;
+    if (tree.num_nodes > 0 && (!tree.parent || !tree.node_len || !tree.node_page_off))
+        return CODEC_ERR_INVALID_ARGUMENT;
+    if (tree.num_requests > 0 && !tree.req_node) return CODEC_ERR_INVALID_ARGUMENT;
+    if (head.num_q_heads < 1 || head.num_kv_heads < 1) return CODEC_ERR_INVALID_ARGUMENT;
+    if (head.num_q_heads % head.num_kv_heads != 0) return CODEC_ERR_INVALID_ARGUMENT;
+    if (head.head_dim != 128) return CODEC_ERR_UNSUPPORTED;
+    if (head.dtype != CODEC_DTYPE_FP16 && head.dtype != CODEC_DTYPE_BF16) return CODEC_ERR_UNSUPPORTED;
+    if (head.page_size < 16 || head.page_size % 16 != 0) return CODEC_ERR_UNSUPPORTED;
+    if (!(head.scale > 0.0f) || !(head.scale < 1e30f)) return CODEC_ERR_INVALID_ARGUMENT;
+    const int32_t group = head.num_q_heads / head.num_kv_heads;
+    if (group > 64) return CODEC_ERR_UNSUPPORTED;
+
+    const int32_t m = opt.num_slots > 0 ? opt.num_slots : std::max(1, 512 / head.num_kv_heads);
+    const int32_t align = opt.split_align > 0 ? opt.split_align : std::max(256, head.page_size);
+    const int32_t max_rows = opt.max_rows > 0 ? opt.max_rows : 64;
+    if (opt.num_slots < 0 || opt.split_align < 0 || opt.max_rows < 0) return CODEC_ERR_INVALID_ARGUMENT;
+    if (m > (1 << 20)) return CODEC_ERR_INVALID_ARGUMENT;
+    if (align % 32 != 0 || align % head.page_size != 0) return CODEC_ERR_INVALID_ARGUMENT;
+    if (max_rows > 64 || max_rows < group) return CODEC_ERR_INVALID_ARGUMENT;
+    if (opt.share != 0 && opt.share != 1) return CODEC_ERR_INVALID_ARGUMENT;
+
+    CostTable user;
+    const CostTable *table = &builtin_cost_table();
+    if (opt.cost) {
+        const codec_cost_table &c = *opt.cost;
+        if (c.num_row_points < 1 || c.num_len_points < 1 || !c.row_grid || !c.len_grid || !c.cost)
+            return CODEC_ERR_INVALID_ARGUMENT;
+        user.row_grid.assign(c.row_grid, c.row_grid + c.num_row_points);
+        user.len_grid.assign(c.len_grid, c.len_grid + c.num_len_points);
+        user.cost.assign(c.cost, c.cost + size_t(c.num_row_points) * c.num_len_points);
+        if (int st = user.validate()) return st;
+        table = &user;
+    }
+
+    const int32_t N = tree.num_nodes, B = tree.num_requests;
+
+    // ---- forest checks --------------------------------------------------------------
+    for (int32_t i = 0; i < N; ++i) {
+        if (tree.parent[i] < -1 || tree.parent[i] >= N || tree.parent[i] == i) return CODEC_ERR_INVALID_TREE;
+        if (tree.node_len[i] < 1) return CODEC_ERR_INVALID_TREE;
+    }
+    {   // cycles anywhere in the parent array: colour walk (0 new, 1 on the current walk, 2 cleared)
+        std::vector<uint8_t> colour(N, 0);
+        std::vector<int32_t> walk;
+        for (int32_t s = 0; s < N; ++s) {
+            walk.clear();
+            int32_t n = s;
+            while (n != -1 && colour[n] == 0) {
+                colour[n] = 1;
+                walk.push_back(n);
+                n = tree.parent[n];
+            }
+            if (n != -1 && colour[n] == 1) return CODEC_ERR_INVALID_TREE;
+            for (int32_t v : walk) colour[v] = 2;
+        }
+    }
+    if (N > 0) {
+        if (tree.node_page_off[0] < 0) return CODEC_ERR_INVALID_TREE;
+        for (int32_t i = 0; i < N; ++i) {
+            const int64_t have = int64_t(tree.node_page_off[i + 1]) - tree.node_page_off[i];
+            if (have < ceil_div(tree.node_len[i], head.page_size)) return CODEC_ERR_INVALID_TREE;
+        }
+        if (tree.node_page_off[N] > 0 && !tree.page_ids) return CODEC_ERR_INVALID_ARGUMENT;
+        for (int32_t i = tree.node_page_off[0]; i < tree.node_page_off[N]; ++i)
+            if (tree.page_ids[i] < 0) return CODEC_ERR_INVALID_TREE;
+    }
+    for (int32_t r = 0; r < B; ++r)
+        if (tree.req_node[r] < 0 || tree.req_node[r] >= N) return CODEC_ERR_INVALID_TREE;
+
+    p.head = head;
+    p.group = group;
+    p.num_slots = m;
+    p.split_align = align;
+    p.max_rows = max_rows;
+    p.share = opt.share;
+    p.num_nodes = N;
+    p.num_requests = B;
+    p.node_len.assign(tree.node_len, tree.node_len + N);
+    p.node_page_off.assign(tree.node_page_off, tree.node_page_off + (N ? N + 1 : 0));
+    if (N) p.page_ids.assign(tree.page_ids, tree.page_ids + tree.node_page_off[N]);
+
+    // ---- a1: prefix paths and per-node query sets (Sec. 4.1) ------------------------------
+    std::vector<std::vector<int32_t>> paths(B);
+    std::vector<int32_t> n_q(N, 0);
+    for (int32_t r = 0; r < B; ++r) {
+        for (int32_t n = tree.req_node[r]; n != -1; n = tree.parent[n]) paths[r].push_back(n);
+        std::reverse(paths[r].begin(), paths[r].end());
+        for (int32_t n : paths[r]) ++n_q[n];
+    }
+    p.node_q_off.assign(N + 1, 0);
+    for (int32_t i = 0; i < N; ++i) p.node_q_off[i + 1] = p.node_q_off[i] + n_q[i];
+    p.node_q.assign(p.node_q_off[N], 0);
+    {
+        std::vector<int32_t> fill(p.node_q_off.begin(), p.node_q_off.end() - 1);
+        for (int32_t r = 0; r < B; ++r)           // ascending r keeps every list sorted
+            for (int32_t n : paths[r]) p.node_q[fill[n]++] = r;
+    }
+
+    // ---- work items: a node with (a row tile of) its queries -------------------------------
+    const int32_t qpt = p.share ? std::max(1, max_rows / group) : 1;
+    std::vector<int32_t> first_item(N, 0);
+    for (int32_t n = 0; n < N; ++n) {
+        first_item[n] = int32_t(p.items.size());
+        for (int32_t a = 0; a < n_q[n]; a += qpt) {
+            codec_item it{};
+            it.node = n;
+            it.q_off = p.node_q_off[n] + a;
+            it.n_req = std::min(qpt, n_q[n] - a);
+            it.rows = it.n_req * group;
+            it.len = p.node_len[n];
+            it.cost = table->estimate(it.rows, it.len);       // a2: Eq. 6
+            p.items.push_back(it);
+        }
+    }
+    const size_t J = p.items.size();
+    std::vector<int64_t> max_b(J);
+    for (size_t j = 0; j < J; ++j) max_b[j] = ceil_div(p.items[j].len, align);
+
+    auto slices_at = [&](size_t j, int64_t T) {
+        return std::min(ceil_div(p.items[j].cost, T), max_b[j]);
+    };
+    auto division_cost = [&](size_t j, int64_t want) {
+        const Slicing s = slice_node(p.items[j].len, want, align);
+        return int64_t(s.count - 1) * table->estimate(p.items[j].rows, s.length)
+               + table->estimate(p.items[j].rows, s.last);
+    };
+
+    // ---- a3: lower bound cost_l (Eq. 4) by binary search, upper bounds (Eq. 5) ----------------
+    p.cost_l = 0;
+    if (J) {
+        int64_t biggest = 0, sum = 0;
+        for (const codec_item &it : p.items) {
+            biggest = std::max(biggest, it.cost);
+            sum += it.cost;
+        }
+        int64_t lo = 1, hi = std::max(biggest, ceil_div(sum, m));
+        while (lo < hi) {
+            const int64_t mid = lo + (hi - lo) / 2;
+            __int128 total = 0;
+            for (size_t j = 0; j < J; ++j) total += division_cost(j, slices_at(j, mid));
+            if (total <= static_cast<__int128>(m) * mid) hi = mid; else lo = mid + 1;
+        }
+        p.cost_l = lo;
+    }
+    for (size_t j = 0; j < J; ++j) {
+        p.items[j].ub = slice_node(p.items[j].len, slices_at(j, p.cost_l), align).count;
+        p.items[j].b = p.items[j].ub;
+    }
+
+    // ---- grid search over slice counts, evaluated by the greedy schedule ---------------------
+    std::vector<Sub> sub;
+    auto expand = [&]() {
+        sub.clear();
+        for (size_t j = 0; j < J; ++j) {
+            const codec_item &it = p.items[j];
+            const Slicing s = slice_node(it.len, it.b, align);
+            const int64_t c_full = s.count > 1 ? table->estimate(it.rows, s.length) : 0;
+            const int64_t c_last = table->estimate(it.rows, s.last);
+            for (int32_t c = 0; c < s.count; ++c) {
+                const bool last = c == s.count - 1;
+                sub.push_back({last ? c_last : c_full, int32_t(j), c, c * s.length, last ? s.last : s.length});
+            }
+        }
+    };
+    {
+        std::vector<int32_t> order;
+        for (size_t j = 0; j < J; ++j)
+            if (p.items[j].ub > 1) order.push_back(int32_t(j));
+        std::sort(order.begin(), order.end(), [&](int32_t a, int32_t b) {
+            if (p.items[a].cost != p.items[b].cost) return p.items[a].cost > p.items[b].cost;
+            return a < b;
+        });
+        Schedule trial;
+        for (int32_t j : order) {
+            codec_item &it = p.items[j];
+            int32_t best_b = 0, prev = 0;
+            int64_t best_ms = 0;
+            for (int32_t want = 1; want <= it.ub; ++want) {
+                const int32_t count = slice_node(it.len, want, align).count;
+                if (count == prev) continue;            // counts are non-decreasing in `want`
+                prev = count;
+                it.b = count;
+                expand();
+                schedule_lpt(sub, m, false, trial);
+                if (best_b == 0 || trial.makespan < best_ms) {
+                    best_b = count;
+                    best_ms = trial.makespan;
+                }
+            }
+            it.b = best_b;
+        }
+    }
+
+    // ---- a4: final schedule and emission --------------------------------------------------------
+    expand();
+    Schedule fin;
+    schedule_lpt(sub, m, true, fin);
+    p.makespan = fin.makespan;
+
+    std::vector<int32_t> first_task(J, 0);
+    p.tasks.resize(sub.size());
+    int64_t base = 0;
+    for (size_t i = 0; i < sub.size(); ++i) {
+        const codec_item &it = p.items[sub[i].item];
+        if (sub[i].chunk == 0) first_task[sub[i].item] = int32_t(i);
+        codec_task &t = p.tasks[i];
+        t.item = sub[i].item;
+        t.node = it.node;
+        t.kv_begin = sub[i].begin;
+        t.kv_len = sub[i].len;
+        t.q_off = it.q_off;
+        t.n_req = it.n_req;
+        t.part_row_base = int32_t(base);
+        t.slot = fin.slot_of[i];
+        t.cost = sub[i].cost;
+        base += it.rows;
+        if (base > INT32_MAX) return CODEC_ERR_UNSUPPORTED;
+    }
+    p.part_rows = int32_t(base);
+
+    p.slot_off.assign(m + 1, 0);
+    p.slot_tasks.clear();
+    for (int32_t s = 0; s < m; ++s) {
+        p.slot_tasks.insert(p.slot_tasks.end(), fin.lists[s].begin(), fin.lists[s].end());
+        p.slot_off[s + 1] = int32_t(p.slot_tasks.size());
+    }
+
+    // per-request partial lists: path order, slices in order (Sec. 4.1 "Indexing of partial results")
+    p.req_part_off.assign(B + 1, 0);
+    p.req_part.clear();
+    for (int32_t r = 0; r < B; ++r) {
+        for (int32_t n : paths[r]) {
+            const int32_t *lo = p.node_q.data() + p.node_q_off[n];
+            const int32_t *hi = p.node_q.data() + p.node_q_off[n + 1];
+            const int32_t qi = int32_t(std::lower_bound(lo, hi, r) - lo);
+            const int32_t j = first_item[n] + qi / qpt;
+            for (int32_t c = 0; c < p.items[j].b; ++c)
+                p.req_part.push_back(p.tasks[first_task[j] + c].part_row_base + (qi % qpt) * group);
+        }
+        p.req_part_off[r + 1] = int32_t(p.req_part.size());
+    }
+
+    // ---- device image ------------------------------------------------------------------------------
+    const int32_t ps = head.page_size;
+    DevLayout &L = p.layout;
+    size_t off = 0;
+    auto place = [&](size_t bytes) { size_t at = off; off = align_up(off + bytes, 256); return at; };
+    L.tasks = place(p.tasks.size() * sizeof(DevTask));
+    L.slot_off = place(p.slot_off.size() * 4);
+    L.slot_tasks = place(p.slot_tasks.size() * 4);
+    L.node_q = place(p.node_q.size() * 4);
+    L.page_ids = place(p.page_ids.size() * 4);
+    L.req_part_off = place(p.req_part_off.size() * 4);
+    L.req_part = place(p.req_part.size() * 4);
+    L.total = std::max<size_t>(off, 256);
+    p.blob.assign(L.total, 0);
+    {
+        DevTask *dt = reinterpret_cast<DevTask *>(p.blob.data() + L.tasks);
+        for (size_t i = 0; i < p.tasks.size(); ++i) {
+            const codec_task &t = p.tasks[i];
+            dt[i].page_off = p.node_page_off[t.node] + t.kv_begin / ps;
+            dt[i].kv_len = t.kv_len;
+            dt[i].q_off = t.q_off;
+            dt[i].n_req = t.n_req;
+            dt[i].part_row_base = t.part_row_base;
+        }
+        auto put = [&](size_t at, const std::vector<int32_t> &v) {
+            if (!v.empty()) std::memcpy(p.blob.data() + at, v.data(), v.size() * 4);
+        };
+        put(L.slot_off, p.slot_off);
+        put(L.slot_tasks, p.slot_tasks);
+        put(L.node_q, p.node_q);
+        put(L.page_ids, p.page_ids);
+        put(L.req_part_off, p.req_part_off);
+        put(L.req_part, p.req_part);
+    }
+    return CODEC_OK;
+}
+
+}  // namespace codec

@@ -1,0 +1,63 @@
+// Host-side workload balancer: forest indexing, cost estimation, KV division and
+// slot scheduling (paper Sec. 4.1 indexes, Sec. 5 Eq. 3-7).  Pure C++, no HIP.
+#pragma once
+
+#include <cstdint>
+#include <vector>
+
+#include "codec.h"
+
+namespace codec {
+
+// Profiled cost table with integer bilinear interpolation (Sec. 5.2, Eq. 6).
+struct CostTable {
+    std::vector<int32_t> row_grid;
+    std::vector<int32_t> len_grid;
+    std::vector<int64_t> cost;          // [row][len]
+
+    int validate() const;
+    int64_t estimate(int64_t rows, int64_t len) const;
+};
+
+// Task record as the kernels read it (32 bytes).
+struct DevTask {
+    int32_t page_off;       // index into the device copy of page_ids of the slice's first page
+    int32_t kv_len;         // tokens in the slice
+    int32_t q_off;          // first request of the task in node_q
+    int32_t n_req;          // requests in the task
+    int32_t part_row_base;  // first partial row
+    int32_t reserved[3];
+};
+
+// Byte offsets of the arrays inside the device metadata blob.
+struct DevLayout {
+    size_t tasks = 0, slot_off = 0, slot_tasks = 0, node_q = 0, page_ids = 0,
+           req_part_off = 0, req_part = 0, total = 0;
+};
+
+struct PlanData {
+    codec_head_config head{};
+    int32_t group = 1;
+    int32_t num_slots = 0, split_align = 0, max_rows = 0, share = 1;
+    int32_t num_nodes = 0, num_requests = 0;
+
+    std::vector<int32_t> node_len, node_page_off, page_ids;
+    std::vector<int32_t> node_q_off, node_q;
+    std::vector<codec_item> items;
+    std::vector<codec_task> tasks;
+    std::vector<int32_t> slot_off, slot_tasks;
+    std::vector<int32_t> req_part_off, req_part;
+    int64_t cost_l = 0, makespan = 0;
+    int32_t part_rows = 0;
+
+    DevLayout layout;
+    std::vector<unsigned char> blob;    // host image of the device metadata
+};
+
+const CostTable &builtin_cost_table();
+
+// Fills `plan` from the caller's forest; returns a CODEC_* status.
+int build_plan(const codec_tree &tree, const codec_head_config &head,
+               const codec_plan_options &opt, PlanData &plan);
+
+}  // namespace codec

@@ -1,0 +1,72 @@
+"""Thin holder of a plan and the PyTorch tensors that back it (marshalling only)."""
+from __future__ import annotations
+
+import torch
+
+from . import binding as B
+
+
+class PlannedAttention:
+    """Owns a codec plan plus its device metadata and workspace tensors.
+
+    ``forest``/``paged``/``head`` are plain attribute bags (see ``workloads``):
+    forest.parent, forest.node_len, forest.req_node; paged.node_page_off,
+    paged.page_ids, paged.num_pages and the three strides; head.num_q_heads,
+    num_kv_heads, head_dim, dtype, page_size, scale.
+    """
+
+    def __init__(self, forest, paged, head, device="cuda:0", num_slots=0, split_align=0,
+                 max_rows=0, share=1, cost_table=None):
+        st, plan = B.codec_plan_create(forest.parent, forest.node_len, forest.req_node,
+                                       paged.node_page_off, paged.page_ids,
+                                       head.num_q_heads, head.num_kv_heads, head.head_dim,
+                                       head.dtype, head.page_size, head.scale,
+                                       num_slots, split_align, max_rows, share, cost_table)
+        if st != B.CODEC_OK:
+            raise B.CodecError(st, "codec_plan_create")
+        self.plan = plan
+        self.paged = paged
+        self.head = head
+        self.device = torch.device(device)
+        self.num_requests = len(forest.req_node)
+        self.meta = None
+        self.workspace = None
+        if self.device.type == "cuda":
+            self.meta = torch.empty(B.codec_plan_device_bytes(plan), dtype=torch.uint8, device=self.device)
+            stream = torch.cuda.current_stream(self.device).cuda_stream
+            st = B.codec_plan_upload(plan, self.meta.data_ptr(), self.meta.numel(), stream)
+            if st != B.CODEC_OK:
+                raise B.CodecError(st, "codec_plan_upload")
+            self.workspace = torch.empty(B.codec_plan_workspace_bytes(plan), dtype=torch.uint8,
+                                         device=self.device)
+
+    def export(self):
+        st, view = B.codec_plan_export(self.plan)
+        if st != B.CODEC_OK:
+            raise B.CodecError(st, "codec_plan_export")
+        return view
+
+    def decode(self, q: torch.Tensor, k_pool: torch.Tensor, v_pool: torch.Tensor,
+               out: torch.Tensor = None, stream=None) -> torch.Tensor:
+        if out is None:
+            out = torch.empty_like(q)
+        s = (stream or torch.cuda.current_stream(self.device)).cuda_stream
+        p = self.paged
+        st = B.codec_decode_attention(self.plan, q.data_ptr(), k_pool.data_ptr(), v_pool.data_ptr(),
+                                      p.num_pages, p.page_stride, p.token_stride, p.head_stride,
+                                      out.data_ptr(), self.workspace.data_ptr(),
+                                      self.workspace.numel(), s)
+        if st != B.CODEC_OK:
+            raise B.CodecError(st, "codec_decode_attention")
+        return out
+
+    def close(self):
+        if self.plan is not None:
+            B.codec_plan_destroy(self.plan)
+            self.plan = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass

@@ -1,0 +1,222 @@
+"""GPU parity: the HIP path through the C ABI against the fp64 definition oracle.
+
+Bar (both sides on the same 16-bit-rounded inputs): max |out - oracle| <= 1e-2,
+the bound the build is held to for fp16/bf16 I/O with fp32 accumulation.  A
+tighter mixed bar (2e-3 + 2^-7 |oracle|) is asserted as well; it is what the
+arithmetic supports: P is rounded to 16 bits before the second product and the
+output is rounded once to 16 bits (relative 2^-9 for bf16), everything else is
+fp32.
+"""
+import numpy as np
+import pytest
+import torch
+
+from oracle import attention as A
+from workloads import (HeadConfig, Forest, make_workload, make_small_config, make_config,
+                       two_level_forest, three_level_forest, unshared_forest, random_forest,
+                       concat_forests, degenerate_forest, DTYPE_FP16, DTYPE_BF16)
+
+pytestmark = pytest.mark.gpu
+
+TOL = 1e-2
+
+
+def _C():
+    import paper_2505_17694_amd as C
+    return C
+
+
+def run_gpu(w, share=1, **opts):
+    C = _C()
+    wd = w.to("cuda:0")
+    pa = C.PlannedAttention(w.forest, w.paged, w.head, device="cuda:0", share=share, **opts)
+    out = pa.decode(wd.q, wd.k_pool, wd.v_pool)
+    torch.cuda.synchronize()
+    res = out.to(torch.float64).cpu().numpy()
+    view = pa.export()
+    pa.close()
+    return res, view
+
+
+def check(w, share=1, sel=None, **opts):
+    print(f"[case] {w.name} share={share} opts={opts} B={w.forest.num_requests} "
+          f"nodes={w.forest.num_nodes} heads={w.head.num_q_heads}/{w.head.num_kv_heads}", flush=True)
+    got, view = run_gpu(w, share, **opts)
+    if sel is None:
+        ref, _ = A.decode_attention_workload(w)
+        g = got
+    else:
+        ref, _ = A.decode_attention_workload(w, sel=sel)
+        g = np.stack([got[r, h] for r, h in sel])
+    assert not np.any(np.isnan(g)), "NaN in the output (a masked position leaked?)"
+    err = np.abs(g - ref)
+    assert err.max() <= TOL, f"max abs err {err.max():.3e}"
+    assert np.all(err <= 2e-3 + 2.0 ** -7 * np.abs(ref)), f"mixed bar: worst {err.max():.3e}"
+    return got, view
+
+
+@pytest.mark.parametrize("name,shrink,req_shrink", [
+    ("cfg1", 4, 1), ("cfg2", 8, 2), ("cfg3", 16, 2), ("cfg4", 8, 8),
+    ("cfg5a", 64, 4), ("cfg5b", 64, 8), ("cfg5c", 64, 8)])
+@pytest.mark.parametrize("share", [1, 0])
+def test_shrunken_configurations(name, shrink, req_shrink, share):
+    w = make_small_config(name, shrink, req_shrink, poison=True)
+    check(w, share=share)
+
+
+@pytest.mark.parametrize("lens", [[1], [15], [16], [17], [31], [32], [33], [63, 64, 65], [127, 129, 1, 2]])
+@pytest.mark.parametrize("dtype", [DTYPE_FP16, DTYPE_BF16])
+def test_ragged_single_nodes(lens, dtype):
+    """Lengths around the 16-token tile and the 32-token block; waves that get no block at all."""
+    w = make_workload(f"ragged{lens}", unshared_forest(lens), HeadConfig(8, 2, 128, dtype), seed=5, poison=True)
+    check(w)
+
+
+@pytest.mark.parametrize("hq,hkv", [(8, 8), (4, 1), (28, 4), (16, 2), (64, 1)])
+def test_head_layouts(hq, hkv):
+    """MHA, MQA and GQA groups 7, 8 and 64 (rows per request not a divisor of the 16-row tile)."""
+    f = three_level_forest(70, [130, 45], 3, [5, 33, 64, 1, 17, 48])
+    w = make_workload(f"heads{hq}/{hkv}", f, HeadConfig(hq, hkv, 128, DTYPE_BF16), seed=8, poison=True)
+    check(w)
+    check(w, share=0)
+
+
+@pytest.mark.parametrize("max_rows", [8, 16, 32, 48, 64])
+def test_row_tiles(max_rows):
+    """40 requests x group 4 = 160 rows under the root: 1-, 2- and 4-tile register variants, row tiling."""
+    f = two_level_forest(300, [7 + (i % 5) for i in range(40)])
+    w = make_workload(f"rows{max_rows}", f, HeadConfig(16, 4, 128, DTYPE_BF16), seed=12, poison=True)
+    _, view = check(w, max_rows=max_rows)
+    assert max(t["n_req"] * 4 for t in view["tasks"]) <= max_rows
+
+
+@pytest.mark.parametrize("slots,align", [(1, 32), (7, 32), (64, 32), (64, 64), (256, 32)])
+def test_division_granularity(slots, align):
+    """From everything on one slot to slices of a single block: merged result must not change."""
+    f = concat_forests(two_level_forest(2100, [40, 90, 33]), unshared_forest([700, 31]))
+    w = make_workload(f"div{slots}/{align}", f, HeadConfig(8, 2, 128, DTYPE_FP16), seed=3, poison=True)
+    _, view = check(w, num_slots=slots, split_align=align)
+    if slots >= 64:
+        assert max(it["b"] for it in view["items"]) > 4
+
+
+@pytest.mark.parametrize("layout,page_size", [("htd", 16), ("thd", 32), ("htd", 64), ("thd", 128)])
+def test_layouts_and_page_sizes(layout, page_size):
+    f = three_level_forest(200, [333, 90], 2, [5, 70, 130, 17])
+    head = HeadConfig(8, 2, 128, DTYPE_BF16, page_size=page_size)
+    w = make_workload(f"{layout}{page_size}", f, head, seed=21, poison=True, layout=layout)
+    check(w, split_align=max(32, page_size), num_slots=16)
+
+
+def test_irregular_forest_with_internal_requests():
+    f = random_forest(48, 5, 2.0, 100, 1.0, 1, 3000, seed=17)
+    inner = [int(f.parent[n]) for n in f.req_node[:6] if f.parent[n] >= 0]
+    f = Forest(f.parent, f.node_len, np.concatenate([f.req_node, np.array(inner, dtype=np.int32)]))
+    w = make_workload("irregular", f, HeadConfig(32, 8, 128, DTYPE_BF16), seed=4, poison=True)
+    check(w, num_slots=16, split_align=32)
+    check(w, share=0, num_slots=16, split_align=32)
+
+
+def test_degenerate_tree():
+    w = make_workload("spine", degenerate_forest(6, 500, 60), HeadConfig(8, 2, 128, DTYPE_FP16), seed=2, poison=True)
+    check(w, num_slots=8, split_align=32)
+
+
+def test_large_logits_and_peaked_softmax():
+    """Q scaled by 8: logits of order +-90, outputs of order 1; LSE merging must stay stable."""
+    f = two_level_forest(1500, [64, 200, 31, 7])
+    w = make_workload("stress", f, HeadConfig(8, 2, 128, DTYPE_BF16), seed=9, poison=True, q_scale=8.0)
+    got, _ = check(w, num_slots=32, split_align=32)
+    assert np.abs(got).max() > 0.5
+
+
+def test_request_order_permutation_is_equivariant():
+    f = two_level_forest(600, [33, 70, 5, 128, 90])
+    w = make_workload("perm", f, HeadConfig(8, 2, 128, DTYPE_BF16), seed=13)
+    base, _ = run_gpu(w, num_slots=8, split_align=32)
+    perm = np.array([3, 0, 4, 1, 2])
+    f2 = Forest(f.parent, f.node_len, f.req_node[perm])
+    w2 = make_workload("perm2", f2, w.head, seed=13, paged=w.paged)
+    w2.q[:] = w.q[torch.from_numpy(perm)]
+    w2.k_pool[:] = w.k_pool
+    w2.v_pool[:] = w.v_pool
+    got, _ = check(w2, num_slots=8, split_align=32)
+    # same tasks on the shared root up to row order; each request's own rows see identical arithmetic
+    assert np.max(np.abs(got - base[perm])) <= 2.0 ** -7 * np.abs(base).max()
+
+
+def test_same_plan_decodes_repeatedly_and_with_new_queries():
+    C = _C()
+    w = make_small_config("cfg2", 8, 2, poison=True)
+    wd = w.to("cuda:0")
+    pa = C.PlannedAttention(w.forest, w.paged, w.head, device="cuda:0")
+    a = pa.decode(wd.q, wd.k_pool, wd.v_pool).clone()
+    b = pa.decode(wd.q, wd.k_pool, wd.v_pool).clone()
+    torch.cuda.synchronize()
+    assert torch.equal(a.view(torch.int16), b.view(torch.int16))      # bit-identical replays
+    w.q[:] = torch.randn(w.q.shape, generator=torch.Generator().manual_seed(5)).to(w.q.dtype)
+    out = pa.decode(w.q.to("cuda:0"), wd.k_pool, wd.v_pool)
+    torch.cuda.synchronize()
+    ref, _ = A.decode_attention_workload(w)
+    assert np.max(np.abs(out.double().cpu().numpy() - ref)) <= TOL
+    pa.close()
+
+
+def test_tree_equals_flat_on_the_gpu():
+    w = make_small_config("cfg3", 16, 2, poison=True)
+    tree, _ = run_gpu(w, share=1)
+    flat, _ = run_gpu(w, share=0)
+    assert np.max(np.abs(tree - flat)) <= TOL
+
+
+def test_error_paths_on_the_device_side():
+    C = _C()
+    w = make_small_config("cfg1", 4, 1)
+    wd = w.to("cuda:0")
+    pa = C.PlannedAttention(w.forest, w.paged, w.head, device="cuda:0")
+    p = w.paged
+    out = torch.empty_like(wd.q)
+    args = (wd.q.data_ptr(), wd.k_pool.data_ptr(), wd.v_pool.data_ptr())
+    ws = pa.workspace
+    # pool smaller than the largest page id, workspace too small, misaligned query pointer
+    assert C.codec_decode_attention(pa.plan, *args, 3, p.page_stride, p.token_stride, p.head_stride,
+                                    out.data_ptr(), ws.data_ptr(), ws.numel()) == C.CODEC_ERR_INVALID_ARGUMENT
+    assert C.codec_decode_attention(pa.plan, *args, p.num_pages, p.page_stride, p.token_stride, p.head_stride,
+                                    out.data_ptr(), ws.data_ptr(), 16) == C.CODEC_ERR_WORKSPACE_TOO_SMALL
+    assert C.codec_decode_attention(pa.plan, args[0] + 2, args[1], args[2], p.num_pages, p.page_stride,
+                                    p.token_stride, p.head_stride, out.data_ptr(), ws.data_ptr(),
+                                    ws.numel()) == C.CODEC_ERR_INVALID_ARGUMENT
+    pa.close()
+
+
+# ---- full-size configurations, in the launch configuration the benchmark times -------------------
+
+def _sample_pairs(w, n, seed):
+    rng = np.random.Generator(np.random.PCG64(seed))
+    B, H = w.forest.num_requests, w.head.num_q_heads
+    idx = rng.choice(B * H, size=min(n, B * H), replace=False)
+    return [(int(i // H), int(i % H)) for i in idx]
+
+
+@pytest.mark.parametrize("name,n_pairs", [("cfg1", 10 ** 9), ("cfg2", 10 ** 9), ("cfg3", 1024),
+                                          ("cfg4", 1024), ("cfg5a", 96), ("cfg5b", 96), ("cfg5c", 96)])
+def test_full_size_configurations_on_sampled_outputs(name, n_pairs):
+    """Inputs are generated on the GPU, copied back for the oracle; sampled (request, head) pairs."""
+    w = make_config(name, device="cuda:0")
+    C = _C()
+    print(f"[case] full {name} unique_kv_bytes={w.unique_kv_bytes}", flush=True)
+    sel = _sample_pairs(w, n_pairs, seed=77)
+    for share in (1, 0):
+        pa = C.PlannedAttention(w.forest, w.paged, w.head, device="cuda:0", share=share)
+        out = pa.decode(w.q, w.k_pool, w.v_pool)
+        torch.cuda.synchronize()
+        got = out.to(torch.float64).cpu().numpy()
+        pa.close()
+        if share == 1:
+            ref, _ = A.decode_attention_workload(w, sel=sel)
+        g = np.stack([got[r, h] for r, h in sel])
+        err = np.abs(g - ref)
+        print(f"[case] full {name} share={share} max_err={err.max():.3e}", flush=True)
+        assert not np.any(np.isnan(got))
+        assert err.max() <= TOL
+        assert np.all(err <= 2e-3 + 2.0 ** -7 * np.abs(ref))

@@ -1,0 +1,108 @@
+"""The library's planner (C++) against the independent integer re-derivation, bit for bit.
+
+The paper gives the solver in prose (Sec. 5); the exact plan is therefore
+pinned only by the two implementations agreeing, while the oracle itself is
+pinned to the paper in test_planner_oracle.py.
+"""
+import random
+
+import numpy as np
+import pytest
+
+import paper_2505_17694_amd as C
+from oracle import planner as P
+from golden_tables import load_table2
+from workloads import (two_level_forest, three_level_forest, random_forest, unshared_forest,
+                       concat_forests, degenerate_forest, full_kary_forest, Forest, HeadConfig,
+                       build_paged_kv)
+from workloads.configs import config_forest, config_head, CONFIG_NAMES
+
+TABLE2 = load_table2()
+
+
+def _tuple(t):
+    return (t["row_grid"], t["len_grid"], t["cost"])
+
+
+def _default_table():
+    rg, lg, c = C.codec_default_cost_table()
+    return {"row_grid": rg, "len_grid": lg, "cost": c}
+
+
+def _lib_plan(f, head, m, align, max_rows, share, table):
+    paged = build_paged_kv(f, head, seed=1)
+    st, plan = C.codec_plan_create(f.parent, f.node_len, f.req_node, paged.node_page_off, paged.page_ids,
+                                   head.num_q_heads, head.num_kv_heads, head.head_dim, head.dtype,
+                                   head.page_size, head.scale, m, align, max_rows, int(share),
+                                   _tuple(table) if table is not None else None)
+    assert st == C.CODEC_OK, C.codec_status_string(st)
+    st, view = C.codec_plan_export(plan)
+    assert st == C.CODEC_OK
+    C.codec_plan_destroy(plan)
+    return view
+
+
+def _compare(view, ref):
+    assert view["cost_l"] == ref["cost_l"]
+    assert view["makespan"] == ref["makespan"]
+    assert view["part_rows"] == ref["part_rows"]
+    assert len(view["items"]) == len(ref["items"])
+    for a, b in zip(view["items"], ref["items"]):
+        for k in ("node", "q_off", "n_req", "rows", "len", "ub", "b", "cost"):
+            assert a[k] == b[k], (k, a, b)
+    assert len(view["tasks"]) == len(ref["tasks"])
+    for a, b in zip(view["tasks"], ref["tasks"]):
+        for k in ("item", "node", "kv_begin", "kv_len", "q_off", "n_req", "part_row_base", "slot", "cost"):
+            assert a[k] == b[k], (k, a, b)
+    for k in ("slot_off", "slot_tasks", "node_q_off", "node_q", "req_part_off", "req_part"):
+        assert list(view[k]) == list(ref[k]), k
+
+
+def test_cost_estimate_matches_oracle_everywhere():
+    rng = random.Random(3)
+    for table in (TABLE2, _default_table(),
+                  {"row_grid": [1, 3], "len_grid": [10, 20], "cost": [[10, 20], [30, 42]]},
+                  {"row_grid": [4], "len_grid": [8], "cost": [[7]]}):
+        for _ in range(400):
+            r, n = rng.randint(1, 300), rng.choice([rng.randint(1, 600), rng.randint(1, 200000)])
+            assert C.codec_cost_estimate(_tuple(table), r, n) == P.c_est(table, r, n)
+    assert C.codec_cost_estimate(None, 16, 256) == P.c_est(_default_table(), 16, 256)
+    # the paper's Table 2 at its own grid points through the C ABI
+    assert C.codec_cost_estimate(_tuple(TABLE2), 10, 4096) == 126
+    assert C.codec_cost_estimate(_tuple(TABLE2), 100, 16384) == 746
+
+
+FORESTS = {
+    "docqa": lambda: two_level_forest(10000, [50] * 24),
+    "three": lambda: three_level_forest(2048, [8192] * 4, 5, [37 + 13 * i for i in range(20)]),
+    "random": lambda: random_forest(60, 5, 2.0, 512, 1.0, 16, 32768, seed=8),
+    "mixed": lambda: concat_forests(two_level_forest(30000, [100] * 9), unshared_forest([7000, 8000, 50])),
+    "degenerate": lambda: degenerate_forest(6, 3000, 200),
+    "binary": lambda: full_kary_forest(2, 5, lambda lvl: 4000 // lvl),
+    "inner_request": lambda: Forest(np.array([-1, 0, 0, -1]), np.array([300, 40, 50, 77]), np.array([1, 0, 1])),
+}
+
+
+@pytest.mark.parametrize("name", sorted(FORESTS))
+@pytest.mark.parametrize("share", [True, False])
+@pytest.mark.parametrize("m,align,max_rows,hq,hkv,table", [
+    (8, 256, 64, 32, 8, "table2"), (3, 32, 16, 8, 1, "default"), (64, 64, 64, 8, 8, "table2"),
+    (17, 32, 7, 28, 4, "default")])
+def test_library_plan_equals_rederivation(name, share, m, align, max_rows, hq, hkv, table):
+    f = FORESTS[name]()
+    head = HeadConfig(hq, hkv, 128)
+    tab = TABLE2 if table == "table2" else _default_table()
+    view = _lib_plan(f, head, m, align, max_rows, share, tab if table == "table2" else None)
+    ref = P.plan(f.parent, f.node_len, f.req_node, head.group, m, align, max_rows, share, tab)
+    _compare(view, ref)
+
+
+@pytest.mark.parametrize("name", CONFIG_NAMES)
+@pytest.mark.parametrize("share", [True, False])
+def test_measured_configurations_with_library_defaults(name, share):
+    """Full-size forests of the measured configurations, default options of the library."""
+    f, head = config_forest(name), config_head(name)
+    view = _lib_plan(f, head, 0, 0, 0, share, None)
+    ref = P.plan(f.parent, f.node_len, f.req_node, head.group, 512 // head.num_kv_heads, 256, 64,
+                 share, _default_table())
+    _compare(view, ref)
