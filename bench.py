@@ -1,0 +1,262 @@
+#!/usr/bin/env python3
+"""Benchmark of prefix-shared decode attention on one MI355X.
+
+A step is one pass of the whole hot path (partial attention over the scheduled
+tasks + per-query reduction) over one synthetic batch whose Q/K/V already sit
+in HBM.  The step is timed cold: consecutive steps rotate over enough copies of
+the K/V pools that nothing of a pool survives in L2 / Infinity Cache until its
+next use, which is what a multi-layer decode loop sees.
+
+Prints ONE JSON line.  ``value`` is GB/s of unique KV bytes (every node counted
+once) over the whole step of the headline workload; ``roofline`` prices the
+partial-attention kernel alone against the 8 TB/s HBM peak; ``per_config``
+carries the same figures, the flat (no-sharing) baseline of the same library
+and the tree/flat speedup for every configuration; ``cpu_baseline`` is the fp64
+oracle timed on this machine's host cores on a bounded sample.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import math
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0
+COLD_FOOTPRINT_BYTES = 3 << 30        # rotate pool copies until this much K/V is cycled through
+
+
+def parse_args():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="cfg2", help="headline configuration")
+    ap.add_argument("--configs", default="cfg1,cfg2,cfg3,cfg4,cfg5a,cfg5b,cfg5c",
+                    help="configurations reported in per_config ('' = headline only)")
+    ap.add_argument("--layout", default="thd", choices=["thd", "htd"])
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-flat", action="store_true")
+    ap.add_argument("--num-slots", type=int, default=0)
+    ap.add_argument("--split-align", type=int, default=0)
+    ap.add_argument("--max-rows", type=int, default=0)
+    ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU time of the oracle sample")
+    return ap.parse_args()
+
+
+class Rotating:
+    """``copies`` clones of the K/V pools of a workload, all resident in HBM."""
+
+    def __init__(self, w, copies):
+        import torch
+        self.k = [w.k_pool] + [w.k_pool.clone() for _ in range(copies - 1)]
+        self.v = [w.v_pool] + [w.v_pool.clone() for _ in range(copies - 1)]
+        self.n = copies
+        torch.cuda.synchronize()
+
+    def pools(self, i):
+        return self.k[i % self.n], self.v[i % self.n]
+
+
+def time_plan(pa, w, rot, steps, warmup):
+    """Whole-step time over exactly ``steps`` steps plus per-phase kernel times from HIP events."""
+    import torch
+    out = torch.empty_like(w.q)
+    stream = torch.cuda.current_stream()
+    for i in range(warmup):
+        k, v = rot.pools(i)
+        pa.decode(w.q, k, v, out)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record(stream)
+    for i in range(steps):
+        k, v = rot.pools(warmup + i)
+        pa.decode(w.q, k, v, out)
+    e1.record(stream)
+    torch.cuda.synchronize()
+    wall_ms = (time.perf_counter() - t0) * 1e3 / steps
+    step_ms = e0.elapsed_time(e1) / steps
+
+    # second pass over the same steps: events around each phase, on the stream the kernels run on
+    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(steps)]
+    for i in range(steps):
+        k, v = rot.pools(warmup + i)
+        ev[i][0].record(stream)
+        pa.partial_attention(w.q, k, v)
+        ev[i][1].record(stream)
+        pa.partial_reduction(out)
+        ev[i][2].record(stream)
+    torch.cuda.synchronize()
+    pac = sorted(e[0].elapsed_time(e[1]) for e in ev)
+    por = sorted(e[1].elapsed_time(e[2]) for e in ev)
+    return {"step_ms": step_ms, "wall_ms": wall_ms,
+            "pac_ms_avg": sum(pac) / steps, "pac_ms_min": pac[0], "pac_ms_med": pac[steps // 2],
+            "por_ms_avg": sum(por) / steps}, out
+
+
+def run_config(name, args, steps, warmup, want_flat):
+    import torch
+    import paper_2505_17694_amd as C
+    from workloads import make_config, forest_stats
+
+    w = make_config(name, device="cuda:0", layout=args.layout)
+    st = forest_stats(w.forest)
+    unique_bytes = st["unique_tokens"] * w.head.bytes_per_token
+    flat_bytes = st["flat_tokens"] * w.head.bytes_per_token
+    pool_bytes = 2 * w.k_pool.numel() * 2
+    copies = max(1, min(int(math.ceil(COLD_FOOTPRINT_BYTES / max(pool_bytes, 1))), 64))
+    free, _ = torch.cuda.mem_get_info()
+    copies = max(1, min(copies, int(free * 0.8 // max(pool_bytes, 1)) + 1))
+    rot = Rotating(w, copies)
+    res = {"workload": name, "unique_kv_bytes": unique_bytes, "flat_kv_bytes": flat_bytes,
+           "mean_sharing": round(st["mean_sharing"], 3), "pool_copies": copies,
+           "requests": st["num_requests"], "nodes": st["num_nodes"]}
+    outs = {}
+    for share in ([1, 0] if want_flat else [1]):
+        t0 = time.perf_counter()
+        pa = C.PlannedAttention(w.forest, w.paged, w.head, device="cuda:0", share=share,
+                                num_slots=args.num_slots, split_align=args.split_align,
+                                max_rows=args.max_rows)
+        plan_ms = (time.perf_counter() - t0) * 1e3
+        view = pa.export()
+        t, out = time_plan(pa, w, rot, steps, warmup)
+        outs[share] = out.clone()
+        key = "tree" if share else "flat"
+        res[key] = {
+            "us_per_step": round(t["step_ms"] * 1e3, 2),
+            "pac_us": round(t["pac_ms_avg"] * 1e3, 2), "pac_us_min": round(t["pac_ms_min"] * 1e3, 2),
+            "por_us": round(t["por_ms_avg"] * 1e3, 2),
+            "unique_kv_GBps": round(unique_bytes / (t["step_ms"] * 1e-3) / 1e9, 1),
+            "frac_of_hbm_peak": round(unique_bytes / (t["step_ms"] * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4),
+            "read_GBps": round((unique_bytes if share else flat_bytes) / (t["step_ms"] * 1e-3) / 1e9, 1),
+            "pac_unique_kv_GBps": round(unique_bytes / (t["pac_ms_avg"] * 1e-3) / 1e9, 1),
+            "pac_frac_of_hbm_peak": round(unique_bytes / (t["pac_ms_avg"] * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4),
+            "plan_ms": round(plan_ms, 2), "tasks": len(view["tasks"]), "part_rows": view["part_rows"],
+            "est_makespan": view["makespan"], "cost_l": view["cost_l"],
+        }
+        res[key]["_raw"] = t
+        pa.close()
+    if want_flat:
+        res["speedup_vs_flat"] = round(res["flat"]["us_per_step"] / res["tree"]["us_per_step"], 3)
+        res["tree_vs_flat_max_abs_diff"] = float((outs[1].float() - outs[0].float()).abs().max())
+    return res, w, outs[1]
+
+
+def cpu_baseline(w, gpu_out, seconds):
+    """The fp64 oracle, as it stands, on a bounded sample of (request, head) pairs of the workload."""
+    import numpy as np
+    from oracle import attention as A
+
+    f, h = w.forest, w.head
+    B, H = f.num_requests, h.num_q_heads
+    ctx = np.array([sum(int(f.node_len[n]) for n in f.path(r)) for r in range(B)], dtype=np.int64)
+    total_tokens = int(ctx.sum()) * H                    # (request, head, token) triples of one step
+    rng = np.random.Generator(np.random.PCG64(4242))
+    order = rng.permutation(B * H)
+    threads = A.max_threads()
+    # the host copies of the inputs are made once, outside the timed region
+    qb, kb, vb = w.q_bits(), w.k_bits(), w.v_bits()
+    p = w.paged
+
+    def run(pairs):
+        t0 = time.perf_counter()
+        out, _ = A.decode_attention(f.parent, f.node_len, f.req_node, p.node_page_off, p.page_ids,
+                                    p.page_size, H, h.num_kv_heads, h.head_dim, h.dtype, h.scale,
+                                    qb, kb, vb, p.page_stride, p.token_stride, p.head_stride, sel=pairs)
+        return time.perf_counter() - t0, out
+
+    probe = [(int(i // H), int(i % H)) for i in order[:2 * threads]]
+    t_probe, _ = run(probe)
+    per_token = t_probe / max(1, sum(int(ctx[r]) for r, _ in probe))
+    n = int(min(B * H, max(2 * threads, seconds / max(per_token * ctx.mean(), 1e-9))))
+    pairs = [(int(i // H), int(i % H)) for i in order[:n]]
+    t, out = run(pairs)
+    sample_tokens = sum(int(ctx[r]) for r, _ in pairs)
+    t_full = t * total_tokens / sample_tokens
+    got = gpu_out.double().cpu().numpy()
+    err = float(np.max(np.abs(np.stack([got[r, hq] for r, hq in pairs]) - out)))
+    unique_bytes = w.unique_kv_bytes
+    return {"value": round(unique_bytes / t_full / 1e9, 4), "unit": "GB/s", "cores": threads,
+            "kind": "oracle",
+            "sample": f"{n} of {B * H} (request, head) pairs of {w.name} ({sample_tokens} of {total_tokens} "
+                      f"(request, head, token) triples) in {t:.2f} s; scaled to one full step = {t_full:.2f} s",
+            "seconds_per_step": round(t_full, 3), "gpu_vs_oracle_max_abs_err_on_sample": err}
+
+
+def main():
+    args = parse_args()
+    if args.gpus != 1:
+        print(f"bench.py: this build runs on ONE GPU; --gpus {args.gpus} is not supported "
+              "(no collectives, no sharding: see DESIGN.md, 'More than one GPU')", file=sys.stderr)
+        sys.exit(2)
+    import torch
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(2)
+
+    names = [c for c in args.configs.split(",") if c]
+    if args.workload not in names:
+        names.append(args.workload)
+    per_config = {}
+    headline = None
+    for name in names:
+        is_head = name == args.workload
+        steps = args.steps if is_head else max(10, min(args.steps, 30))
+        res, w, out = run_config(name, args, steps, args.warmup, not args.no_flat)
+        print(f"[bench] {name}: tree {res['tree']['us_per_step']} us/step "
+              f"({res['tree']['unique_kv_GBps']} GB/s unique KV)"
+              + (f", flat {res['flat']['us_per_step']} us, speedup {res['speedup_vs_flat']}x" if "flat" in res else ""),
+              file=sys.stderr, flush=True)
+        if is_head:
+            headline = (res, w, out)
+        else:
+            del w, out
+            torch.cuda.empty_cache()
+        per_config[name] = res
+
+    res, w, out = headline
+    raw = res["tree"]["_raw"]
+    cpu = None
+    if not args.no_cpu_baseline:
+        cpu = cpu_baseline(w, out, args.cpu_seconds)
+    for r in per_config.values():
+        for k in ("tree", "flat"):
+            if k in r:
+                r[k].pop("_raw", None)
+
+    unique = res["unique_kv_bytes"]
+    achieved = unique / (raw["pac_ms_avg"] * 1e-3) / 1e9
+    line = {
+        "metric": "decode_attention_unique_kv_bandwidth",
+        "value": res["tree"]["unique_kv_GBps"],
+        "unit": "GB/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(raw["step_ms"], 5),
+        "us_per_step": res["tree"]["us_per_step"],
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16" if w.head.dtype == 1 else "fp16",
+        "data": "synthetic",
+        "config": {"workload": args.workload, "q_heads": w.head.num_q_heads, "kv_heads": w.head.num_kv_heads,
+                   "head_dim": w.head.head_dim, "page_size": w.head.page_size, "kv_layout": args.layout,
+                   "requests": res["requests"], "nodes": res["nodes"], "unique_kv_bytes": unique,
+                   "cold_cache": f"rotation over {res['pool_copies']} K/V pool copies"},
+        "speedup_vs_flat": res.get("speedup_vs_flat"),
+        "roofline": {"bound": "hbm", "kernel": "pac_kernel (partial attention)",
+                     "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                     "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": None,
+                     "algorithmic_bytes_per_launch": unique,
+                     "avg_launch_us": round(raw["pac_ms_avg"] * 1e3, 2)},
+        "cpu_baseline": cpu,
+        "per_config": per_config,
+    }
+    print(json.dumps(line))
+
+
+if __name__ == "__main__":
+    main()

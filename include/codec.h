@@ -222,6 +222,20 @@ int codec_decode_attention(const codec_plan_t *plan, const void *q,
                            const codec_kv_layout *layout, void *out,
                            void *workspace, size_t workspace_bytes, void *stream);
 
+/*
+ * The two phases of Alg. 4 on their own, for callers that time or overlap them:
+ * codec_partial_attention runs the scheduled partial attention tasks and fills
+ * `workspace`; codec_partial_reduction merges the partials in `workspace` into
+ * `out`.  Same arguments, checks and stream semantics as codec_decode_attention,
+ * which is exactly the first followed by the second.
+ */
+int codec_partial_attention(const codec_plan_t *plan, const void *q,
+                            const void *k_pages, const void *v_pages,
+                            const codec_kv_layout *layout,
+                            void *workspace, size_t workspace_bytes, void *stream);
+int codec_partial_reduction(const codec_plan_t *plan, const void *workspace,
+                            size_t workspace_bytes, void *out, void *stream);
+
 /* Static, human-readable name of a status code. */
 const char *codec_status_string(int status);
 

@@ -31,7 +31,8 @@ CODEC_DTYPE_BF16 = 1
 EXPORTED_SYMBOLS = [
     "codec_plan_create", "codec_plan_destroy", "codec_plan_export", "codec_cost_estimate",
     "codec_default_cost_table", "codec_plan_device_bytes", "codec_plan_upload",
-    "codec_plan_workspace_bytes", "codec_decode_attention", "codec_status_string",
+    "codec_plan_workspace_bytes", "codec_decode_attention", "codec_partial_attention",
+    "codec_partial_reduction", "codec_status_string",
 ]
 
 _i32p = POINTER(c_int32)
@@ -112,6 +113,11 @@ _lib.codec_decode_attention.restype = c_int
 _lib.codec_decode_attention.argtypes = [c_void_p, c_void_p, c_void_p, c_void_p,
                                         POINTER(codec_kv_layout), c_void_p, c_void_p, c_size_t,
                                         c_void_p]
+_lib.codec_partial_attention.restype = c_int
+_lib.codec_partial_attention.argtypes = [c_void_p, c_void_p, c_void_p, c_void_p,
+                                         POINTER(codec_kv_layout), c_void_p, c_size_t, c_void_p]
+_lib.codec_partial_reduction.restype = c_int
+_lib.codec_partial_reduction.argtypes = [c_void_p, c_void_p, c_size_t, c_void_p, c_void_p]
 _lib.codec_status_string.restype = c_char_p
 _lib.codec_status_string.argtypes = [c_int]
 
@@ -233,3 +239,18 @@ def codec_decode_attention(plan, q_ptr: int, k_ptr: int, v_ptr: int, num_pages: 
     return _lib.codec_decode_attention(plan, c_void_p(q_ptr), c_void_p(k_ptr), c_void_p(v_ptr),
                                        byref(lay), c_void_p(out_ptr), c_void_p(workspace_ptr),
                                        workspace_bytes, c_void_p(stream))
+
+
+def codec_partial_attention(plan, q_ptr: int, k_ptr: int, v_ptr: int, num_pages: int,
+                            page_stride: int, token_stride: int, head_stride: int,
+                            workspace_ptr: int, workspace_bytes: int, stream: int = 0) -> int:
+    lay = codec_kv_layout(num_pages, page_stride, token_stride, head_stride)
+    return _lib.codec_partial_attention(plan, c_void_p(q_ptr), c_void_p(k_ptr), c_void_p(v_ptr),
+                                        byref(lay), c_void_p(workspace_ptr), workspace_bytes,
+                                        c_void_p(stream))
+
+
+def codec_partial_reduction(plan, workspace_ptr: int, workspace_bytes: int, out_ptr: int,
+                            stream: int = 0) -> int:
+    return _lib.codec_partial_reduction(plan, c_void_p(workspace_ptr), workspace_bytes,
+                                        c_void_p(out_ptr), c_void_p(stream))

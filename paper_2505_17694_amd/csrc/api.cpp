@@ -152,17 +152,17 @@ size_t codec_plan_workspace_bytes(const codec_plan_t *plan)
     return n ? n : 256;
 }
 
-int codec_decode_attention(const codec_plan_t *plan, const void *q, const void *k_pages,
-                           const void *v_pages, const codec_kv_layout *layout, void *out,
-                           void *workspace, size_t workspace_bytes, void *stream)
+int codec_partial_attention(const codec_plan_t *plan, const void *q, const void *k_pages,
+                            const void *v_pages, const codec_kv_layout *layout,
+                            void *workspace, size_t workspace_bytes, void *stream)
 {
     if (!plan || !layout) return CODEC_ERR_INVALID_ARGUMENT;
     const codec::PlanData &d = plan->d;
     if (d.num_requests == 0) return CODEC_OK;               // nothing to compute
-    if (!q || !k_pages || !v_pages || !out || !workspace) return CODEC_ERR_INVALID_ARGUMENT;
+    if (!q || !k_pages || !v_pages || !workspace) return CODEC_ERR_INVALID_ARGUMENT;
     if (!plan->device_meta) return CODEC_ERR_NOT_UPLOADED;
     if (workspace_bytes < codec_plan_workspace_bytes(plan)) return CODEC_ERR_WORKSPACE_TOO_SMALL;
-    if (!aligned16(q) || !aligned16(k_pages) || !aligned16(v_pages) || !aligned16(out)) return CODEC_ERR_INVALID_ARGUMENT;
+    if (!aligned16(q) || !aligned16(k_pages) || !aligned16(v_pages)) return CODEC_ERR_INVALID_ARGUMENT;
     if (reinterpret_cast<uintptr_t>(workspace) & 255u) return CODEC_ERR_INVALID_ARGUMENT;
     if (layout->num_pages <= plan->max_page_id) return CODEC_ERR_INVALID_ARGUMENT;
     if (layout->page_stride < 1 || layout->token_stride < 128 || layout->head_stride < 128 ||
@@ -194,10 +194,26 @@ int codec_decode_attention(const codec_plan_t *plan, const void *q, const void *
     pp.part_rows = d.part_rows;
     pp.scale_log2e = d.head.scale * 1.4426950408889634f;
     if (codec::launch_pac(pp, d.head.dtype, d.num_slots, plan->max_task_rows, stream) != 0) return CODEC_ERR_HIP;
+    return CODEC_OK;
+}
 
+int codec_partial_reduction(const codec_plan_t *plan, const void *workspace, size_t workspace_bytes,
+                            void *out, void *stream)
+{
+    if (!plan) return CODEC_ERR_INVALID_ARGUMENT;
+    const codec::PlanData &d = plan->d;
+    if (d.num_requests == 0) return CODEC_OK;
+    if (!workspace || !out) return CODEC_ERR_INVALID_ARGUMENT;
+    if (!plan->device_meta) return CODEC_ERR_NOT_UPLOADED;
+    if (workspace_bytes < codec_plan_workspace_bytes(plan)) return CODEC_ERR_WORKSPACE_TOO_SMALL;
+    if (!aligned16(out) || (reinterpret_cast<uintptr_t>(workspace) & 255u)) return CODEC_ERR_INVALID_ARGUMENT;
+
+    const char *meta = static_cast<const char *>(plan->device_meta);
+    const codec::DevLayout &L = d.layout;
+    const char *ws = static_cast<const char *>(workspace);
     codec::MergeParams mp{};
-    mp.part_o = pp.part_o;
-    mp.part_ml = pp.part_ml;
+    mp.part_o = reinterpret_cast<const float *>(ws);
+    mp.part_ml = reinterpret_cast<const float *>(ws + part_o_bytes(d));
     mp.req_part_off = reinterpret_cast<const int32_t *>(meta + L.req_part_off);
     mp.req_part = reinterpret_cast<const int32_t *>(meta + L.req_part);
     mp.out = out;
@@ -207,6 +223,17 @@ int codec_decode_attention(const codec_plan_t *plan, const void *q, const void *
     mp.part_rows = d.part_rows;
     if (codec::launch_merge(mp, d.head.dtype, stream) != 0) return CODEC_ERR_HIP;
     return CODEC_OK;
+}
+
+int codec_decode_attention(const codec_plan_t *plan, const void *q, const void *k_pages,
+                           const void *v_pages, const codec_kv_layout *layout, void *out,
+                           void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (plan && plan->d.num_requests == 0) return layout ? CODEC_OK : CODEC_ERR_INVALID_ARGUMENT;
+    if (!out || !aligned16(out)) return CODEC_ERR_INVALID_ARGUMENT;
+    if (int st = codec_partial_attention(plan, q, k_pages, v_pages, layout, workspace, workspace_bytes, stream))
+        return st;
+    return codec_partial_reduction(plan, workspace, workspace_bytes, out, stream);
 }
 
 const char *codec_status_string(int status)

@@ -60,6 +60,22 @@ class PlannedAttention:
             raise B.CodecError(st, "codec_decode_attention")
         return out
 
+    def partial_attention(self, q, k_pool, v_pool, stream=None) -> None:
+        s = (stream or torch.cuda.current_stream(self.device)).cuda_stream
+        p = self.paged
+        st = B.codec_partial_attention(self.plan, q.data_ptr(), k_pool.data_ptr(), v_pool.data_ptr(),
+                                       p.num_pages, p.page_stride, p.token_stride, p.head_stride,
+                                       self.workspace.data_ptr(), self.workspace.numel(), s)
+        if st != B.CODEC_OK:
+            raise B.CodecError(st, "codec_partial_attention")
+
+    def partial_reduction(self, out, stream=None) -> None:
+        s = (stream or torch.cuda.current_stream(self.device)).cuda_stream
+        st = B.codec_partial_reduction(self.plan, self.workspace.data_ptr(), self.workspace.numel(),
+                                       out.data_ptr(), s)
+        if st != B.CODEC_OK:
+            raise B.CodecError(st, "codec_partial_reduction")
+
     def close(self):
         if self.plan is not None:
             B.codec_plan_destroy(self.plan)
