@@ -53,7 +53,7 @@ typedef struct {
     int32_t num_kv_heads;       /* must divide num_q_heads; group = ratio, 1..64        */
     int32_t head_dim;           /* 128                                                  */
     int32_t dtype;              /* CODEC_DTYPE_*: type of q, K, V and out               */
-    int32_t page_size;          /* tokens per KV page, a multiple of 16                 */
+    int32_t page_size;          /* tokens per KV page, a power of two, 16..4096         */
     float   scale;              /* softmax scale, 1/sqrt(head_dim) in Eq. 1             */
 } codec_head_config;
 
@@ -93,11 +93,12 @@ typedef struct {
 } codec_cost_table;
 
 typedef struct {
-    int32_t num_slots;      /* m of Eq. 3: persistent workgroups per KV head; 0 = 512 / num_kv_heads */
+    int32_t num_slots;      /* m of Eq. 3: persistent workgroups per KV head; 0 = as many as run at once:
+                               256 / num_kv_heads if a task holds more than 16 rows, else 512 / num_kv_heads */
     int32_t split_align;    /* KV slices start on multiples of this many tokens; a multiple of
                                max(32, page_size); 0 = 256                                          */
-    int32_t max_rows;       /* most query rows (requests x group) one task may hold, 1..64,
-                               >= group; 0 = 64.  Larger query sets are cut into row tiles.        */
+    int32_t max_rows;       /* most query rows (requests x group) one task may hold, 1..256,
+                               >= group; 0 = 256.  Larger query sets are cut into row tiles.       */
     int32_t share;          /* 1 = prefix-shared plan; 0 = flat baseline: every request gets its
                                own tasks for every node on its path, nothing shared across requests */
     const codec_cost_table *cost;   /* NULL = built-in table                                        */

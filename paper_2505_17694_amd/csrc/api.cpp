@@ -190,7 +190,8 @@ int codec_partial_attention(const codec_plan_t *plan, const void *q, const void 
     pp.h_q = d.head.num_q_heads;
     pp.h_kv = d.head.num_kv_heads;
     pp.group = d.group;
-    pp.page_size = d.head.page_size;
+    pp.page_shift = 0;
+    while ((1 << pp.page_shift) < d.head.page_size) ++pp.page_shift;
     pp.part_rows = d.part_rows;
     pp.scale_log2e = d.head.scale * 1.4426950408889634f;
     if (codec::launch_pac(pp, d.head.dtype, d.num_slots, plan->max_task_rows, stream) != 0) return CODEC_ERR_HIP;

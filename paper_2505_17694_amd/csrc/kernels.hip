@@ -5,24 +5,28 @@
 // walks the slot's task list.  A task is a KV slice of a node together with the
 // query rows of the requests below the node: rows = requests x heads of the GQA
 // group, gathered straight from the query tensor into MFMA operand registers
-// (the on-chip query assembly of Sec. 4.1).  The four waves take interleaved
-// 32-token blocks of the slice, so every K and V byte is fetched from HBM once
-// per task and serves all rows.
+// (the on-chip query assembly of Sec. 4.1).  Every K and V byte of the slice is
+// fetched from HBM once per task and serves all rows.
 //
-// Per block a wave computes S^T = K Q^T (tokens x rows) with
-// v_mfma_f32_16x16x32: K rows are the A operand, loaded as 16-byte pieces
-// straight from the paged pool in operand layout; Q is the B operand.  The
-// accumulator layout (lane = row, 4 tokens per lane and tile) is already the B
-// operand layout of the second product O^T = V^T P^T once the eight tokens a
-// lane holds are taken as its k-slice, so P never moves between lanes.  V is
-// loaded with the matching token-to-lane map (lane group G takes tokens
-// 4G..4G+3 of both 16-token tiles, 16 bytes = 8 channels each) and turned into
-// the A operand by an 8x8 16-bit transpose inside each lane (v_perm_b32): no LDS
-// traffic in the main loop.  A lane ends up owning 32 consecutive channels of
-// one row.  Softmax statistics stay in fp32, in log2 units.
+// Arithmetic of one 32-token block, per wave: S^T = K Q^T (tokens x rows) with
+// v_mfma_f32_16x16x32, K rows as the A operand (16-byte pieces in operand
+// layout), Q as the B operand.  The accumulator layout (lane = row, 4 tokens per
+// lane and 16-token tile) is already the B-operand layout of the second product
+// O^T = V^T P^T once the eight tokens a lane holds are taken as its k-slice, so P
+// never moves between lanes.  V is fetched with the matching token-to-lane map
+// (lane group G takes tokens 4G..4G+3 of both tiles, 16 bytes = 8 channels each)
+// and becomes the A operand by an 8x8 16-bit transpose inside each lane
+// (v_perm_b32).  A lane ends up owning 32 consecutive channels of one row.
+// Softmax statistics stay in fp32, in log2 units.
 //
-// At the end of a task the four waves' states are merged through LDS and wave 0
-// writes the unnormalised partial output with (max, sum) per row.
+// Two task shapes share that arithmetic:
+//  * up to 32 rows ("stream"): the four waves take interleaved 32-token blocks
+//    of the slice, each with all rows; K and V go from HBM straight to registers
+//    (no LDS in the loop); the waves' states are merged through LDS at the end.
+//  * 33..256 rows ("dense"): the waves split the rows (up to 64 each) and walk
+//    the slice together; blocks are copied HBM -> LDS asynchronously into a ring of
+//    eight 16 KB slots (seven blocks in flight, one barrier per block) and read by
+//    all waves.
 #include <hip/hip_runtime.h>
 
 #include "kernels.hpp"
@@ -38,6 +42,7 @@ typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;
 constexpr int kWaves = 4;
 constexpr int kThreads = kWaves * 64;
 constexpr int kHeadDim = 128;
+constexpr int kMergeBytes = (2 * 8 * 64 * 4 + 2 * 64 * 2) * 4;      // stream-path merge of a 32-row state
 
 template <int DT>
 __device__ __forceinline__ f32x4 mfma16(u32x4 a, u32x4 b, f32x4 c)
@@ -67,80 +72,101 @@ __device__ __forceinline__ unsigned int pack2(float lo, float hi)
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
-__device__ __forceinline__ u32x4 ld16(const void *p) { return *reinterpret_cast<const u32x4 *>(p); }
+__device__ __forceinline__ u32x4 ld16(const char *p) { return *reinterpret_cast<const u32x4 *>(p); }
 
-// K and V registers of one 32-token block.
+// Slice being processed: wave-uniform values only, so that addresses are SGPR base + 32-bit lane offset.
+struct SliceCtx {
+    const char *k_head;         // K pool + KV-head offset
+    const char *v_head;
+    const int32_t *pages;       // page ids of the slice, first page first
+    int64_t page_bytes;
+    uint32_t token_bytes;
+    int32_t kv_len;
+    int32_t page_shift;         // log2(page_size)
+    int32_t page_mask;
+};
+
+// Page ids are read through the scalar data path (s_load_dword, a read-only access): a vector load
+// would sit in the same in-order return queue as the K/V traffic, and waiting for it would drain every
+// prefetched block.  The compiler cannot pick the scalar path itself here because the kernel also
+// stores to global memory.  `p` and `index` must be wave-uniform.
+__device__ __forceinline__ int scalar_load(const int32_t *p, int index)
+{
+    int v;
+    asm volatile("s_load_dword %0, %1, %2\n\t"
+                 "s_waitcnt lgkmcnt(0)"
+                 : "=s"(v)
+                 : "s"(p), "s"(index * 4)
+                 : "memory");
+    return v;
+}
+
+// Byte offset of the 16-token tile that starts at token `tok0` of the slice (wave-uniform).
+__device__ __forceinline__ int64_t tile_offset(const SliceCtx &c, int tok0)
+{
+    const int pg = scalar_load(c.pages, tok0 >> c.page_shift);
+    return int64_t(pg) * c.page_bytes + int64_t(tok0 & c.page_mask) * c.token_bytes;
+}
+
+// K and V registers of one 32-token block (stream path).
 struct BlockRegs {
-    u32x4 k[2][4];      // [16-token tile][32-channel k-step]: token = tile*16 + lane%16, channels 32*ks + 8*(lane/16)..+7
+    u32x4 k[2][4];      // [tile][k-step]: token = tile*16 + lane%16, channels 32*ks + 8*(lane/16)..+7
     u32x4 v[8];         // [e]: token = (e/4)*16 + 4*(lane/16) + e%4, channels 8*(lane%16)..+7
 };
 
-struct WaveCtx {
-    const char *k_base;     // pool base + KV-head offset, bytes
-    const char *v_base;
-    int64_t page_bytes, token_bytes;
-    const int32_t *pages;   // the slice's first page id
-    int32_t kv_len;
-    int32_t page_size;
-    int l16, grp;
-};
-
-// Issue the loads of block `tb` (32 tokens).  Tiles that start beyond the slice are redirected to
-// tile 0 so that no address leaves the slice's pages; their scores are masked later.
-__device__ __forceinline__ void load_block(const WaveCtx &c, int tb, BlockRegs &r)
+// Issue the loads of block `tb`.  A tile that starts beyond the slice is redirected to tile 0 so that
+// no address leaves the slice's pages; its scores are masked later.
+__device__ __forceinline__ void load_block(const SliceCtx &c, int tb, uint32_t koff, uint32_t voff, BlockRegs &r)
 {
 #pragma unroll
     for (int j = 0; j < 2; ++j) {
         int tok0 = tb * 32 + j * 16;
         if (tok0 >= c.kv_len) tok0 = 0;
-        const int pg = c.pages[tok0 / c.page_size];
-        const int slot0 = tok0 % c.page_size;
-        const int64_t tile_off = int64_t(pg) * c.page_bytes + int64_t(slot0) * c.token_bytes;
-        const char *kp = c.k_base + tile_off + int64_t(c.l16) * c.token_bytes + c.grp * 16;
+        const int64_t off = tile_offset(c, tok0);
+        const char *kt = c.k_head + off;
+        const char *vt = c.v_head + off;
 #pragma unroll
-        for (int ks = 0; ks < 4; ++ks) r.k[j][ks] = ld16(kp + ks * 64);
-        const char *vp = c.v_base + tile_off + int64_t(c.grp * 4) * c.token_bytes + c.l16 * 16;
+        for (int ks = 0; ks < 4; ++ks) r.k[j][ks] = ld16(kt + koff + ks * 64);
 #pragma unroll
-        for (int e = 0; e < 4; ++e) r.v[j * 4 + e] = ld16(vp + int64_t(e) * c.token_bytes);
+        for (int e = 0; e < 4; ++e) r.v[j * 4 + e] = ld16(vt + size_t(e) * c.token_bytes + voff);
     }
 }
 
-template <int DT, int NT>
+template <int NT>
 struct RowState {
-    f32x4 o[NT][8];     // [row tile][channel tile dt]: row = 16*nt + lane%16, channel = 32*(lane/16) + 8*e + dt
+    f32x4 o[NT][8];     // [row tile][dt]: row = 16*nt + lane%16, channel = 32*(lane/16) + 8*e + dt
     float m[NT];        // running maximum, log2 units (same in the 4 lanes that share a row)
     float l[NT];        // this lane's share of the running sum of exponentials
-};
 
-template <int DT, int NT>
-__device__ __forceinline__ void compute_block(const WaveCtx &c, int tb, BlockRegs &r,
-                                              const u32x4 (&qb)[NT][4], RowState<DT, NT> &st,
-                                              float scale_log2e)
-{
-    f32x4 s[2][NT];
-#pragma unroll
-    for (int j = 0; j < 2; ++j)
+    __device__ __forceinline__ void clear()
+    {
 #pragma unroll
         for (int nt = 0; nt < NT; ++nt) {
-            f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+            m[nt] = -INFINITY;
+            l[nt] = 0.f;
 #pragma unroll
-            for (int ks = 0; ks < 4; ++ks) acc = mfma16<DT>(r.k[j][ks], qb[nt][ks], acc);
-            s[j][nt] = acc;
+            for (int dt = 0; dt < 8; ++dt) o[nt][dt] = f32x4{0.f, 0.f, 0.f, 0.f};
         }
+    }
+};
 
-    const int valid = c.kv_len - tb * 32;           // >= 1
+// Online softmax update and O^T += V^T P^T for one block of NT row tiles, straight-line code apart
+// from two wave-uniform branches (ragged tail, rescale).  `s` are raw scores (tokens past `valid`
+// are masked here), `v` the block's V rows in the lane map described above.
+template <int DT, int NT>
+__device__ __forceinline__ void softmax_pv(f32x4 (&s)[2][NT], u32x4 (&v)[8], RowState<NT> &st,
+                                           int valid, int grp, float scale_log2e)
+{
     if (valid < 32) {
-        // ragged tail: tokens past the slice score -inf and their V rows count as zero
 #pragma unroll
         for (int j = 0; j < 2; ++j)
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
-                const bool dead = j * 16 + c.grp * 4 + e >= valid;
-                if (dead) {
-                    r.v[j * 4 + e] = u32x4{0u, 0u, 0u, 0u};
+                const bool dead = j * 16 + grp * 4 + e >= valid;
 #pragma unroll
-                    for (int nt = 0; nt < NT; ++nt) s[j][nt][e] = -INFINITY;
-                }
+                for (int c = 0; c < 4; ++c) v[j * 4 + e][c] = dead ? 0u : v[j * 4 + e][c];
+#pragma unroll
+                for (int nt = 0; nt < NT; ++nt) s[j][nt][e] = dead ? -INFINITY : s[j][nt][e];
             }
     }
 
@@ -152,7 +178,13 @@ __device__ __forceinline__ void compute_block(const WaveCtx &c, int tb, BlockReg
         mx = fmaxf(mx, __shfl_xor(mx, 16));
         mx = fmaxf(mx, __shfl_xor(mx, 32));
         const float m_new = fmaxf(st.m[nt], mx * scale_log2e);
-        const float alpha = fast_exp2(st.m[nt] - m_new);
+        if (__any(m_new > st.m[nt])) {          // rescale only when some row's maximum moved
+            const float alpha = fast_exp2(st.m[nt] - m_new);
+            st.l[nt] *= alpha;
+#pragma unroll
+            for (int dt = 0; dt < 8; ++dt) st.o[nt][dt] *= alpha;
+            st.m[nt] = m_new;
+        }
         float p[2][4];
         float sum = 0.f;
 #pragma unroll
@@ -162,44 +194,32 @@ __device__ __forceinline__ void compute_block(const WaveCtx &c, int tb, BlockReg
                 p[j][e] = fast_exp2(__builtin_fmaf(s[j][nt][e], scale_log2e, -m_new));
                 sum += p[j][e];
             }
-        st.l[nt] = st.l[nt] * alpha + sum;
-        st.m[nt] = m_new;
-#pragma unroll
-        for (int dt = 0; dt < 8; ++dt) st.o[nt][dt] *= alpha;
+        st.l[nt] += sum;
         pb[nt] = u32x4{pack2<DT>(p[0][0], p[0][1]), pack2<DT>(p[0][2], p[0][3]),
                        pack2<DT>(p[1][0], p[1][1]), pack2<DT>(p[1][2], p[1][3])};
     }
 
-    // 8x8 transpose inside the lane: v[e] holds 8 channels of token e, va[dt] holds 8 tokens of channel dt
+    // 8x8 transpose inside the lane: v[e] holds 8 channels of token e, va holds 8 tokens of channel dt
 #pragma unroll
     for (int dt = 0; dt < 8; ++dt) {
         const unsigned int sel = (dt & 1) ? 0x07060302u : 0x05040100u;
         u32x4 va;
 #pragma unroll
         for (int k = 0; k < 4; ++k)
-            va[k] = __builtin_amdgcn_perm(r.v[2 * k + 1][dt >> 1], r.v[2 * k][dt >> 1], sel);
+            va[k] = __builtin_amdgcn_perm(v[2 * k + 1][dt >> 1], v[2 * k][dt >> 1], sel);
 #pragma unroll
         for (int nt = 0; nt < NT; ++nt) st.o[nt][dt] = mfma16<DT>(va, pb[nt], st.o[nt][dt]);
     }
 }
 
-// exp2(a - m) with the convention that the side holding the maximum weighs exactly 1
-// (keeps "-inf minus -inf" of a wave that saw no token out of the arithmetic).
-__device__ __forceinline__ float weight(float a, float m) { return a == m ? 1.f : fast_exp2(a - m); }
-
-template <int DT, int NT>
-__device__ void run_task(const PacParams &P, const DevTask &t, int head, float *lds)
+// Gather the wave's query rows (task rows row0 .. row0 + 16*NT) into B-operand registers.
+template <int NT>
+__device__ __forceinline__ void gather_q(const PacParams &P, const DevTask &t, int head, int row0, int rows,
+                                         int l16, int grp, u32x4 (&qb)[NT][4])
 {
-    const int lane = threadIdx.x & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int l16 = lane & 15, grp = lane >> 4;
-    const int rows = t.n_req * P.group;
-
-    // query rows -> B operand registers
-    u32x4 qb[NT][4];
 #pragma unroll
     for (int nt = 0; nt < NT; ++nt) {
-        const int row = nt * 16 + l16;
+        const int row = row0 + nt * 16 + l16;
         const bool live = row < rows;
         const int qi = live ? row / P.group : 0;
         const int hj = live ? row - qi * P.group : 0;
@@ -209,41 +229,98 @@ __device__ void run_task(const PacParams &P, const DevTask &t, int head, float *
 #pragma unroll
         for (int ks = 0; ks < 4; ++ks) qb[nt][ks] = live ? ld16(qp + ks * 64) : u32x4{0u, 0u, 0u, 0u};
     }
+}
 
-    WaveCtx c;
-    c.k_base = static_cast<const char *>(P.k_pages) + int64_t(head) * P.head_stride * 2;
-    c.v_base = static_cast<const char *>(P.v_pages) + int64_t(head) * P.head_stride * 2;
-    c.page_bytes = P.page_stride * 2;
-    c.token_bytes = P.token_stride * 2;
-    c.pages = P.page_ids + t.page_off;
-    c.kv_len = t.kv_len;
-    c.page_size = P.page_size;
-    c.l16 = l16;
-    c.grp = grp;
-
-    RowState<DT, NT> st;
+// Write one wave's rows of the partial result: unnormalised output, (max, sum) per row.
+template <int NT>
+__device__ __forceinline__ void store_partial(const PacParams &P, const DevTask &t, int head, int row0, int rows,
+                                              int l16, int grp, const RowState<NT> &st)
+{
 #pragma unroll
     for (int nt = 0; nt < NT; ++nt) {
-        st.m[nt] = -INFINITY;
-        st.l[nt] = 0.f;
+        const int row = row0 + nt * 16 + l16;
+        if (row < rows) {
+            const int64_t prow = int64_t(head) * P.part_rows + t.part_row_base + row;
+            float *po = P.part_o + prow * kHeadDim + grp * 32;
 #pragma unroll
-        for (int dt = 0; dt < 8; ++dt) st.o[nt][dt] = f32x4{0.f, 0.f, 0.f, 0.f};
+            for (int e = 0; e < 4; ++e) {
+                f32x4 lo = {st.o[nt][0][e], st.o[nt][1][e], st.o[nt][2][e], st.o[nt][3][e]};
+                f32x4 hi = {st.o[nt][4][e], st.o[nt][5][e], st.o[nt][6][e], st.o[nt][7][e]};
+                *reinterpret_cast<f32x4 *>(po + e * 8) = lo;
+                *reinterpret_cast<f32x4 *>(po + e * 8 + 4) = hi;
+            }
+            if (grp == 0) {
+                float2 ml = {st.m[nt], st.l[nt]};
+                *reinterpret_cast<float2 *>(P.part_ml + prow * 2) = ml;
+            }
+        }
     }
+}
+
+__device__ __forceinline__ SliceCtx make_ctx(const PacParams &P, const DevTask &t, int head)
+{
+    SliceCtx c;
+    c.k_head = static_cast<const char *>(P.k_pages) + int64_t(head) * P.head_stride * 2;
+    c.v_head = static_cast<const char *>(P.v_pages) + int64_t(head) * P.head_stride * 2;
+    c.pages = P.page_ids + t.page_off;
+    c.page_bytes = P.page_stride * 2;
+    c.token_bytes = uint32_t(P.token_stride * 2);
+    c.kv_len = t.kv_len;
+    c.page_shift = P.page_shift;
+    c.page_mask = (1 << P.page_shift) - 1;
+    return c;
+}
+
+// exp2(a - m) with the convention that the side holding the maximum weighs exactly 1
+// (keeps "-inf minus -inf" of a wave that saw no token out of the arithmetic).
+__device__ __forceinline__ float weight(float a, float m) { return a == m ? 1.f : fast_exp2(a - m); }
+
+// ---- stream path: rows <= 16*NT (NT = 1, 2), waves split the tokens ----------------------------------------------
+template <int DT, int NT>
+__device__ void run_stream(const PacParams &P, const DevTask &t, int head, char *lds_raw)
+{
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int l16 = lane & 15, grp = lane >> 4;
+    const int rows = t.n_req * P.group;
+
+    u32x4 qb[NT][4];
+    gather_q<NT>(P, t, head, 0, rows, l16, grp, qb);
+    const SliceCtx c = make_ctx(P, t, head);
+    const uint32_t koff = uint32_t(l16) * c.token_bytes + grp * 16;
+    const uint32_t voff = uint32_t(grp * 4) * c.token_bytes + l16 * 16;
+
+    RowState<NT> st;
+    st.clear();
+
+    auto compute = [&](int tb, BlockRegs &r) {
+        f32x4 s[2][NT];
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+            for (int nt = 0; nt < NT; ++nt) {
+                f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (int ks = 0; ks < 4; ++ks) acc = mfma16<DT>(r.k[j][ks], qb[nt][ks], acc);
+                s[j][nt] = acc;
+            }
+        softmax_pv<DT, NT>(s, r.v, st, c.kv_len - tb * 32, grp, P.scale_log2e);
+    };
 
     // software pipeline: the loads of the wave's next block are in flight while it computes this one
     const int nblk = (t.kv_len + 31) >> 5;
     BlockRegs ra, rb;
     int tb = wave;
-    if (tb < nblk) load_block(c, tb, ra);
+    if (tb < nblk) load_block(c, tb, koff, voff, ra);
     while (tb < nblk) {
         int nb = tb + kWaves;
-        if (nb < nblk) load_block(c, nb, rb);
-        compute_block<DT, NT>(c, tb, ra, qb, st, P.scale_log2e);
+        if (nb < nblk) load_block(c, nb, koff, voff, rb);
+        compute(tb, ra);
         tb = nb;
         if (tb >= nblk) break;
         nb = tb + kWaves;
-        if (nb < nblk) load_block(c, nb, ra);
-        compute_block<DT, NT>(c, tb, rb, qb, st, P.scale_log2e);
+        if (nb < nblk) load_block(c, nb, koff, voff, ra);
+        compute(tb, rb);
         tb = nb;
     }
 
@@ -254,6 +331,7 @@ __device__ void run_task(const PacParams &P, const DevTask &t, int head, float *
     }
 
     // merge the four waves: wave w hands its state to wave w-1 through LDS, 3 -> 2 -> 1 -> 0
+    float *lds = reinterpret_cast<float *>(lds_raw);
     f32x4 *lds_o = reinterpret_cast<f32x4 *>(lds);                     // [NT][8][64]
     float *lds_m = lds + NT * 8 * 64 * 4;                               // [NT][64]
     float *lds_l = lds_m + NT * 64;
@@ -284,34 +362,161 @@ __device__ void run_task(const PacParams &P, const DevTask &t, int head, float *
         }
         __syncthreads();
     }
+    if (wave == 0) store_partial<NT>(P, t, head, 0, rows, l16, grp, st);
+}
 
-    if (wave == 0) {
+// ---- dense path: 33..256 rows, waves split the rows and share each staged block ------------------
+//
+// Blocks travel HBM -> LDS without passing through registers (global_load_lds_dwordx4: every lane
+// moves 16 bytes, a wave fills 1 KB of consecutive LDS).  A ring of kRing block slots (16 KB each:
+// 32 K rows then 32 V rows of 256 B) keeps kRing-1 blocks in flight per workgroup.  Rows are stored
+// unpadded; the 16-byte column index is XORed with (row & 15) so that both operand read patterns
+// (16 lanes down a column for K, 16 lanes along a row for V) spread over all banks.  The swizzle is
+// applied on the global side: the lane that fills LDS column c of row r fetches column c ^ (r & 15).
+//
+// The compiler does not see these loads (inline asm), so the waits are explicit: loads complete in
+// issue order, block b is in LDS once at most 4 * (blocks issued after b) of the wave's loads are
+// outstanding, and the barrier that follows publishes all four waves' parts.
+constexpr int kRing = 8;
+constexpr int kBlockBytes = 16384;
+constexpr int kRingBytes = kRing * kBlockBytes;
+
+__device__ __forceinline__ void dma16(uint32_t lds_addr, uint32_t voff, const char *gbase)
+{
+    uint32_t m0_saved;
+    asm volatile("s_mov_b32 %0, m0\n\t"
+                 "s_mov_b32 m0, %1\n\t"
+                 "s_nop 0\n\t"
+                 "global_load_lds_dwordx4 %2, %3\n\t"
+                 "s_mov_b32 m0, %0\n"
+                 : "=&s"(m0_saved)
+                 : "s"(lds_addr), "v"(voff), "s"(gbase)
+                 : "memory");
+}
+
+// One wave's share of a dense task: NL live row tiles starting at task row `row0` (NL = 0: the wave
+// only helps moving blocks).  All waves run the same number of barriers.
+template <int DT, int NL>
+__device__ __forceinline__ void dense_wave(const PacParams &P, const DevTask &t, int head, char *lds,
+                                           int wave, int row0, int rows)
+{
+    static_assert(kRing - 2 == 6, "the steady-state wait below is for 6 blocks ahead");
+    const int lane = threadIdx.x & 63;
+    const int l16 = lane & 15, grp = lane >> 4;
+    constexpr int NQ = NL > 0 ? NL : 1;
+
+    u32x4 qb[NQ][4];
+    RowState<NQ> st;
+    if constexpr (NL > 0) {
+        gather_q<NL>(P, t, head, row0, rows, l16, grp, qb);
+        st.clear();
+    }
+    // every load the compiler knows about is complete before the first asynchronous copy is issued, so
+    // that it places no vector-memory wait of its own inside the loop (such a wait would also drain
+    // the copies in flight)
+    __builtin_amdgcn_s_waitcnt(0x0F70);
+    const SliceCtx c = make_ctx(P, t, head);
+
+    // wave w moves rows 8w .. 8w+7 of every block: two 1 KB pieces of K and two of V
+    const uint32_t lds_base = uint32_t(uintptr_t(lds));
+    uint32_t voff[2];
 #pragma unroll
-        for (int nt = 0; nt < NT; ++nt) {
-            const int row = nt * 16 + l16;
-            if (row < rows) {
-                const int64_t prow = int64_t(head) * P.part_rows + t.part_row_base + row;
-                float *po = P.part_o + prow * kHeadDim + grp * 32;
+    for (int i = 0; i < 2; ++i) {
+        const int key = ((wave & 1) * 8 + 4 * i + grp) & 15;           // destination row & 15
+        voff[i] = uint32_t(4 * i + grp) * c.token_bytes + uint32_t((l16 ^ key) << 4);
+    }
+    auto dma_block = [&](int bb) {
+        int tok0 = bb * 32 + wave * 8;
+        if (tok0 >= c.kv_len) tok0 = 0;                                 // nothing of the group is live
+        const int64_t off = tile_offset(c, tok0 & ~15) + int64_t(tok0 & 15) * c.token_bytes;
+        const uint32_t slot = lds_base + uint32_t(bb % kRing) * kBlockBytes + uint32_t(wave) * 2048;
 #pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    f32x4 lo = {st.o[nt][0][e], st.o[nt][1][e], st.o[nt][2][e], st.o[nt][3][e]};
-                    f32x4 hi = {st.o[nt][4][e], st.o[nt][5][e], st.o[nt][6][e], st.o[nt][7][e]};
-                    *reinterpret_cast<f32x4 *>(po + e * 8) = lo;
-                    *reinterpret_cast<f32x4 *>(po + e * 8 + 4) = hi;
-                }
-                if (grp == 0) {
-                    float2 ml = {st.m[nt], st.l[nt]};
-                    *reinterpret_cast<float2 *>(P.part_ml + prow * 2) = ml;
+        for (int i = 0; i < 2; ++i) {
+            dma16(slot + i * 1024, voff[i], c.k_head + off);
+            dma16(slot + 8192 + i * 1024, voff[i], c.v_head + off);
+        }
+    };
+    // lane-dependent parts of the operand addresses (the slot base is added per block)
+    uint32_t ka_off[4], va_off[4];
+#pragma unroll
+    for (int x = 0; x < 4; ++x) {
+        ka_off[x] = uint32_t(l16 * 256 + (((x * 4 + grp) ^ l16) << 4));                 // k-step x
+        va_off[x] = uint32_t(8192 + (grp * 4 + x) * 256 + ((l16 ^ (grp * 4 + x)) << 4)); // token 4*grp + x
+    }
+
+    const int nblk = (t.kv_len + 31) >> 5;
+#pragma unroll 1
+    for (int d = 0; d < kRing - 1; ++d)
+        if (d < nblk) dma_block(d);
+#pragma unroll 1
+    for (int b = 0; b < nblk; ++b) {
+        // block b has landed once at most 4 loads per block issued after it are outstanding; near the
+        // end of the slice no new loads were issued, so wait for everything
+        if (nblk - 1 - b >= kRing - 2) __builtin_amdgcn_s_waitcnt(0x4F78);     // vmcnt(24)
+        else                           __builtin_amdgcn_s_waitcnt(0x0F70);     // vmcnt(0)
+        __syncthreads();                    // block b is complete; everyone is done with block b-1
+        if (b + kRing - 1 < nblk) dma_block(b + kRing - 1);            // refills the slot of block b-1
+        if constexpr (NL > 0) {
+            const char *buf = lds + (b % kRing) * kBlockBytes;
+            f32x4 s[2][NL];
+#pragma unroll
+            for (int j = 0; j < 2; ++j) {
+                u32x4 ka[4];
+#pragma unroll
+                for (int ks = 0; ks < 4; ++ks)
+                    ka[ks] = *reinterpret_cast<const u32x4 *>(buf + j * 4096 + ka_off[ks]);
+#pragma unroll
+                for (int nt = 0; nt < NL; ++nt) {
+                    f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                    for (int ks = 0; ks < 4; ++ks) acc = mfma16<DT>(ka[ks], qb[nt][ks], acc);
+                    s[j][nt] = acc;
                 }
             }
+            u32x4 v[8];
+#pragma unroll
+            for (int e = 0; e < 8; ++e)
+                v[e] = *reinterpret_cast<const u32x4 *>(buf + (e >> 2) * 4096 + va_off[e & 3]);
+            softmax_pv<DT, NL>(s, v, st, c.kv_len - b * 32, grp, P.scale_log2e);
         }
+    }
+
+    if constexpr (NL > 0) {
+#pragma unroll
+        for (int nt = 0; nt < NL; ++nt) {
+            st.l[nt] += __shfl_xor(st.l[nt], 16);
+            st.l[nt] += __shfl_xor(st.l[nt], 32);
+        }
+        store_partial<NL>(P, t, head, row0, rows, l16, grp, st);
+    }
+    __syncthreads();                        // the ring is reused by the slot's next task
+}
+
+template <int DT>
+__device__ void run_dense(const PacParams &P, const DevTask &t, int head, char *lds)
+{
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int rows = t.n_req * P.group;
+    const int tiles_per_wave = (rows + 63) >> 6;                        // ceil(rows / 64) row tiles of 16
+    const int row0 = wave * tiles_per_wave * 16;
+    int live = (rows - row0 + 15) >> 4;
+    live = live < 0 ? 0 : (live > tiles_per_wave ? tiles_per_wave : live);
+    switch (live) {
+    case 0: dense_wave<DT, 0>(P, t, head, lds, wave, row0, rows); break;
+    case 1: dense_wave<DT, 1>(P, t, head, lds, wave, row0, rows); break;
+    case 2: dense_wave<DT, 2>(P, t, head, lds, wave, row0, rows); break;
+    case 3: dense_wave<DT, 3>(P, t, head, lds, wave, row0, rows); break;
+    default: dense_wave<DT, 4>(P, t, head, lds, wave, row0, rows); break;
     }
 }
 
-template <int DT, int MAXNT>
-__global__ void __launch_bounds__(kThreads, MAXNT >= 4 ? 1 : 2) pac_kernel(const PacParams P)
+extern __shared__ __attribute__((aligned(16))) char dyn_lds[];      // WIDE: kRingBytes of dynamic LDS
+
+template <int DT, int WIDE>
+__global__ void __launch_bounds__(kThreads, WIDE ? 1 : 2) pac_kernel(const PacParams P)
 {
-    __shared__ __attribute__((aligned(16))) float lds[MAXNT * 8 * 64 * 4 + MAXNT * 64 * 2];
+    __shared__ __attribute__((aligned(16))) char static_lds[WIDE ? 16 : kMergeBytes];
+    char *lds = WIDE ? dyn_lds : static_lds;
     const int head = blockIdx.x % P.h_kv;
     const int slot = blockIdx.x / P.h_kv;
     const int t0 = P.slot_off[slot], t1 = P.slot_off[slot + 1];
@@ -319,12 +524,14 @@ __global__ void __launch_bounds__(kThreads, MAXNT >= 4 ? 1 : 2) pac_kernel(const
     for (int i = t0; i < t1; ++i) {
         const DevTask t = P.tasks[P.slot_tasks[i]];
         const int rows = t.n_req * P.group;
-        if (rows <= 16)
-            run_task<DT, 1>(P, t, head, lds);
-        else if (MAXNT >= 2 && rows <= 32)
-            run_task<DT, (MAXNT >= 2 ? 2 : 1)>(P, t, head, lds);
-        else if (MAXNT >= 4)
-            run_task<DT, (MAXNT >= 4 ? 4 : 1)>(P, t, head, lds);
+        if (rows <= 16) {
+            run_stream<DT, 1>(P, t, head, lds);
+        } else if constexpr (WIDE != 0) {
+            if (rows <= 32)
+                run_stream<DT, 2>(P, t, head, lds);
+            else
+                run_dense<DT>(P, t, head, lds);
+        }
     }
 }
 
@@ -358,17 +565,29 @@ __global__ void __launch_bounds__(kThreads) merge_kernel(const MergeParams P)
 
 }  // namespace
 
+// The wide variant needs more dynamic LDS than the 64 KB a kernel gets by default.
+template <typename K>
+int allow_ring_lds(K kernel)
+{
+    static int status = int(hipFuncSetAttribute(reinterpret_cast<const void *>(kernel),
+                                                hipFuncAttributeMaxDynamicSharedMemorySize, kRingBytes));
+    return status;
+}
+
 int launch_pac(const PacParams &p, int dtype, int num_slots, int max_rows_in_plan, void *stream)
 {
     const dim3 grid(unsigned(num_slots) * unsigned(p.h_kv)), block(kThreads);
     hipStream_t s = static_cast<hipStream_t>(stream);
-    const bool wide = max_rows_in_plan > 32;
-    if (dtype == CODEC_DTYPE_FP16) {
-        if (wide) hipLaunchKernelGGL((pac_kernel<CODEC_DTYPE_FP16, 4>), grid, block, 0, s, p);
-        else      hipLaunchKernelGGL((pac_kernel<CODEC_DTYPE_FP16, 2>), grid, block, 0, s, p);
+    const bool wide = max_rows_in_plan > 16;
+    if (wide) {
+        auto k16 = pac_kernel<CODEC_DTYPE_FP16, 1>;
+        auto kbf = pac_kernel<CODEC_DTYPE_BF16, 1>;
+        if (int e = (dtype == CODEC_DTYPE_FP16 ? allow_ring_lds(k16) : allow_ring_lds(kbf))) return e;
+        if (dtype == CODEC_DTYPE_FP16) hipLaunchKernelGGL(k16, grid, block, kRingBytes, s, p);
+        else                           hipLaunchKernelGGL(kbf, grid, block, kRingBytes, s, p);
     } else {
-        if (wide) hipLaunchKernelGGL((pac_kernel<CODEC_DTYPE_BF16, 4>), grid, block, 0, s, p);
-        else      hipLaunchKernelGGL((pac_kernel<CODEC_DTYPE_BF16, 2>), grid, block, 0, s, p);
+        if (dtype == CODEC_DTYPE_FP16) hipLaunchKernelGGL((pac_kernel<CODEC_DTYPE_FP16, 0>), grid, block, 0, s, p);
+        else                           hipLaunchKernelGGL((pac_kernel<CODEC_DTYPE_BF16, 0>), grid, block, 0, s, p);
     }
     return int(hipGetLastError());
 }

@@ -19,7 +19,7 @@ struct PacParams {
     const int32_t *page_ids;
     float *part_o;                  // [h_kv][part_rows][128] unnormalised partial outputs
     float *part_ml;                 // [h_kv][part_rows][2]   (max in log2 units, sum of exponentials)
-    int32_t h_q, h_kv, group, page_size, part_rows;
+    int32_t h_q, h_kv, group, page_shift, part_rows;    // page_shift = log2(tokens per page)
     float scale_log2e;              // scale * log2(e): scores are kept in log2 units
 };
 

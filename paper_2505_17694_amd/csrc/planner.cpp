@@ -123,18 +123,20 @@ int64_t CostTable::estimate(int64_t rows, int64_t len) const
     return v < 1 ? 1 : static_cast<int64_t>(v);
 }
 
-// Bootstrap table (ns per workgroup) from a bandwidth model of the streaming
-// kernel: setup + tokens * (46 + 0.3 rows) + 95 per partial row.  Replaced by a
-// measured table through codec_plan_options.cost.
+// Bootstrap table (ns per workgroup, one workgroup per CU) from a bandwidth
+// model of the kernel: 2500 + tokens * (23 + 0.03 rows) + 30 per partial row.
+// Replaced by a measured table through codec_plan_options.cost.
 const CostTable &builtin_cost_table()
 {
     static const CostTable t = {
-        {1, 16, 32, 64},
+        {1, 16, 32, 64, 128, 256},
         {32, 256, 1024, 4096, 16384, 65536},
-        {4576, 14947, 50506, 192739, 761674, 3037411,
-         6145, 17524, 56539, 212596, 836827, 3333748,
-         7819, 20273, 62974, 233777, 916990, 3649841,
-         11166, 25771, 75844, 276139, 1077316, 4282027}};
+        {3266, 8425, 26112, 96860, 379853, 1511824,
+         3731, 8990, 27023, 99154, 387676, 1541765,
+         4226, 9593, 27995, 101600, 396020, 1573702,
+         5217, 10799, 29938, 106492, 412709, 1637577,
+         7198, 13211, 33824, 116276, 446086, 1765326,
+         11161, 18034, 41596, 135845, 512841, 2020824}};
     return t;
 }
 
@@ -151,18 +153,18 @@ int build_plan(const codec_tree &tree, const codec_head_config &head,
     if (head.num_q_heads % head.num_kv_heads != 0) return CODEC_ERR_INVALID_ARGUMENT;
     if (head.head_dim != 128) return CODEC_ERR_UNSUPPORTED;
     if (head.dtype != CODEC_DTYPE_FP16 && head.dtype != CODEC_DTYPE_BF16) return CODEC_ERR_UNSUPPORTED;
-    if (head.page_size < 16 || head.page_size % 16 != 0) return CODEC_ERR_UNSUPPORTED;
+    if (head.page_size < 16 || head.page_size > 4096 || (head.page_size & (head.page_size - 1)) != 0)
+        return CODEC_ERR_UNSUPPORTED;
     if (!(head.scale > 0.0f) || !(head.scale < 1e30f)) return CODEC_ERR_INVALID_ARGUMENT;
     const int32_t group = head.num_q_heads / head.num_kv_heads;
     if (group > 64) return CODEC_ERR_UNSUPPORTED;
 
-    const int32_t m = opt.num_slots > 0 ? opt.num_slots : std::max(1, 512 / head.num_kv_heads);
     const int32_t align = opt.split_align > 0 ? opt.split_align : std::max(256, head.page_size);
-    const int32_t max_rows = opt.max_rows > 0 ? opt.max_rows : 64;
+    const int32_t max_rows = opt.max_rows > 0 ? opt.max_rows : std::max(256, group);
     if (opt.num_slots < 0 || opt.split_align < 0 || opt.max_rows < 0) return CODEC_ERR_INVALID_ARGUMENT;
-    if (m > (1 << 20)) return CODEC_ERR_INVALID_ARGUMENT;
+    if (opt.num_slots > (1 << 20)) return CODEC_ERR_INVALID_ARGUMENT;
     if (align % 32 != 0 || align % head.page_size != 0) return CODEC_ERR_INVALID_ARGUMENT;
-    if (max_rows > 64 || max_rows < group) return CODEC_ERR_INVALID_ARGUMENT;
+    if (max_rows > 256 || max_rows < group) return CODEC_ERR_INVALID_ARGUMENT;
     if (opt.share != 0 && opt.share != 1) return CODEC_ERR_INVALID_ARGUMENT;
 
     CostTable user;
@@ -215,7 +217,6 @@ int build_plan(const codec_tree &tree, const codec_head_config &head,
 
     p.head = head;
     p.group = group;
-    p.num_slots = m;
     p.split_align = align;
     p.max_rows = max_rows;
     p.share = opt.share;
@@ -259,6 +260,13 @@ int build_plan(const codec_tree &tree, const codec_head_config &head,
         }
     }
     const size_t J = p.items.size();
+    // slots that run at once per KV head: tasks above 16 rows need the one-workgroup-per-CU kernel
+    // variant (256 CUs), otherwise two workgroups share a CU
+    int32_t widest = 0;
+    for (const codec_item &it : p.items) widest = std::max(widest, it.rows);
+    const int32_t m = opt.num_slots > 0 ? opt.num_slots
+                                        : std::max(1, (widest > 16 ? 256 : 512) / head.num_kv_heads);
+    p.num_slots = m;
     std::vector<int64_t> max_b(J);
     for (size_t j = 0; j < J; ++j) max_b[j] = ceil_div(p.items[j].len, align);
 

@@ -50,18 +50,19 @@ def test_create_ok_and_sizes():
     (HeadConfig(8, 2, 64), C.CODEC_ERR_UNSUPPORTED),
     (HeadConfig(8, 2, 128, dtype=2), C.CODEC_ERR_UNSUPPORTED),
     (HeadConfig(8, 2, 128, page_size=24), C.CODEC_ERR_UNSUPPORTED),
+    (HeadConfig(8, 2, 128, page_size=48), C.CODEC_ERR_UNSUPPORTED),
     (HeadConfig(8, 3, 128), C.CODEC_ERR_INVALID_ARGUMENT),
     (HeadConfig(130, 1, 128), C.CODEC_ERR_UNSUPPORTED),
     (HeadConfig(8, 2, 128, scale=-1.0), C.CODEC_ERR_INVALID_ARGUMENT),
 ])
 def test_bad_head_configs(head, status):
-    good = HeadConfig(8, 2, 128, page_size=head.page_size if head.page_size % 16 == 0 else 16)
+    good = HeadConfig(8, 2, 128, page_size=head.page_size if head.page_size in (16, 32, 64) else 16)
     paged = build_paged_kv(two_level_forest(100, [20, 30]), good, seed=1)
     assert _create(head=head, paged=paged)[0] == status
 
 
 @pytest.mark.parametrize("kw", [dict(num_slots=-1), dict(split_align=48), dict(split_align=16),
-                                dict(max_rows=65), dict(max_rows=2), dict(share=2),
+                                dict(max_rows=257), dict(max_rows=2), dict(share=2),
                                 dict(cost_table=([1, 1], [10], [[1], [2]])),
                                 dict(cost_table=([1], [10, 5], [[1, 2]])),
                                 dict(cost_table=([1], [10], [[0]]))])

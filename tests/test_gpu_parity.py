@@ -81,10 +81,10 @@ def test_head_layouts(hq, hkv):
     check(w, share=0)
 
 
-@pytest.mark.parametrize("max_rows", [8, 16, 32, 48, 64])
+@pytest.mark.parametrize("max_rows", [8, 16, 32, 48, 64, 100, 128, 200, 256])
 def test_row_tiles(max_rows):
-    """40 requests x group 4 = 160 rows under the root: 1-, 2- and 4-tile register variants, row tiling."""
-    f = two_level_forest(300, [7 + (i % 5) for i in range(40)])
+    """70 requests x group 4 = 280 rows under the root: stream and dense task shapes, row tiling."""
+    f = two_level_forest(300, [7 + (i % 5) for i in range(70)])
     w = make_workload(f"rows{max_rows}", f, HeadConfig(16, 4, 128, DTYPE_BF16), seed=12, poison=True)
     _, view = check(w, max_rows=max_rows)
     assert max(t["n_req"] * 4 for t in view["tasks"]) <= max_rows

@@ -86,8 +86,8 @@ FORESTS = {
 @pytest.mark.parametrize("name", sorted(FORESTS))
 @pytest.mark.parametrize("share", [True, False])
 @pytest.mark.parametrize("m,align,max_rows,hq,hkv,table", [
-    (8, 256, 64, 32, 8, "table2"), (3, 32, 16, 8, 1, "default"), (64, 64, 64, 8, 8, "table2"),
-    (17, 32, 7, 28, 4, "default")])
+    (8, 256, 64, 32, 8, "table2"), (3, 32, 16, 8, 1, "default"), (64, 64, 256, 8, 8, "table2"),
+    (17, 32, 7, 28, 4, "default"), (32, 256, 130, 64, 8, "default")])
 def test_library_plan_equals_rederivation(name, share, m, align, max_rows, hq, hkv, table):
     f = FORESTS[name]()
     head = HeadConfig(hq, hkv, 128)
@@ -103,6 +103,10 @@ def test_measured_configurations_with_library_defaults(name, share):
     """Full-size forests of the measured configurations, default options of the library."""
     f, head = config_forest(name), config_head(name)
     view = _lib_plan(f, head, 0, 0, 0, share, None)
-    ref = P.plan(f.parent, f.node_len, f.req_node, head.group, 512 // head.num_kv_heads, 256, 64,
-                 share, _default_table())
+    # library defaults: 256-token alignment, row tiles of 256, and as many slots as workgroups that
+    # run at once (one per CU if any task holds more than 16 rows, else two)
+    widest = max(it["rows"] for it in view["items"])
+    m = (256 if widest > 16 else 512) // head.num_kv_heads
+    assert view["num_slots"] == m
+    ref = P.plan(f.parent, f.node_len, f.req_node, head.group, m, 256, 256, share, _default_table())
     _compare(view, ref)
