@@ -20,10 +20,10 @@
 // Softmax statistics stay in fp32, in log2 units.
 //
 // Two task shapes share that arithmetic:
-//  * up to 32 rows ("stream"): the four waves take interleaved 32-token blocks
-//    of the slice, each with all rows; K and V go from HBM straight to registers
-//    (no LDS in the loop); the waves' states are merged through LDS at the end.
-//  * 33..256 rows ("dense"): the waves split the rows (up to 64 each) and walk
+//  * up to 16 rows ("stream"): the waves take interleaved 32-token blocks of the
+//    slice, each with all rows; K and V go from HBM straight to registers (no LDS
+//    in the loop); the waves' states are merged through LDS at the end.
+//  * 17..256 rows ("dense"): eight waves split the rows (up to 32 each) and walk
 //    the slice together; blocks are copied HBM -> LDS asynchronously into a ring of
 //    eight 16 KB slots (seven blocks in flight, one barrier per block) and read by
 //    all waves.
@@ -39,10 +39,12 @@ typedef __attribute__((ext_vector_type(8))) _Float16 f16x8;
 typedef __attribute__((ext_vector_type(4))) float f32x4;
 typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;
 
-constexpr int kWaves = 4;
-constexpr int kThreads = kWaves * 64;
 constexpr int kHeadDim = 128;
-constexpr int kMergeBytes = (2 * 8 * 64 * 4 + 2 * 64 * 2) * 4;      // stream-path merge of a 32-row state
+constexpr int kNarrowWaves = 4;     // stream-only kernel variant: 4 waves, two workgroups per CU
+constexpr int kWideWaves = 8;       // all task shapes: 8 waves (two per SIMD), one workgroup per CU
+constexpr int kMergeWaves = 4;      // reduction kernel
+// LDS for merging the waves' states at the end of a stream task: W/2 states of NT row tiles
+constexpr int merge_bytes(int waves, int nt) { return (waves / 2) * (nt * 8 * 64 * 4 + nt * 64 * 2) * 4; }
 
 template <int DT>
 __device__ __forceinline__ f32x4 mfma16(u32x4 a, u32x4 b, f32x4 c)
@@ -150,9 +152,17 @@ struct RowState {
     }
 };
 
-// Online softmax update and O^T += V^T P^T for one block of NT row tiles, straight-line code apart
-// from two wave-uniform branches (ragged tail, rescale).  `s` are raw scores (tokens past `valid`
-// are masked here), `v` the block's V rows in the lane map described above.
+// Online softmax update and O^T += V^T P^T for one block of NT row tiles.
+//
+// The reference m of a row (the value subtracted before exponentiation) is allowed to lag behind the
+// row's true running maximum by up to kLag (log2 units): softmax is invariant to the reference, and
+// with the lag bounded every exponential stays <= 2^kLag, well inside fp16/bf16 and fp32 range.  A
+// block therefore only needs each lane's own maximum over its 8 scores and one wave-wide vote; the
+// cross-lane maximum and the rescaling of the accumulators run only when some row's scores outgrow
+// the lag (always on a wave's first block, rarely afterwards).  `s` are raw scores (tokens past
+// `valid` are masked here), `v` the block's V rows in the lane map described above.
+constexpr float kLag = 8.f;
+
 template <int DT, int NT>
 __device__ __forceinline__ void softmax_pv(f32x4 (&s)[2][NT], u32x4 (&v)[8], RowState<NT> &st,
                                            int valid, int grp, float scale_log2e)
@@ -170,28 +180,40 @@ __device__ __forceinline__ void softmax_pv(f32x4 (&s)[2][NT], u32x4 (&v)[8], Row
             }
     }
 
-    u32x4 pb[NT];
+    float lane_max[NT];
+    bool outgrown = false;
 #pragma unroll
     for (int nt = 0; nt < NT; ++nt) {
-        float mx = fmaxf(fmaxf(fmaxf(s[0][nt][0], s[0][nt][1]), fmaxf(s[0][nt][2], s[0][nt][3])),
-                         fmaxf(fmaxf(s[1][nt][0], s[1][nt][1]), fmaxf(s[1][nt][2], s[1][nt][3])));
-        mx = fmaxf(mx, __shfl_xor(mx, 16));
-        mx = fmaxf(mx, __shfl_xor(mx, 32));
-        const float m_new = fmaxf(st.m[nt], mx * scale_log2e);
-        if (__any(m_new > st.m[nt])) {          // rescale only when some row's maximum moved
-            const float alpha = fast_exp2(st.m[nt] - m_new);
+        lane_max[nt] = fmaxf(fmaxf(fmaxf(s[0][nt][0], s[0][nt][1]), fmaxf(s[0][nt][2], s[0][nt][3])),
+                             fmaxf(fmaxf(s[1][nt][0], s[1][nt][1]), fmaxf(s[1][nt][2], s[1][nt][3])))
+                       * scale_log2e;
+        outgrown |= lane_max[nt] > st.m[nt] + kLag;
+    }
+    if (__any(outgrown)) {
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt) {
+            float mx = lane_max[nt];
+            mx = fmaxf(mx, __shfl_xor(mx, 16));
+            mx = fmaxf(mx, __shfl_xor(mx, 32));
+            const float m_new = fmaxf(st.m[nt], mx);
+            const float alpha = fast_exp2(st.m[nt] - m_new);       // 0 on the first block (m = -inf)
             st.l[nt] *= alpha;
 #pragma unroll
             for (int dt = 0; dt < 8; ++dt) st.o[nt][dt] *= alpha;
             st.m[nt] = m_new;
         }
+    }
+
+    u32x4 pb[NT];
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt) {
         float p[2][4];
         float sum = 0.f;
 #pragma unroll
         for (int j = 0; j < 2; ++j)
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
-                p[j][e] = fast_exp2(__builtin_fmaf(s[j][nt][e], scale_log2e, -m_new));
+                p[j][e] = fast_exp2(__builtin_fmaf(s[j][nt][e], scale_log2e, -st.m[nt]));
                 sum += p[j][e];
             }
         st.l[nt] += sum;
@@ -275,8 +297,8 @@ __device__ __forceinline__ SliceCtx make_ctx(const PacParams &P, const DevTask &
 // (keeps "-inf minus -inf" of a wave that saw no token out of the arithmetic).
 __device__ __forceinline__ float weight(float a, float m) { return a == m ? 1.f : fast_exp2(a - m); }
 
-// ---- stream path: rows <= 16*NT (NT = 1, 2), waves split the tokens ----------------------------------------------
-template <int DT, int NT>
+// ---- stream path: rows <= 16*NT (NT = 1 in use), the W waves split the tokens ---------------------
+template <int DT, int NT, int W>
 __device__ void run_stream(const PacParams &P, const DevTask &t, int head, char *lds_raw)
 {
     const int lane = threadIdx.x & 63;
@@ -313,12 +335,12 @@ __device__ void run_stream(const PacParams &P, const DevTask &t, int head, char 
     int tb = wave;
     if (tb < nblk) load_block(c, tb, koff, voff, ra);
     while (tb < nblk) {
-        int nb = tb + kWaves;
+        int nb = tb + W;
         if (nb < nblk) load_block(c, nb, koff, voff, rb);
         compute(tb, ra);
         tb = nb;
         if (tb >= nblk) break;
-        nb = tb + kWaves;
+        nb = tb + W;
         if (nb < nblk) load_block(c, nb, koff, voff, ra);
         compute(tb, rb);
         tb = nb;
@@ -330,34 +352,37 @@ __device__ void run_stream(const PacParams &P, const DevTask &t, int head, char 
         st.l[nt] += __shfl_xor(st.l[nt], 32);
     }
 
-    // merge the four waves: wave w hands its state to wave w-1 through LDS, 3 -> 2 -> 1 -> 0
+    // merge the waves' states pairwise through LDS: waves [h, 2h) hand theirs to waves [0, h), h = W/2 .. 1
+    constexpr int kState = NT * 8 * 64 * 4 + NT * 64 * 2;              // floats per handed-over state
     float *lds = reinterpret_cast<float *>(lds_raw);
-    f32x4 *lds_o = reinterpret_cast<f32x4 *>(lds);                     // [NT][8][64]
-    float *lds_m = lds + NT * 8 * 64 * 4;                               // [NT][64]
-    float *lds_l = lds_m + NT * 64;
 #pragma unroll 1
-    for (int src = kWaves - 1; src >= 1; --src) {
-        if (wave == src) {
+    for (int h = W / 2; h >= 1; h >>= 1) {
+        if (wave >= h && wave < 2 * h) {
+            float *base = lds + (wave - h) * kState;
+            f32x4 *lo = reinterpret_cast<f32x4 *>(base);                // [NT][8][64]
 #pragma unroll
             for (int nt = 0; nt < NT; ++nt) {
 #pragma unroll
-                for (int dt = 0; dt < 8; ++dt) lds_o[(nt * 8 + dt) * 64 + lane] = st.o[nt][dt];
-                lds_m[nt * 64 + lane] = st.m[nt];
-                lds_l[nt * 64 + lane] = st.l[nt];
+                for (int dt = 0; dt < 8; ++dt) lo[(nt * 8 + dt) * 64 + lane] = st.o[nt][dt];
+                base[NT * 8 * 64 * 4 + nt * 64 + lane] = st.m[nt];
+                base[NT * 8 * 64 * 4 + NT * 64 + nt * 64 + lane] = st.l[nt];
             }
         }
         __syncthreads();
-        if (wave == src - 1) {
+        if (wave < h) {
+            const float *base = lds + wave * kState;
+            const f32x4 *lo = reinterpret_cast<const f32x4 *>(base);
 #pragma unroll
             for (int nt = 0; nt < NT; ++nt) {
-                const float m2 = lds_m[nt * 64 + lane], l2 = lds_l[nt * 64 + lane];
+                const float m2 = base[NT * 8 * 64 * 4 + nt * 64 + lane];
+                const float l2 = base[NT * 8 * 64 * 4 + NT * 64 + nt * 64 + lane];
                 const float mm = fmaxf(st.m[nt], m2);
                 const float a = weight(st.m[nt], mm), b = weight(m2, mm);
                 st.l[nt] = st.l[nt] * a + l2 * b;
                 st.m[nt] = mm;
 #pragma unroll
                 for (int dt = 0; dt < 8; ++dt)
-                    st.o[nt][dt] = st.o[nt][dt] * a + lds_o[(nt * 8 + dt) * 64 + lane] * b;
+                    st.o[nt][dt] = st.o[nt][dt] * a + lo[(nt * 8 + dt) * 64 + lane] * b;
             }
         }
         __syncthreads();
@@ -365,7 +390,7 @@ __device__ void run_stream(const PacParams &P, const DevTask &t, int head, char 
     if (wave == 0) store_partial<NT>(P, t, head, 0, rows, l16, grp, st);
 }
 
-// ---- dense path: 33..256 rows, waves split the rows and share each staged block ------------------
+// ---- dense path: 17..256 rows, the 8 waves split the rows (up to 32 each) and share each block ----
 //
 // Blocks travel HBM -> LDS without passing through registers (global_load_lds_dwordx4: every lane
 // moves 16 bytes, a wave fills 1 KB of consecutive LDS).  A ring of kRing block slots (16 KB each:
@@ -375,8 +400,8 @@ __device__ void run_stream(const PacParams &P, const DevTask &t, int head, char 
 // applied on the global side: the lane that fills LDS column c of row r fetches column c ^ (r & 15).
 //
 // The compiler does not see these loads (inline asm), so the waits are explicit: loads complete in
-// issue order, block b is in LDS once at most 4 * (blocks issued after b) of the wave's loads are
-// outstanding, and the barrier that follows publishes all four waves' parts.
+// issue order, block b is in LDS once at most 2 * (blocks issued after b) of the wave's loads are
+// outstanding, and the barrier that follows publishes all eight waves' parts.
 constexpr int kRing = 8;
 constexpr int kBlockBytes = 16384;
 constexpr int kRingBytes = kRing * kBlockBytes;
@@ -395,7 +420,7 @@ __device__ __forceinline__ void dma16(uint32_t lds_addr, uint32_t voff, const ch
 }
 
 // One wave's share of a dense task: NL live row tiles starting at task row `row0` (NL = 0: the wave
-// only helps moving blocks).  All waves run the same number of barriers.
+// only helps moving blocks).  All eight waves run the same number of barriers.
 template <int DT, int NL>
 __device__ __forceinline__ void dense_wave(const PacParams &P, const DevTask &t, int head, char *lds,
                                            int wave, int row0, int rows)
@@ -417,24 +442,17 @@ __device__ __forceinline__ void dense_wave(const PacParams &P, const DevTask &t,
     __builtin_amdgcn_s_waitcnt(0x0F70);
     const SliceCtx c = make_ctx(P, t, head);
 
-    // wave w moves rows 8w .. 8w+7 of every block: two 1 KB pieces of K and two of V
+    // wave w moves rows 4w .. 4w+3 of every block: one 1 KB piece of K and one of V
     const uint32_t lds_base = uint32_t(uintptr_t(lds));
-    uint32_t voff[2];
-#pragma unroll
-    for (int i = 0; i < 2; ++i) {
-        const int key = ((wave & 1) * 8 + 4 * i + grp) & 15;           // destination row & 15
-        voff[i] = uint32_t(4 * i + grp) * c.token_bytes + uint32_t((l16 ^ key) << 4);
-    }
+    const int key = (wave * 4 + grp) & 15;                              // destination row & 15
+    const uint32_t voff = uint32_t(grp) * c.token_bytes + uint32_t((l16 ^ key) << 4);
     auto dma_block = [&](int bb) {
-        int tok0 = bb * 32 + wave * 8;
+        int tok0 = bb * 32 + wave * 4;
         if (tok0 >= c.kv_len) tok0 = 0;                                 // nothing of the group is live
         const int64_t off = tile_offset(c, tok0 & ~15) + int64_t(tok0 & 15) * c.token_bytes;
-        const uint32_t slot = lds_base + uint32_t(bb % kRing) * kBlockBytes + uint32_t(wave) * 2048;
-#pragma unroll
-        for (int i = 0; i < 2; ++i) {
-            dma16(slot + i * 1024, voff[i], c.k_head + off);
-            dma16(slot + 8192 + i * 1024, voff[i], c.v_head + off);
-        }
+        const uint32_t slot = lds_base + uint32_t(bb % kRing) * kBlockBytes + uint32_t(wave) * 1024;
+        dma16(slot, voff, c.k_head + off);
+        dma16(slot + 8192, voff, c.v_head + off);
     };
     // lane-dependent parts of the operand addresses (the slot base is added per block)
     uint32_t ka_off[4], va_off[4];
@@ -450,9 +468,9 @@ __device__ __forceinline__ void dense_wave(const PacParams &P, const DevTask &t,
         if (d < nblk) dma_block(d);
 #pragma unroll 1
     for (int b = 0; b < nblk; ++b) {
-        // block b has landed once at most 4 loads per block issued after it are outstanding; near the
+        // block b has landed once at most 2 loads per block issued after it are outstanding; near the
         // end of the slice no new loads were issued, so wait for everything
-        if (nblk - 1 - b >= kRing - 2) __builtin_amdgcn_s_waitcnt(0x4F78);     // vmcnt(24)
+        if (nblk - 1 - b >= kRing - 2) __builtin_amdgcn_s_waitcnt(0x0F7C);     // vmcnt(12)
         else                           __builtin_amdgcn_s_waitcnt(0x0F70);     // vmcnt(0)
         __syncthreads();                    // block b is complete; everyone is done with block b-1
         if (b + kRing - 1 < nblk) dma_block(b + kRing - 1);            // refills the slot of block b-1
@@ -497,25 +515,25 @@ __device__ void run_dense(const PacParams &P, const DevTask &t, int head, char *
 {
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int rows = t.n_req * P.group;
-    const int tiles_per_wave = (rows + 63) >> 6;                        // ceil(rows / 64) row tiles of 16
+    const int tiles_per_wave = (rows + 127) >> 7;                       // ceil(rows / 128) row tiles of 16
     const int row0 = wave * tiles_per_wave * 16;
     int live = (rows - row0 + 15) >> 4;
     live = live < 0 ? 0 : (live > tiles_per_wave ? tiles_per_wave : live);
     switch (live) {
     case 0: dense_wave<DT, 0>(P, t, head, lds, wave, row0, rows); break;
     case 1: dense_wave<DT, 1>(P, t, head, lds, wave, row0, rows); break;
-    case 2: dense_wave<DT, 2>(P, t, head, lds, wave, row0, rows); break;
-    case 3: dense_wave<DT, 3>(P, t, head, lds, wave, row0, rows); break;
-    default: dense_wave<DT, 4>(P, t, head, lds, wave, row0, rows); break;
+    default: dense_wave<DT, 2>(P, t, head, lds, wave, row0, rows); break;
     }
 }
 
 extern __shared__ __attribute__((aligned(16))) char dyn_lds[];      // WIDE: kRingBytes of dynamic LDS
 
 template <int DT, int WIDE>
-__global__ void __launch_bounds__(kThreads, WIDE ? 1 : 2) pac_kernel(const PacParams P)
+__global__ void __launch_bounds__(WIDE ? kWideWaves * 64 : kNarrowWaves * 64, 2) pac_kernel(const PacParams P)
 {
-    __shared__ __attribute__((aligned(16))) char static_lds[WIDE ? 16 : kMergeBytes];
+    constexpr int W = WIDE ? kWideWaves : kNarrowWaves;
+    static_assert(merge_bytes(kWideWaves, 1) <= kRingBytes, "stream merge must fit in the ring");
+    __shared__ __attribute__((aligned(16))) char static_lds[WIDE ? 16 : merge_bytes(kNarrowWaves, 1)];
     char *lds = WIDE ? dyn_lds : static_lds;
     const int head = blockIdx.x % P.h_kv;
     const int slot = blockIdx.x / P.h_kv;
@@ -525,12 +543,9 @@ __global__ void __launch_bounds__(kThreads, WIDE ? 1 : 2) pac_kernel(const PacPa
         const DevTask t = P.tasks[P.slot_tasks[i]];
         const int rows = t.n_req * P.group;
         if (rows <= 16) {
-            run_stream<DT, 1>(P, t, head, lds);
+            run_stream<DT, 1, W>(P, t, head, lds);
         } else if constexpr (WIDE != 0) {
-            if (rows <= 32)
-                run_stream<DT, 2>(P, t, head, lds);
-            else
-                run_dense<DT>(P, t, head, lds);
+            run_dense<DT>(P, t, head, lds);
         }
     }
 }
@@ -538,10 +553,10 @@ __global__ void __launch_bounds__(kThreads, WIDE ? 1 : 2) pac_kernel(const PacPa
 // Partial output reduction (Alg. 3), n-ary: one wave per (request, query head) folds the request's
 // partials in list order; each lane owns two channels.
 template <int DT>
-__global__ void __launch_bounds__(kThreads) merge_kernel(const MergeParams P)
+__global__ void __launch_bounds__(kMergeWaves * 64) merge_kernel(const MergeParams P)
 {
     const int lane = threadIdx.x & 63;
-    const int row = blockIdx.x * kWaves + (threadIdx.x >> 6);
+    const int row = blockIdx.x * kMergeWaves + (threadIdx.x >> 6);
     if (row >= P.num_requests * P.h_q) return;
     const int r = row / P.h_q, hq = row - r * P.h_q;
     const int head = hq / P.group, hj = hq - head * P.group;
@@ -576,9 +591,9 @@ int allow_ring_lds(K kernel)
 
 int launch_pac(const PacParams &p, int dtype, int num_slots, int max_rows_in_plan, void *stream)
 {
-    const dim3 grid(unsigned(num_slots) * unsigned(p.h_kv)), block(kThreads);
-    hipStream_t s = static_cast<hipStream_t>(stream);
     const bool wide = max_rows_in_plan > 16;
+    const dim3 grid(unsigned(num_slots) * unsigned(p.h_kv)), block((wide ? kWideWaves : kNarrowWaves) * 64);
+    hipStream_t s = static_cast<hipStream_t>(stream);
     if (wide) {
         auto k16 = pac_kernel<CODEC_DTYPE_FP16, 1>;
         auto kbf = pac_kernel<CODEC_DTYPE_BF16, 1>;
@@ -595,7 +610,7 @@ int launch_pac(const PacParams &p, int dtype, int num_slots, int max_rows_in_pla
 int launch_merge(const MergeParams &p, int dtype, void *stream)
 {
     const int rows = p.num_requests * p.h_q;
-    const dim3 grid(unsigned((rows + kWaves - 1) / kWaves)), block(kThreads);
+    const dim3 grid(unsigned((rows + kMergeWaves - 1) / kMergeWaves)), block(kMergeWaves * 64);
     hipStream_t s = static_cast<hipStream_t>(stream);
     if (dtype == CODEC_DTYPE_FP16) hipLaunchKernelGGL((merge_kernel<CODEC_DTYPE_FP16>), grid, block, 0, s, p);
     else                           hipLaunchKernelGGL((merge_kernel<CODEC_DTYPE_BF16>), grid, block, 0, s, p);
