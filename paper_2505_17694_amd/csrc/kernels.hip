@@ -137,8 +137,11 @@ __device__ __forceinline__ void load_block(const SliceCtx &c, int tb, uint32_t k
 template <int NT>
 struct RowState {
     f32x4 o[NT][8];     // [row tile][dt]: row = 16*nt + lane%16, channel = 32*(lane/16) + 8*e + dt
-    float m[NT];        // running maximum, log2 units (same in the 4 lanes that share a row)
-    float l[NT];        // this lane's share of the running sum of exponentials
+    f32x4 lsum[NT];     // row sum of exponentials, accumulated by the matrix unit against an all-ones
+                        // A operand: four equal copies per lane, complete over all 32 tokens of a block
+    float m[NT];        // reference subtracted before exponentiation, log2 units (same in the 4 lanes
+                        // that share a row)
+    float l[NT];        // final row sum, filled by finish()
 
     __device__ __forceinline__ void clear()
     {
@@ -146,92 +149,167 @@ struct RowState {
         for (int nt = 0; nt < NT; ++nt) {
             m[nt] = -INFINITY;
             l[nt] = 0.f;
+            lsum[nt] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
             for (int dt = 0; dt < 8; ++dt) o[nt][dt] = f32x4{0.f, 0.f, 0.f, 0.f};
         }
     }
-};
-
-// Online softmax update and O^T += V^T P^T for one block of NT row tiles.
-//
-// The reference m of a row (the value subtracted before exponentiation) is allowed to lag behind the
-// row's true running maximum by up to kLag (log2 units): softmax is invariant to the reference, and
-// with the lag bounded every exponential stays <= 2^kLag, well inside fp16/bf16 and fp32 range.  A
-// block therefore only needs each lane's own maximum over its 8 scores and one wave-wide vote; the
-// cross-lane maximum and the rescaling of the accumulators run only when some row's scores outgrow
-// the lag (always on a wave's first block, rarely afterwards).  `s` are raw scores (tokens past
-// `valid` are masked here), `v` the block's V rows in the lane map described above.
-constexpr float kLag = 8.f;
-
-template <int DT, int NT>
-__device__ __forceinline__ void softmax_pv(f32x4 (&s)[2][NT], u32x4 (&v)[8], RowState<NT> &st,
-                                           int valid, int grp, float scale_log2e)
-{
-    if (valid < 32) {
-#pragma unroll
-        for (int j = 0; j < 2; ++j)
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                const bool dead = j * 16 + grp * 4 + e >= valid;
-#pragma unroll
-                for (int c = 0; c < 4; ++c) v[j * 4 + e][c] = dead ? 0u : v[j * 4 + e][c];
-#pragma unroll
-                for (int nt = 0; nt < NT; ++nt) s[j][nt][e] = dead ? -INFINITY : s[j][nt][e];
-            }
-    }
-
-    float lane_max[NT];
-    bool outgrown = false;
-#pragma unroll
-    for (int nt = 0; nt < NT; ++nt) {
-        lane_max[nt] = fmaxf(fmaxf(fmaxf(s[0][nt][0], s[0][nt][1]), fmaxf(s[0][nt][2], s[0][nt][3])),
-                             fmaxf(fmaxf(s[1][nt][0], s[1][nt][1]), fmaxf(s[1][nt][2], s[1][nt][3])))
-                       * scale_log2e;
-        outgrown |= lane_max[nt] > st.m[nt] + kLag;
-    }
-    if (__any(outgrown)) {
+    // MSUM: the row sums were accumulated by the matrix unit; otherwise each lane summed its own 8
+    // tokens per block and the four lanes of a row are added up here.
+    template <bool MSUM>
+    __device__ __forceinline__ void finish()
+    {
 #pragma unroll
         for (int nt = 0; nt < NT; ++nt) {
-            float mx = lane_max[nt];
-            mx = fmaxf(mx, __shfl_xor(mx, 16));
-            mx = fmaxf(mx, __shfl_xor(mx, 32));
-            const float m_new = fmaxf(st.m[nt], mx);
-            const float alpha = fast_exp2(st.m[nt] - m_new);       // 0 on the first block (m = -inf)
-            st.l[nt] *= alpha;
-#pragma unroll
-            for (int dt = 0; dt < 8; ++dt) st.o[nt][dt] *= alpha;
-            st.m[nt] = m_new;
+            if constexpr (MSUM) {
+                l[nt] = lsum[nt][0];
+            } else {
+                l[nt] += __shfl_xor(l[nt], 16);
+                l[nt] += __shfl_xor(l[nt], 32);
+            }
         }
     }
+};
 
-    u32x4 pb[NT];
+// ---- one 32-token block of online softmax, in pieces so that callers can interleave them ---------
+//
+// The reference m of a row is allowed to lag behind the row's true running maximum by up to kLag
+// (log2 units): softmax is invariant to the reference, and with the lag bounded every exponential
+// stays <= 2^kLag, well inside fp16/bf16 and fp32 range.  A block therefore only needs each lane's own
+// maximum over its 8 scores and one wave-wide vote; the cross-lane maximum and the rescaling of the
+// accumulators run only when some row's scores outgrow the lag (always on a wave's first block,
+// rarely afterwards).
+constexpr float kLag = 8.f;
+
+// Scores of tokens past `valid` become -inf (ragged last block of a slice).
+template <int NT>
+__device__ __forceinline__ void mask_scores(f32x4 (&s)[2][NT], int valid, int grp)
+{
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const bool dead = j * 16 + grp * 4 + e >= valid;
+#pragma unroll
+            for (int nt = 0; nt < NT; ++nt) s[j][nt][e] = dead ? -INFINITY : s[j][nt][e];
+        }
+}
+
+// V rows of tokens past `valid` count as zero (their memory may hold anything).
+__device__ __forceinline__ void mask_values(u32x4 (&v)[8], int valid, int grp)
+{
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+        const bool dead = (e >> 2) * 16 + grp * 4 + (e & 3) >= valid;
+#pragma unroll
+        for (int c = 0; c < 4; ++c) v[e][c] = dead ? 0u : v[e][c];
+    }
+}
+
+// Each lane's maximum over its 8 scores per row tile, in log2 units.
+template <int NT>
+__device__ __forceinline__ void lane_maxima(const f32x4 (&s)[2][NT], float scale_log2e, float (&lm)[NT])
+{
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt) {
+        float a = fmaxf(fmaxf(s[0][nt][0], s[0][nt][1]), s[0][nt][2]);
+        a = fmaxf(fmaxf(a, s[0][nt][3]), s[1][nt][0]);
+        a = fmaxf(fmaxf(a, s[1][nt][1]), s[1][nt][2]);
+        lm[nt] = fmaxf(a, s[1][nt][3]) * scale_log2e;
+    }
+}
+
+template <int NT>
+__device__ __forceinline__ bool outgrown(const float (&lm)[NT], const RowState<NT> &st)
+{
+    bool any = false;
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt) any |= lm[nt] > st.m[nt] + kLag;
+    return any;
+}
+
+// Move every row's reference up to its true running maximum and rescale its accumulators.
+template <int NT>
+__device__ __forceinline__ void raise_reference(const float (&lm)[NT], RowState<NT> &st)
+{
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt) {
+        float mx = lm[nt];
+        mx = fmaxf(mx, __shfl_xor(mx, 16));
+        mx = fmaxf(mx, __shfl_xor(mx, 32));
+        const float m_new = fmaxf(st.m[nt], mx);
+        const float alpha = fast_exp2(st.m[nt] - m_new);       // 0 on the first block (m = -inf)
+        st.lsum[nt] *= alpha;
+        st.l[nt] *= alpha;
+#pragma unroll
+        for (int dt = 0; dt < 8; ++dt) st.o[nt][dt] *= alpha;
+        st.m[nt] = m_new;
+    }
+}
+
+// P = exp2(scale * S - m), rounded to 16 bits in B-operand layout.  With VSUM the lane also adds its
+// 8 exponentials to its share of the row sum.
+template <int DT, int NT, bool VSUM>
+__device__ __forceinline__ void probabilities(const f32x4 (&s)[2][NT], RowState<NT> &st,
+                                              float scale_log2e, u32x4 (&pb)[NT])
+{
 #pragma unroll
     for (int nt = 0; nt < NT; ++nt) {
         float p[2][4];
-        float sum = 0.f;
 #pragma unroll
         for (int j = 0; j < 2; ++j)
 #pragma unroll
-            for (int e = 0; e < 4; ++e) {
+            for (int e = 0; e < 4; ++e)
                 p[j][e] = fast_exp2(__builtin_fmaf(s[j][nt][e], scale_log2e, -st.m[nt]));
-                sum += p[j][e];
-            }
-        st.l[nt] += sum;
+        if constexpr (VSUM)
+            st.l[nt] += ((p[0][0] + p[0][1]) + (p[0][2] + p[0][3])) + ((p[1][0] + p[1][1]) + (p[1][2] + p[1][3]));
         pb[nt] = u32x4{pack2<DT>(p[0][0], p[0][1]), pack2<DT>(p[0][2], p[0][3]),
                        pack2<DT>(p[1][0], p[1][1]), pack2<DT>(p[1][2], p[1][3])};
     }
+}
 
-    // 8x8 transpose inside the lane: v[e] holds 8 channels of token e, va holds 8 tokens of channel dt
+// Row sums += 1^T P^T on the matrix unit (an all-ones A operand: every output row is the column sum).
+template <int DT, int NT>
+__device__ __forceinline__ void accumulate_row_sums(const u32x4 (&pb)[NT], RowState<NT> &st)
+{
+    constexpr unsigned int one2 = DT == CODEC_DTYPE_FP16 ? 0x3C003C00u : 0x3F803F80u;
+    const u32x4 ones = {one2, one2, one2, one2};
 #pragma unroll
-    for (int dt = 0; dt < 8; ++dt) {
-        const unsigned int sel = (dt & 1) ? 0x07060302u : 0x05040100u;
+    for (int nt = 0; nt < NT; ++nt) st.lsum[nt] = mfma16<DT>(ones, pb[nt], st.lsum[nt]);
+}
+
+// O^T += V^T P^T for the channel tiles dt = 4*HALF .. 4*HALF+3.  `vh[e]` holds dwords 2*HALF and
+// 2*HALF+1 (channels 4*HALF .. 4*HALF+3 of the lane's 8) of token e's V row piece; the 16-bit
+// transpose inside each lane turns them into A operands.
+template <int DT, int NT, int HALF>
+__device__ __forceinline__ void accumulate_half(const unsigned int (&vh)[8][2], const u32x4 (&pb)[NT],
+                                                RowState<NT> &st)
+{
+#pragma unroll
+    for (int d = 0; d < 4; ++d) {
+        const int dt = 4 * HALF + d;
+        const unsigned int sel = (d & 1) ? 0x07060302u : 0x05040100u;
         u32x4 va;
 #pragma unroll
         for (int k = 0; k < 4; ++k)
-            va[k] = __builtin_amdgcn_perm(v[2 * k + 1][dt >> 1], v[2 * k][dt >> 1], sel);
+            va[k] = __builtin_amdgcn_perm(vh[2 * k + 1][d >> 1], vh[2 * k][d >> 1], sel);
 #pragma unroll
         for (int nt = 0; nt < NT; ++nt) st.o[nt][dt] = mfma16<DT>(va, pb[nt], st.o[nt][dt]);
     }
+}
+
+// Same for a whole V row piece per token (16 bytes each) held in registers.
+template <int DT, int NT>
+__device__ __forceinline__ void accumulate(const u32x4 (&v)[8], const u32x4 (&pb)[NT], RowState<NT> &st)
+{
+    unsigned int lo[8][2], hi[8][2];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+        lo[e][0] = v[e][0]; lo[e][1] = v[e][1];
+        hi[e][0] = v[e][2]; hi[e][1] = v[e][3];
+    }
+    accumulate_half<DT, NT, 0>(lo, pb, st);
+    accumulate_half<DT, NT, 1>(hi, pb, st);
 }
 
 // Gather the wave's query rows (task rows row0 .. row0 + 16*NT) into B-operand registers.
@@ -326,7 +404,17 @@ __device__ void run_stream(const PacParams &P, const DevTask &t, int head, char 
                 for (int ks = 0; ks < 4; ++ks) acc = mfma16<DT>(r.k[j][ks], qb[nt][ks], acc);
                 s[j][nt] = acc;
             }
-        softmax_pv<DT, NT>(s, r.v, st, c.kv_len - tb * 32, grp, P.scale_log2e);
+        const int valid = c.kv_len - tb * 32;
+        if (valid < 32) {
+            mask_scores<NT>(s, valid, grp);
+            mask_values(r.v, valid, grp);
+        }
+        float lm[NT];
+        lane_maxima<NT>(s, P.scale_log2e, lm);
+        if (__any(outgrown<NT>(lm, st))) raise_reference<NT>(lm, st);
+        u32x4 pb[NT];
+        probabilities<DT, NT, true>(s, st, P.scale_log2e, pb);
+        accumulate<DT, NT>(r.v, pb, st);
     };
 
     // software pipeline: the loads of the wave's next block are in flight while it computes this one
@@ -346,11 +434,7 @@ __device__ void run_stream(const PacParams &P, const DevTask &t, int head, char 
         tb = nb;
     }
 
-#pragma unroll
-    for (int nt = 0; nt < NT; ++nt) {
-        st.l[nt] += __shfl_xor(st.l[nt], 16);
-        st.l[nt] += __shfl_xor(st.l[nt], 32);
-    }
+    st.template finish<false>();
 
     // merge the waves' states pairwise through LDS: waves [h, 2h) hand theirs to waves [0, h), h = W/2 .. 1
     constexpr int kState = NT * 8 * 64 * 4 + NT * 64 * 2;              // floats per handed-over state
@@ -425,7 +509,7 @@ template <int DT, int NL>
 __device__ __forceinline__ void dense_wave(const PacParams &P, const DevTask &t, int head, char *lds,
                                            int wave, int row0, int rows)
 {
-    static_assert(kRing - 2 == 6, "the steady-state wait below is for 6 blocks ahead");
+    static_assert(kRing == 8, "the waits below are written for a ring of 8 slots");
     const int lane = threadIdx.x & 63;
     const int l16 = lane & 15, grp = lane >> 4;
     constexpr int NQ = NL > 0 ? NL : 1;
@@ -461,51 +545,117 @@ __device__ __forceinline__ void dense_wave(const PacParams &P, const DevTask &t,
         ka_off[x] = uint32_t(l16 * 256 + (((x * 4 + grp) ^ l16) << 4));                 // k-step x
         va_off[x] = uint32_t(8192 + (grp * 4 + x) * 256 + ((l16 ^ (grp * 4 + x)) << 4)); // token 4*grp + x
     }
+    auto scores = [&](int bb, f32x4 (&s)[2][NQ]) {                      // S^T of block bb from its slot
+        const char *buf = lds + (bb % kRing) * kBlockBytes;
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+            u32x4 ka[4];
+#pragma unroll
+            for (int ks = 0; ks < 4; ++ks)
+                ka[ks] = *reinterpret_cast<const u32x4 *>(buf + j * 4096 + ka_off[ks]);
+#pragma unroll
+            for (int nt = 0; nt < NQ; ++nt) {
+                f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (int ks = 0; ks < 4; ++ks) acc = mfma16<DT>(ka[ks], qb[nt][ks], acc);
+                s[j][nt] = acc;
+            }
+        }
+    };
+    // half h (channels 4h .. 4h+3 of the lane's 8) of the V row pieces of block bb; tokens past `valid`
+    // count as zero
+    auto values = [&](int bb, int h, int valid, unsigned int (&vh)[8][2]) {
+        const char *buf = lds + (bb % kRing) * kBlockBytes + h * 8;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            const uint2 x = *reinterpret_cast<const uint2 *>(buf + (e >> 2) * 4096 + va_off[e & 3]);
+            const bool dead = (e >> 2) * 16 + grp * 4 + (e & 3) >= valid;
+            vh[e][0] = dead ? 0u : x.x;
+            vh[e][1] = dead ? 0u : x.y;
+        }
+    };
 
+    // Schedule.  The slots hold blocks b .. b+kRing-1 while block b is being worked on.  A step works on
+    // block b with its scores already in registers: behind one barrier it (1) refills the slot block
+    // b-1 has left, (2) computes the scores of block b+1 on the matrix unit while the vector unit turns
+    // the scores of block b into probabilities, and (3) accumulates block b.  The wait before the
+    // barrier is for block b+1: each wave issues 2 loads per block, loads complete in order, so block
+    // b+1 has landed once at most 2 * (blocks issued after it) loads are outstanding; when fewer than
+    // kRing-3 blocks were issued after it the wait is for everything.
     const int nblk = (t.kv_len + 31) >> 5;
 #pragma unroll 1
-    for (int d = 0; d < kRing - 1; ++d)
+    for (int d = 0; d < kRing; ++d)
         if (d < nblk) dma_block(d);
-#pragma unroll 1
-    for (int b = 0; b < nblk; ++b) {
-        // block b has landed once at most 2 loads per block issued after it are outstanding; near the
-        // end of the slice no new loads were issued, so wait for everything
-        if (nblk - 1 - b >= kRing - 2) __builtin_amdgcn_s_waitcnt(0x0F7C);     // vmcnt(12)
-        else                           __builtin_amdgcn_s_waitcnt(0x0F70);     // vmcnt(0)
-        __syncthreads();                    // block b is complete; everyone is done with block b-1
-        if (b + kRing - 1 < nblk) dma_block(b + kRing - 1);            // refills the slot of block b-1
-        if constexpr (NL > 0) {
-            const char *buf = lds + (b % kRing) * kBlockBytes;
-            f32x4 s[2][NL];
-#pragma unroll
-            for (int j = 0; j < 2; ++j) {
-                u32x4 ka[4];
-#pragma unroll
-                for (int ks = 0; ks < 4; ++ks)
-                    ka[ks] = *reinterpret_cast<const u32x4 *>(buf + j * 4096 + ka_off[ks]);
-#pragma unroll
-                for (int nt = 0; nt < NL; ++nt) {
-                    f32x4 acc = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-                    for (int ks = 0; ks < 4; ++ks) acc = mfma16<DT>(ka[ks], qb[nt][ks], acc);
-                    s[j][nt] = acc;
-                }
-            }
-            u32x4 v[8];
-#pragma unroll
-            for (int e = 0; e < 8; ++e)
-                v[e] = *reinterpret_cast<const u32x4 *>(buf + (e >> 2) * 4096 + va_off[e & 3]);
-            softmax_pv<DT, NL>(s, v, st, c.kv_len - b * 32, grp, P.scale_log2e);
-        }
+    switch (nblk < kRing ? nblk - 1 : kRing - 1) {                      // blocks issued after block 0
+    case 0: __builtin_amdgcn_s_waitcnt(0x0F70); break;
+    case 1: __builtin_amdgcn_s_waitcnt(0x0F72); break;
+    case 2: __builtin_amdgcn_s_waitcnt(0x0F74); break;
+    case 3: __builtin_amdgcn_s_waitcnt(0x0F76); break;
+    case 4: __builtin_amdgcn_s_waitcnt(0x0F78); break;
+    case 5: __builtin_amdgcn_s_waitcnt(0x0F7A); break;
+    case 6: __builtin_amdgcn_s_waitcnt(0x0F7C); break;
+    default: __builtin_amdgcn_s_waitcnt(0x0F7E); break;
     }
+    __syncthreads();
+
+    auto enter_step = [&](int b) {                                      // b + 1 < nblk
+        if (nblk - b >= kRing - 1) __builtin_amdgcn_s_waitcnt(0x0F7A);  // vmcnt(10): kRing-3 blocks behind
+        else                       __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0)
+        __syncthreads();                    // block b+1 is complete; everyone is done with block b-1
+        if (b >= 1 && b - 1 + kRing < nblk) dma_block(b - 1 + kRing);
+    };
 
     if constexpr (NL > 0) {
-#pragma unroll
-        for (int nt = 0; nt < NL; ++nt) {
-            st.l[nt] += __shfl_xor(st.l[nt], 16);
-            st.l[nt] += __shfl_xor(st.l[nt], 32);
+        f32x4 sa[2][NL], sb[2][NL];
+        float lma[NL], lmb[NL];
+        auto step = [&](int b, f32x4 (&s_cur)[2][NL], float (&lm_cur)[NL],
+                        f32x4 (&s_nxt)[2][NL], float (&lm_nxt)[NL]) {   // full block b, b + 1 < nblk
+            enter_step(b);
+            if (__any(outgrown<NL>(lm_cur, st))) raise_reference<NL>(lm_cur, st);
+            u32x4 pb[NL];
+            unsigned int vh[8][2];
+            scores(b + 1, s_nxt);
+            probabilities<DT, NL, true>(s_cur, st, P.scale_log2e, pb);
+            values(b, 0, 32, vh);
+            accumulate_half<DT, NL, 0>(vh, pb, st);
+            values(b, 1, 32, vh);
+            accumulate_half<DT, NL, 1>(vh, pb, st);
+            const int valid_nxt = c.kv_len - (b + 1) * 32;
+            if (valid_nxt < 32) mask_scores<NL>(s_nxt, valid_nxt, grp);
+            lane_maxima<NL>(s_nxt, P.scale_log2e, lm_nxt);
+        };
+        auto last = [&](int b, f32x4 (&s_cur)[2][NL], float (&lm_cur)[NL]) {
+            if (__any(outgrown<NL>(lm_cur, st))) raise_reference<NL>(lm_cur, st);
+            u32x4 pb[NL];
+            unsigned int vh[8][2];
+            const int valid = c.kv_len - b * 32;
+            probabilities<DT, NL, true>(s_cur, st, P.scale_log2e, pb);
+            values(b, 0, valid, vh);
+            accumulate_half<DT, NL, 0>(vh, pb, st);
+            values(b, 1, valid, vh);
+            accumulate_half<DT, NL, 1>(vh, pb, st);
+        };
+
+        scores(0, sa);
+        if (c.kv_len < 32) mask_scores<NL>(sa, c.kv_len, grp);
+        lane_maxima<NL>(sa, P.scale_log2e, lma);
+        int b = 0;
+#pragma unroll 1
+        for (; b + 2 < nblk; b += 2) {
+            step(b, sa, lma, sb, lmb);
+            step(b + 1, sb, lmb, sa, lma);
         }
+        if (b + 1 < nblk) {
+            step(b, sa, lma, sb, lmb);
+            last(b + 1, sb, lmb);
+        } else {
+            last(b, sa, lma);
+        }
+        st.template finish<false>();
         store_partial<NL>(P, t, head, row0, rows, l16, grp, st);
+    } else {
+#pragma unroll 1
+        for (int b = 0; b + 1 < nblk; ++b) enter_step(b);
     }
     __syncthreads();                        // the ring is reused by the slot's next task
 }
