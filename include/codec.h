@@ -101,7 +101,7 @@ typedef struct {
                                >= group; 0 = 256.  Larger query sets are cut into row tiles.       */
     int32_t share;          /* 1 = prefix-shared plan; 0 = flat baseline: every request gets its
                                own tasks for every node on its path, nothing shared across requests */
-    const codec_cost_table *cost;   /* NULL = built-in table                                        */
+    const codec_cost_table *cost;   /* NULL = built-in table of the kernel variant the plan needs     */
 } codec_plan_options;
 
 /* One work item of the division problem: a node (or a row tile of it) with its queries. */
@@ -188,11 +188,18 @@ int codec_plan_destroy(codec_plan_t *plan);
 /* Fills *view with pointers into the plan's own host arrays. */
 int codec_plan_export(const codec_plan_t *plan, codec_plan_view *view);
 
-/* C_est(rows, len) of Eq. 6 on `table` (NULL = built-in); returns the cost, or a negative status. */
+/*
+ * C_est(rows, len) of Eq. 6 on `table`; returns the cost, or a negative status.  NULL = the
+ * built-in table of the kernel variant a task of `rows` rows needs (wide above 16 rows).
+ */
 int64_t codec_cost_estimate(const codec_cost_table *table, int32_t rows, int32_t len);
 
-/* The built-in cost table (static storage). */
-const codec_cost_table *codec_default_cost_table(void);
+/*
+ * The built-in cost tables (static storage), profiled on an MI355X in ns per task: wide != 0 for
+ * plans that hold a task of more than 16 query rows, wide == 0 for the others (the kernel runs such
+ * plans with a different workgroup shape, see num_slots).
+ */
+const codec_cost_table *codec_default_cost_table(int32_t wide);
 
 /* Bytes of device memory the plan's task lists and indexes need. */
 size_t codec_plan_device_bytes(const codec_plan_t *plan);
@@ -239,6 +246,13 @@ int codec_partial_reduction(const codec_plan_t *plan, const void *workspace,
 
 /* Static, human-readable name of a status code. */
 const char *codec_status_string(int status);
+
+/*
+ * Text of the HIP runtime's error for the calling thread's most recent CODEC_ERR_HIP
+ * (the failing call and hipGetErrorString of its result); "" if there was none.
+ * The pointer stays valid until the thread's next failing call.
+ */
+const char *codec_last_error_message(void);
 
 #ifdef __cplusplus
 }

@@ -32,7 +32,7 @@ EXPORTED_SYMBOLS = [
     "codec_plan_create", "codec_plan_destroy", "codec_plan_export", "codec_cost_estimate",
     "codec_default_cost_table", "codec_plan_device_bytes", "codec_plan_upload",
     "codec_plan_workspace_bytes", "codec_decode_attention", "codec_partial_attention",
-    "codec_partial_reduction", "codec_status_string",
+    "codec_partial_reduction", "codec_status_string", "codec_last_error_message",
 ]
 
 _i32p = POINTER(c_int32)
@@ -87,6 +87,14 @@ class codec_kv_layout(Structure):
                 ("head_stride", c_int64)]
 
 
+# PyTorch wheels carry their own copy of the HIP runtime.  Device pointers and streams handed to the
+# library come from PyTorch, so both must use the same runtime instance: load PyTorch's first, and
+# libcodec.so's dependency on libamdhip64 then resolves to the copy already in the process.
+try:
+    import torch  # noqa: F401
+except ImportError:
+    pass
+
 if not os.path.exists(LIB_PATH):
     raise ImportError(f"{LIB_PATH} is missing: build it with `python -m paper_2505_17694_amd.build` "
                       "(there is no CPU fallback)")
@@ -102,7 +110,7 @@ _lib.codec_plan_export.argtypes = [c_void_p, POINTER(codec_plan_view)]
 _lib.codec_cost_estimate.restype = c_int64
 _lib.codec_cost_estimate.argtypes = [POINTER(codec_cost_table), c_int32, c_int32]
 _lib.codec_default_cost_table.restype = POINTER(codec_cost_table)
-_lib.codec_default_cost_table.argtypes = []
+_lib.codec_default_cost_table.argtypes = [c_int32]
 _lib.codec_plan_device_bytes.restype = c_size_t
 _lib.codec_plan_device_bytes.argtypes = [c_void_p]
 _lib.codec_plan_upload.restype = c_int
@@ -120,12 +128,15 @@ _lib.codec_partial_reduction.restype = c_int
 _lib.codec_partial_reduction.argtypes = [c_void_p, c_void_p, c_size_t, c_void_p, c_void_p]
 _lib.codec_status_string.restype = c_char_p
 _lib.codec_status_string.argtypes = [c_int]
+_lib.codec_last_error_message.restype = c_char_p
+_lib.codec_last_error_message.argtypes = []
 
 
 class CodecError(RuntimeError):
     def __init__(self, status: int, where: str):
         self.status = status
-        super().__init__(f"{where}: {codec_status_string(status)} ({status})")
+        detail = codec_last_error_message() if status == CODEC_ERR_HIP else ""
+        super().__init__(f"{where}: {codec_status_string(status)} ({status})" + (f": {detail}" if detail else ""))
 
 
 def _i32(a):
@@ -146,6 +157,10 @@ def make_cost_table(row_grid, len_grid, cost):
 
 def codec_status_string(status: int) -> str:
     return _lib.codec_status_string(int(status)).decode()
+
+
+def codec_last_error_message() -> str:
+    return _lib.codec_last_error_message().decode()
 
 
 def codec_plan_create(parent, node_len, req_node, node_page_off, page_ids,
@@ -210,9 +225,9 @@ def codec_cost_estimate(cost_table, rows: int, length: int) -> int:
     return r
 
 
-def codec_default_cost_table():
-    """Returns (row_grid, len_grid, cost[rows][lens]) of the built-in table as Python lists."""
-    t = _lib.codec_default_cost_table().contents
+def codec_default_cost_table(wide: int):
+    """Returns (row_grid, len_grid, cost[rows][lens]) of a built-in table as Python lists."""
+    t = _lib.codec_default_cost_table(int(wide)).contents
     rg = [t.row_grid[i] for i in range(t.num_row_points)]
     lg = [t.len_grid[i] for i in range(t.num_len_points)]
     cost = [[t.cost[i * t.num_len_points + j] for j in range(t.num_len_points)]

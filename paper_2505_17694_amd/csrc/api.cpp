@@ -2,6 +2,7 @@
 #include <hip/hip_runtime.h>
 
 #include <cmath>
+#include <cstdio>
 #include <cstring>
 #include <new>
 
@@ -17,6 +18,17 @@ struct codec_plan {
 };
 
 namespace {
+
+thread_local char g_last_error[256] = "";
+
+// Records which HIP call failed and why; returns CODEC_ERR_HIP.
+int hip_failure(const char *what, int code)
+{
+    std::snprintf(g_last_error, sizeof g_last_error, "%s: %s (%d)", what,
+                  hipGetErrorString(static_cast<hipError_t>(code)), code);
+    (void)hipGetLastError();        // do not leave the error for the caller's next HIP call
+    return CODEC_ERR_HIP;
+}
 
 size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
@@ -99,7 +111,7 @@ int codec_plan_export(const codec_plan_t *plan, codec_plan_view *v)
 int64_t codec_cost_estimate(const codec_cost_table *table, int32_t rows, int32_t len)
 {
     if (rows < 1 || len < 1) return CODEC_ERR_INVALID_ARGUMENT;
-    if (!table) return codec::builtin_cost_table().estimate(rows, len);
+    if (!table) return codec::builtin_cost_table(rows > 16).estimate(rows, len);
     if (table->num_row_points < 1 || table->num_len_points < 1 || !table->row_grid || !table->len_grid || !table->cost)
         return CODEC_ERR_INVALID_ARGUMENT;
     codec::CostTable t;
@@ -114,10 +126,11 @@ int64_t codec_cost_estimate(const codec_cost_table *table, int32_t rows, int32_t
     return t.estimate(rows, len);
 }
 
-const codec_cost_table *codec_default_cost_table(void)
+const codec_cost_table *codec_default_cost_table(int32_t wide)
 {
-    static codec_cost_table view;
-    const codec::CostTable &t = codec::builtin_cost_table();
+    static codec_cost_table views[2];
+    const codec::CostTable &t = codec::builtin_cost_table(wide != 0);
+    codec_cost_table &view = views[wide != 0];
     view.num_row_points = int32_t(t.row_grid.size());
     view.num_len_points = int32_t(t.len_grid.size());
     view.row_grid = t.row_grid.data();
@@ -137,10 +150,10 @@ int codec_plan_upload(codec_plan_t *plan, void *device_meta, size_t device_meta_
     if (device_meta_bytes < plan->d.layout.total) return CODEC_ERR_WORKSPACE_TOO_SMALL;
     if (reinterpret_cast<uintptr_t>(device_meta) & 255u) return CODEC_ERR_INVALID_ARGUMENT;
     hipStream_t s = static_cast<hipStream_t>(stream);
-    if (hipMemcpyAsync(device_meta, plan->d.blob.data(), plan->d.layout.total, hipMemcpyHostToDevice, s) != hipSuccess)
-        return CODEC_ERR_HIP;
+    if (hipError_t e = hipMemcpyAsync(device_meta, plan->d.blob.data(), plan->d.layout.total, hipMemcpyHostToDevice, s))
+        return hip_failure("hipMemcpyAsync(plan metadata)", int(e));
     // the source is pageable host memory owned by the plan: wait so that it may be freed any time after
-    if (hipStreamSynchronize(s) != hipSuccess) return CODEC_ERR_HIP;
+    if (hipError_t e = hipStreamSynchronize(s)) return hip_failure("hipStreamSynchronize", int(e));
     plan->device_meta = device_meta;
     return CODEC_OK;
 }
@@ -194,7 +207,8 @@ int codec_partial_attention(const codec_plan_t *plan, const void *q, const void 
     while ((1 << pp.page_shift) < d.head.page_size) ++pp.page_shift;
     pp.part_rows = d.part_rows;
     pp.scale_log2e = d.head.scale * 1.4426950408889634f;
-    if (codec::launch_pac(pp, d.head.dtype, d.num_slots, plan->max_task_rows, stream) != 0) return CODEC_ERR_HIP;
+    if (int e = codec::launch_pac(pp, d.head.dtype, d.num_slots, plan->max_task_rows, stream))
+        return hip_failure("partial attention launch", e);
     return CODEC_OK;
 }
 
@@ -222,7 +236,7 @@ int codec_partial_reduction(const codec_plan_t *plan, const void *workspace, siz
     mp.h_q = d.head.num_q_heads;
     mp.group = d.group;
     mp.part_rows = d.part_rows;
-    if (codec::launch_merge(mp, d.head.dtype, stream) != 0) return CODEC_ERR_HIP;
+    if (int e = codec::launch_merge(mp, d.head.dtype, stream)) return hip_failure("partial reduction launch", e);
     return CODEC_OK;
 }
 
@@ -236,6 +250,8 @@ int codec_decode_attention(const codec_plan_t *plan, const void *q, const void *
         return st;
     return codec_partial_reduction(plan, workspace, workspace_bytes, out, stream);
 }
+
+const char *codec_last_error_message(void) { return g_last_error; }
 
 const char *codec_status_string(int status)
 {

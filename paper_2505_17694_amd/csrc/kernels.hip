@@ -20,13 +20,14 @@
 // Softmax statistics stay in fp32, in log2 units.
 //
 // Two task shapes share that arithmetic:
-//  * up to 16 rows ("stream"): the waves take interleaved 32-token blocks of the
-//    slice, each with all rows; K and V go from HBM straight to registers (no LDS
-//    in the loop); the waves' states are merged through LDS at the end.
-//  * 17..256 rows ("dense"): eight waves split the rows (up to 32 each) and walk
-//    the slice together; blocks are copied HBM -> LDS asynchronously into a ring of
-//    eight 16 KB slots (seven blocks in flight, one barrier per block) and read by
-//    all waves.
+//  * "stream" (plans whose tasks all have at most 16 rows, e.g. the flat baseline):
+//    four waves take interleaved 32-token blocks of the slice, each with all rows;
+//    K and V go from HBM straight to registers (no LDS in the loop); the waves'
+//    states are merged through LDS at the end.
+//  * "dense" (every other plan, tasks of 1..256 rows): eight waves split the rows
+//    (up to 32 each) and walk the slice together; blocks are copied HBM -> LDS
+//    asynchronously into a ring of eight 16 KB slots (seven blocks in flight, one
+//    barrier per block) and read by all waves.
 #include <hip/hip_runtime.h>
 
 #include "kernels.hpp"
@@ -474,7 +475,7 @@ __device__ void run_stream(const PacParams &P, const DevTask &t, int head, char 
     if (wave == 0) store_partial<NT>(P, t, head, 0, rows, l16, grp, st);
 }
 
-// ---- dense path: 17..256 rows, the 8 waves split the rows (up to 32 each) and share each block ----
+// ---- dense path: 1..256 rows, the 8 waves split the rows (up to 32 each) and share each block -----
 //
 // Blocks travel HBM -> LDS without passing through registers (global_load_lds_dwordx4: every lane
 // moves 16 bytes, a wave fills 1 KB of consecutive LDS).  A ring of kRing block slots (16 KB each:
@@ -682,7 +683,6 @@ template <int DT, int WIDE>
 __global__ void __launch_bounds__(WIDE ? kWideWaves * 64 : kNarrowWaves * 64, 2) pac_kernel(const PacParams P)
 {
     constexpr int W = WIDE ? kWideWaves : kNarrowWaves;
-    static_assert(merge_bytes(kWideWaves, 1) <= kRingBytes, "stream merge must fit in the ring");
     __shared__ __attribute__((aligned(16))) char static_lds[WIDE ? 16 : merge_bytes(kNarrowWaves, 1)];
     char *lds = WIDE ? dyn_lds : static_lds;
     const int head = blockIdx.x % P.h_kv;
@@ -692,11 +692,10 @@ __global__ void __launch_bounds__(WIDE ? kWideWaves * 64 : kNarrowWaves * 64, 2)
     for (int i = t0; i < t1; ++i) {
         const DevTask t = P.tasks[P.slot_tasks[i]];
         const int rows = t.n_req * P.group;
-        if (rows <= 16) {
-            run_stream<DT, 1, W>(P, t, head, lds);
-        } else if constexpr (WIDE != 0) {
+        if constexpr (WIDE != 0)
             run_dense<DT>(P, t, head, lds);
-        }
+        else if (rows <= 16)
+            run_stream<DT, 1, W>(P, t, head, lds);
     }
 }
 

@@ -123,21 +123,28 @@ int64_t CostTable::estimate(int64_t rows, int64_t len) const
     return v < 1 ? 1 : static_cast<int64_t>(v);
 }
 
-// Bootstrap table (ns per workgroup, one workgroup per CU) from a bandwidth
-// model of the kernel: 2500 + tokens * (23 + 0.03 rows) + 30 per partial row.
-// Replaced by a measured table through codec_plan_options.cost.
-const CostTable &builtin_cost_table()
+// Built-in tables: cost in ns of one task inside a busy persistent workgroup, measured on an MI355X
+// with the profiler of the Python package (one launch with three tasks per slot minus one launch with
+// one task per slot, halved; every slot and KV head busy, K/V cold).  The kernel has two launch
+// variants with different workgroup shapes, hence two tables: `wide` for plans that hold a task of
+// more than 16 rows, `narrow` for the others.
+const CostTable &builtin_cost_table(bool wide)
 {
-    static const CostTable t = {
+    static const CostTable narrow_table = {
+        {1, 16},
+        {32, 128, 512, 2048, 8192, 32768},
+        {4260, 4760, 23898, 92029, 366774, 1477695,
+         5719, 6420, 29116, 100567, 373773, 1472995}};
+    static const CostTable wide_table = {
         {1, 16, 32, 64, 128, 256},
-        {32, 256, 1024, 4096, 16384, 65536},
-        {3266, 8425, 26112, 96860, 379853, 1511824,
-         3731, 8990, 27023, 99154, 387676, 1541765,
-         4226, 9593, 27995, 101600, 396020, 1573702,
-         5217, 10799, 29938, 106492, 412709, 1637577,
-         7198, 13211, 33824, 116276, 446086, 1765326,
-         11161, 18034, 41596, 135845, 512841, 2020824}};
-    return t;
+        {32, 128, 512, 2048, 8192, 32768},
+        {2420, 6119, 13478, 48855, 181258, 732448,
+         2939, 6339, 14198, 51093, 183796, 739667,
+         3280, 6780, 16118, 53953, 190116, 746086,
+         5699, 8819, 18718, 58073, 195855, 745126,
+         9379, 11979, 24517, 65492, 263267, 964959,
+         16018, 18857, 41775, 102047, 364255, 1340991}};
+    return wide ? wide_table : narrow_table;
 }
 
 int build_plan(const codec_tree &tree, const codec_head_config &head,
@@ -168,7 +175,7 @@ int build_plan(const codec_tree &tree, const codec_head_config &head,
     if (opt.share != 0 && opt.share != 1) return CODEC_ERR_INVALID_ARGUMENT;
 
     CostTable user;
-    const CostTable *table = &builtin_cost_table();
+    const CostTable *table = nullptr;           // nullptr: the built-in table of the kernel variant
     if (opt.cost) {
         const codec_cost_table &c = *opt.cost;
         if (c.num_row_points < 1 || c.num_len_points < 1 || !c.row_grid || !c.len_grid || !c.cost)
@@ -255,18 +262,19 @@ int build_plan(const codec_tree &tree, const codec_head_config &head,
             it.n_req = std::min(qpt, n_q[n] - a);
             it.rows = it.n_req * group;
             it.len = p.node_len[n];
-            it.cost = table->estimate(it.rows, it.len);       // a2: Eq. 6
             p.items.push_back(it);
         }
     }
     const size_t J = p.items.size();
-    // slots that run at once per KV head: tasks above 16 rows need the one-workgroup-per-CU kernel
-    // variant (256 CUs), otherwise two workgroups share a CU
+    // kernel variant: a task above 16 rows needs the wide one (one workgroup per CU, 256 CUs);
+    // otherwise two narrow workgroups share a CU.  It fixes the default slot count and cost table.
     int32_t widest = 0;
     for (const codec_item &it : p.items) widest = std::max(widest, it.rows);
-    const int32_t m = opt.num_slots > 0 ? opt.num_slots
-                                        : std::max(1, (widest > 16 ? 256 : 512) / head.num_kv_heads);
+    const bool wide = widest > 16;
+    const int32_t m = opt.num_slots > 0 ? opt.num_slots : std::max(1, (wide ? 256 : 512) / head.num_kv_heads);
     p.num_slots = m;
+    if (!table) table = &builtin_cost_table(wide);
+    for (codec_item &it : p.items) it.cost = table->estimate(it.rows, it.len);       // a2: Eq. 6
     std::vector<int64_t> max_b(J);
     for (size_t j = 0; j < J; ++j) max_b[j] = ceil_div(p.items[j].len, align);
 

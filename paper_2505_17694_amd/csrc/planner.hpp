@@ -54,7 +54,7 @@ struct PlanData {
     std::vector<unsigned char> blob;    // host image of the device metadata
 };
 
-const CostTable &builtin_cost_table();
+const CostTable &builtin_cost_table(bool wide);
 
 // Fills `plan` from the caller's forest; returns a CODEC_* status.
 int build_plan(const codec_tree &tree, const codec_head_config &head,

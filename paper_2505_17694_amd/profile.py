@@ -1,0 +1,141 @@
+"""Cost-table profiler: measures C_est(rows, len) of the partial-attention kernel on this GPU.
+
+The planner balances work with a profiled table (paper Sec. 5.2: run the
+partial attention kernel over a grid of query counts and KV lengths on the
+target GPU, record the block execution time, interpolate in between).  One
+measurement here is one launch in which every workgroup slot of one KV head
+runs exactly one task of the given shape, all slots and heads at once, so the
+number is the time of a workgroup under the load the plan will see.  K/V pools
+are rotated so that consecutive launches do not find their data in cache.
+
+Two tables are measured because the kernel has two launch variants: "narrow"
+(only tasks of at most 16 rows; 4 waves per workgroup, two workgroups per CU)
+and "wide" (any task; 8 waves, one workgroup per CU).
+
+    python -m paper_2505_17694_amd.profile --out profiles/cost_table_mi355x.json
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import math
+import sys
+
+import numpy as np
+
+
+def _forest(num_tasks, rows, length, force_wide):
+    """`num_tasks` independent nodes of `length` tokens, `rows` requests ending at each (group = 1)."""
+    parent = [-1] * num_tasks
+    node_len = [length] * num_tasks
+    req_node = [n for n in range(num_tasks) for _ in range(rows)]
+    if force_wide:          # one tiny 17-row node makes the plan pick the wide kernel variant; it shares a
+                            # slot with other tasks and its few microseconds cancel in measure()
+        parent.append(-1)
+        node_len.append(32)
+        req_node += [num_tasks] * 17
+    return np.array(parent, np.int32), np.array(node_len, np.int32), np.array(req_node, np.int32)
+
+
+def launch_time(rows: int, length: int, wide: bool, per_slot: int, iters: int = 8,
+                device: str = "cuda:0") -> float:
+    """Median duration (ns) of the partial-attention launch with `per_slot` (rows, length) tasks per slot."""
+    import torch
+    from . import binding as B
+    from .runtime import PlannedAttention
+
+    class Bag:
+        pass
+
+    h_kv, d, ps = 8, 128, 16
+    slots = 32 if wide else 64
+    force = wide and rows <= 16
+    parent, node_len, req_node = _forest(slots * per_slot, rows, length, force)
+    forest, paged, head = Bag(), Bag(), Bag()
+    forest.parent, forest.node_len, forest.req_node = parent, node_len, req_node
+    pages_per = (node_len.astype(np.int64) + ps - 1) // ps
+    off = np.zeros(len(parent) + 1, np.int64)
+    np.cumsum(pages_per, out=off[1:])
+    paged.node_page_off = off.astype(np.int32)
+    paged.num_pages = int(off[-1])
+    rng = np.random.Generator(np.random.PCG64(rows * 1000003 + length))
+    paged.page_ids = rng.permutation(paged.num_pages).astype(np.int32)
+    paged.page_stride, paged.token_stride, paged.head_stride = ps * h_kv * d, h_kv * d, d
+    head.num_q_heads = head.num_kv_heads = h_kv
+    head.head_dim, head.dtype, head.page_size, head.scale = d, B.CODEC_DTYPE_BF16, ps, 1.0 / math.sqrt(d)
+
+    pool_elems = paged.num_pages * ps * h_kv * d
+    copies = max(1, min(16, int((2 << 30) // max(1, 4 * pool_elems))))
+    gen = torch.Generator(device=device)
+    gen.manual_seed(1)
+    q = torch.randn((len(req_node), h_kv, d), device=device, generator=gen).to(torch.bfloat16)
+    pools = [(torch.randn(pool_elems, device=device, generator=gen).to(torch.bfloat16),
+              torch.randn(pool_elems, device=device, generator=gen).to(torch.bfloat16)) for _ in range(copies)]
+    # a flat table keeps the planner from dividing: one task per node, one node per slot
+    flat = ([1], [1], [[1000]])
+    pa = PlannedAttention(forest, paged, head, device=device, num_slots=slots,
+                          split_align=32, max_rows=256, share=1, cost_table=flat)
+    view = pa.export()
+    assert len(view["tasks"]) == len(parent), "the profiling plan must not divide nodes"
+    per = np.bincount([t["slot"] for t in view["tasks"]][:slots * per_slot], minlength=slots)
+    assert per.max() == per_slot, "every slot must get the same number of tasks"
+    stream = torch.cuda.current_stream()
+    for i in range(2):
+        pa.partial_attention(q, *pools[i % copies])
+    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(iters)]
+    for i, (a, b) in enumerate(ev):
+        k, v = pools[(i + 2) % copies]
+        a.record(stream)
+        pa.partial_attention(q, k, v)
+        b.record(stream)
+    torch.cuda.synchronize()
+    pa.close()
+    times = sorted(a.elapsed_time(b) for a, b in ev)
+    return times[len(times) // 2] * 1e6
+
+
+def measure(rows: int, length: int, wide: bool) -> float:
+    """Cost (ns) of one (rows, length) task inside a busy persistent workgroup.
+
+    The difference between launches with three tasks and with one task per slot, halved: launch
+    latency and the ramp at both ends of a launch drop out.
+    """
+    t1 = launch_time(rows, length, wide, 1)
+    t3 = launch_time(rows, length, wide, 3)
+    return max((t3 - t1) / 2.0, 1.0)
+
+
+def profile(row_grid, len_grid, wide: bool, verbose: bool = True):
+    cost = []
+    for r in row_grid:
+        row = []
+        for n in len_grid:
+            ns = measure(r, n, wide)
+            row.append(int(round(ns)))
+            if verbose:
+                print(f"[profile] {'wide' if wide else 'narrow'} rows={r:4d} len={n:6d}: {ns / 1e3:9.2f} us",
+                      file=sys.stderr, flush=True)
+        cost.append(row)
+    return {"row_grid": list(row_grid), "len_grid": list(len_grid), "cost": cost}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--out", default="")
+    ap.add_argument("--lens", default="32,128,512,2048,8192,32768")
+    ap.add_argument("--wide-rows", default="1,16,17,32,64,128,256")
+    ap.add_argument("--narrow-rows", default="1,16")
+    args = ap.parse_args()
+    lens = [int(x) for x in args.lens.split(",")]
+    tables = {"unit": "ns per workgroup, every slot busy",
+              "narrow": profile([int(x) for x in args.narrow_rows.split(",")], lens, wide=False),
+              "wide": profile([int(x) for x in args.wide_rows.split(",")], lens, wide=True)}
+    text = json.dumps(tables, indent=1)
+    if args.out:
+        with open(args.out, "w") as f:
+            f.write(text + "\n")
+    print(text)
+
+
+if __name__ == "__main__":
+    main()

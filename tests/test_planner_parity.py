@@ -24,8 +24,8 @@ def _tuple(t):
     return (t["row_grid"], t["len_grid"], t["cost"])
 
 
-def _default_table():
-    rg, lg, c = C.codec_default_cost_table()
+def _default_table(wide=1):
+    rg, lg, c = C.codec_default_cost_table(wide)
     return {"row_grid": rg, "len_grid": lg, "cost": c}
 
 
@@ -60,13 +60,14 @@ def _compare(view, ref):
 
 def test_cost_estimate_matches_oracle_everywhere():
     rng = random.Random(3)
-    for table in (TABLE2, _default_table(),
+    for table in (TABLE2, _default_table(0), _default_table(1),
                   {"row_grid": [1, 3], "len_grid": [10, 20], "cost": [[10, 20], [30, 42]]},
                   {"row_grid": [4], "len_grid": [8], "cost": [[7]]}):
         for _ in range(400):
             r, n = rng.randint(1, 300), rng.choice([rng.randint(1, 600), rng.randint(1, 200000)])
             assert C.codec_cost_estimate(_tuple(table), r, n) == P.c_est(table, r, n)
-    assert C.codec_cost_estimate(None, 16, 256) == P.c_est(_default_table(), 16, 256)
+    assert C.codec_cost_estimate(None, 16, 256) == P.c_est(_default_table(0), 16, 256)
+    assert C.codec_cost_estimate(None, 200, 5000) == P.c_est(_default_table(1), 200, 5000)
     # the paper's Table 2 at its own grid points through the C ABI
     assert C.codec_cost_estimate(_tuple(TABLE2), 10, 4096) == 126
     assert C.codec_cost_estimate(_tuple(TABLE2), 100, 16384) == 746
@@ -91,8 +92,10 @@ FORESTS = {
 def test_library_plan_equals_rederivation(name, share, m, align, max_rows, hq, hkv, table):
     f = FORESTS[name]()
     head = HeadConfig(hq, hkv, 128)
-    tab = TABLE2 if table == "table2" else _default_table()
-    view = _lib_plan(f, head, m, align, max_rows, share, tab if table == "table2" else None)
+    view = _lib_plan(f, head, m, align, max_rows, share, TABLE2 if table == "table2" else None)
+    # without a caller's table the library takes the built-in one of the kernel variant the plan needs
+    wide = max(it["rows"] for it in view["items"]) > 16
+    tab = TABLE2 if table == "table2" else _default_table(wide)
     ref = P.plan(f.parent, f.node_len, f.req_node, head.group, m, align, max_rows, share, tab)
     _compare(view, ref)
 
@@ -108,5 +111,6 @@ def test_measured_configurations_with_library_defaults(name, share):
     widest = max(it["rows"] for it in view["items"])
     m = (256 if widest > 16 else 512) // head.num_kv_heads
     assert view["num_slots"] == m
-    ref = P.plan(f.parent, f.node_len, f.req_node, head.group, m, 256, 256, share, _default_table())
+    ref = P.plan(f.parent, f.node_len, f.req_node, head.group, m, 256, 256, share,
+                 _default_table(widest > 16))
     _compare(view, ref)
