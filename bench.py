@@ -46,6 +46,9 @@ def parse_args():
     ap.add_argument("--split-align", type=int, default=0)
     ap.add_argument("--max-rows", type=int, default=0)
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU time of the oracle sample")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run a plain 1 GiB device copy 3 times (reference for scaling FETCH_SIZE / "
+                         "WRITE_SIZE counters when the run is profiled)")
     return ap.parse_args()
 
 
@@ -219,6 +222,15 @@ def main():
             del w, out
             torch.cuda.empty_cache()
         per_config[name] = res
+
+    if args.copy_calibration:
+        # reads 1 GiB and writes 1 GiB; shows up in a profile as an elementwise kernel with "MulFunctor"
+        src = torch.ones(1 << 28, dtype=torch.float32, device="cuda:0")
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            torch.mul(src, 1.5, out=dst)
+        torch.cuda.synchronize()
+        del src, dst
 
     res, w, out = headline
     raw = res["tree"]["_raw"]
