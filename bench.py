@@ -39,7 +39,8 @@ def parse_args():
     ap.add_argument("--workload", default="cfg2", help="headline configuration")
     ap.add_argument("--configs", default="cfg1,cfg2,cfg3,cfg4,cfg5a,cfg5b,cfg5c",
                     help="configurations reported in per_config ('' = headline only)")
-    ap.add_argument("--layout", default="thd", choices=["thd", "htd"])
+    ap.add_argument("--layout", default="htd", choices=["thd", "htd"],
+                    help="page layout: htd = [page][kv_head][token][d] (a page-head is one 4 KB run), thd = [page][token][kv_head][d]")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-flat", action="store_true")
     ap.add_argument("--num-slots", type=int, default=0)
