@@ -91,24 +91,19 @@ struct SliceCtx {
 
 // Page ids are read through the scalar data path (s_load_dword, a read-only access): a vector load
 // would sit in the same in-order return queue as the K/V traffic, and waiting for it would drain every
-// prefetched block.  The compiler cannot pick the scalar path itself here because the kernel also
-// stores to global memory.  `p` and `index` must be wave-uniform.
-__device__ __forceinline__ int scalar_load(const int32_t *p, int index)
+// prefetched block.  The page table does not change while a launch runs, so the load goes through a
+// pointer to the constant address space; with a wave-uniform index the compiler then picks the scalar
+// path and places the wait at the first use, which lets callers load an id a whole step ahead.
+__device__ __forceinline__ int uniform_load(const int32_t *p, int index)
 {
-    int v;
-    asm volatile("s_load_dword %0, %1, %2\n\t"
-                 "s_waitcnt lgkmcnt(0)"
-                 : "=s"(v)
-                 : "s"(p), "s"(index * 4)
-                 : "memory");
-    return v;
+    typedef const int32_t __attribute__((address_space(4))) *const_i32_ptr;
+    return ((const_i32_ptr)(uintptr_t)p)[__builtin_amdgcn_readfirstlane(index)];
 }
 
-// Byte offset of the 16-token tile that starts at token `tok0` of the slice (wave-uniform).
-__device__ __forceinline__ int64_t tile_offset(const SliceCtx &c, int tok0)
+// Byte offset of a page slot: page id `pg`, token slot `slot` inside the page (wave-uniform).
+__device__ __forceinline__ int64_t page_offset(const SliceCtx &c, int pg, int slot)
 {
-    const int pg = scalar_load(c.pages, tok0 >> c.page_shift);
-    return int64_t(pg) * c.page_bytes + int64_t(tok0 & c.page_mask) * c.token_bytes;
+    return int64_t(pg) * c.page_bytes + int64_t(slot) * c.token_bytes;
 }
 
 // K and V registers of one 32-token block (stream path).
@@ -121,11 +116,16 @@ struct BlockRegs {
 // no address leaves the slice's pages; its scores are masked later.
 __device__ __forceinline__ void load_block(const SliceCtx &c, int tb, uint32_t koff, uint32_t voff, BlockRegs &r)
 {
+    int tok[2], pg[2];
 #pragma unroll
     for (int j = 0; j < 2; ++j) {
-        int tok0 = tb * 32 + j * 16;
-        if (tok0 >= c.kv_len) tok0 = 0;
-        const int64_t off = tile_offset(c, tok0);
+        tok[j] = tb * 32 + j * 16;
+        if (tok[j] >= c.kv_len) tok[j] = 0;
+        pg[j] = uniform_load(c.pages, tok[j] >> c.page_shift);
+    }
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+        const int64_t off = page_offset(c, pg[j], tok[j] & c.page_mask);
         const char *kt = c.k_head + off;
         const char *vt = c.v_head + off;
 #pragma unroll
@@ -137,7 +137,8 @@ __device__ __forceinline__ void load_block(const SliceCtx &c, int tb, uint32_t k
 
 template <int NT>
 struct RowState {
-    f32x4 o[NT][8];     // [row tile][dt]: row = 16*nt + lane%16, channel = 32*(lane/16) + 8*e + dt
+    f32x4 o[NT][8];     // [row tile][dt]: row = 16*nt + lane%16; channel of component e: stream path
+                        // 32*(lane/16) + 8*e + dt, dense path 16*dt + 4*(lane/16) + e
     f32x4 lsum[NT];     // row sum of exponentials, accumulated by the matrix unit against an all-ones
                         // A operand: four equal copies per lane, complete over all 32 tokens of a block
     float m[NT];        // reference subtracted before exponentiation, log2 units (same in the 4 lanes
@@ -332,8 +333,10 @@ __device__ __forceinline__ void gather_q(const PacParams &P, const DevTask &t, i
     }
 }
 
-// Write one wave's rows of the partial result: unnormalised output, (max, sum) per row.
-template <int NT>
+// Write one wave's rows of the partial result: unnormalised output, (reference, sum) per row.
+// TR selects the channel map of the accumulators: false (stream path) channel = 32*grp + 8*e + dt,
+// true (dense path, transposing V reads) channel = 16*dt + 4*grp + e.
+template <int NT, bool TR>
 __device__ __forceinline__ void store_partial(const PacParams &P, const DevTask &t, int head, int row0, int rows,
                                               int l16, int grp, const RowState<NT> &st)
 {
@@ -342,13 +345,19 @@ __device__ __forceinline__ void store_partial(const PacParams &P, const DevTask 
         const int row = row0 + nt * 16 + l16;
         if (row < rows) {
             const int64_t prow = int64_t(head) * P.part_rows + t.part_row_base + row;
-            float *po = P.part_o + prow * kHeadDim + grp * 32;
+            if constexpr (TR) {
+                float *po = P.part_o + prow * kHeadDim + grp * 4;
 #pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                f32x4 lo = {st.o[nt][0][e], st.o[nt][1][e], st.o[nt][2][e], st.o[nt][3][e]};
-                f32x4 hi = {st.o[nt][4][e], st.o[nt][5][e], st.o[nt][6][e], st.o[nt][7][e]};
-                *reinterpret_cast<f32x4 *>(po + e * 8) = lo;
-                *reinterpret_cast<f32x4 *>(po + e * 8 + 4) = hi;
+                for (int dt = 0; dt < 8; ++dt) *reinterpret_cast<f32x4 *>(po + dt * 16) = st.o[nt][dt];
+            } else {
+                float *po = P.part_o + prow * kHeadDim + grp * 32;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    f32x4 lo = {st.o[nt][0][e], st.o[nt][1][e], st.o[nt][2][e], st.o[nt][3][e]};
+                    f32x4 hi = {st.o[nt][4][e], st.o[nt][5][e], st.o[nt][6][e], st.o[nt][7][e]};
+                    *reinterpret_cast<f32x4 *>(po + e * 8) = lo;
+                    *reinterpret_cast<f32x4 *>(po + e * 8 + 4) = hi;
+                }
             }
             if (grp == 0) {
                 float2 ml = {st.m[nt], st.l[nt]};
@@ -472,7 +481,7 @@ __device__ void run_stream(const PacParams &P, const DevTask &t, int head, char 
         }
         __syncthreads();
     }
-    if (wave == 0) store_partial<NT>(P, t, head, 0, rows, l16, grp, st);
+    if (wave == 0) store_partial<NT, false>(P, t, head, 0, rows, l16, grp, st);
 }
 
 // ---- dense path: 1..256 rows, the 8 waves split the rows (up to 32 each) and share each block -----
@@ -531,21 +540,32 @@ __device__ __forceinline__ void dense_wave(const PacParams &P, const DevTask &t,
     const uint32_t lds_base = uint32_t(uintptr_t(lds));
     const int key = (wave * 4 + grp) & 15;                              // destination row & 15
     const uint32_t voff = uint32_t(grp) * c.token_bytes + uint32_t((l16 ^ key) << 4);
-    auto dma_block = [&](int bb) {
-        int tok0 = bb * 32 + wave * 4;
-        if (tok0 >= c.kv_len) tok0 = 0;                                 // nothing of the group is live
-        const int64_t off = tile_offset(c, tok0 & ~15) + int64_t(tok0 & 15) * c.token_bytes;
+    // token (slice-relative) at which this wave's four rows of block bb start; a group past the end of
+    // the slice is redirected to token 0 (its rows are masked later) so that no address leaves the pages
+    auto first_token = [&](int bb) {
+        const int tok0 = bb * 32 + wave * 4;
+        return tok0 >= c.kv_len ? 0 : tok0;
+    };
+    auto page_issue = [&](int bb) { return uniform_load(c.pages, first_token(bb) >> c.page_shift); };
+    auto dma_block = [&](int bb, int pg) {                              // pg: page id from page_issue(bb)
+        const int64_t off = page_offset(c, pg, first_token(bb) & c.page_mask);
         const uint32_t slot = lds_base + uint32_t(bb % kRing) * kBlockBytes + uint32_t(wave) * 1024;
         dma16(slot, voff, c.k_head + off);
         dma16(slot + 8192, voff, c.v_head + off);
     };
-    // lane-dependent parts of the operand addresses (the slot base is added per block)
-    uint32_t ka_off[4], va_off[4];
+    // Lane-dependent parts of the operand addresses (the slot base is added per block).
+    // K: lane (grp, l16) reads the 16-byte column 4*ks + grp of row l16 of a tile.
+    // V: ds_read_b64_tr_b16 hands lane i of a 16-lane group the i-th 16-bit column of the 4 x 16 tile
+    //    whose row k the group's lanes 4k .. 4k+3 address 8 bytes (4 columns) apiece.  Lane (k, q)
+    //    therefore addresses token 4*grp + k, channels 16*dt + 4*q .. +3, and every lane receives its
+    //    own channel 16*dt + l16 for tokens 4*grp .. 4*grp+3: the A operand of O^T += V^T P^T without
+    //    a single vector instruction.  With the column swizzle the address for channel tile dt is the
+    //    address for tile 0 with (dt << 5) XORed in.
+    uint32_t ka_off[4];
 #pragma unroll
-    for (int x = 0; x < 4; ++x) {
-        ka_off[x] = uint32_t(l16 * 256 + (((x * 4 + grp) ^ l16) << 4));                 // k-step x
-        va_off[x] = uint32_t(8192 + (grp * 4 + x) * 256 + ((l16 ^ (grp * 4 + x)) << 4)); // token 4*grp + x
-    }
+    for (int x = 0; x < 4; ++x) ka_off[x] = uint32_t(l16 * 256 + (((x * 4 + grp) ^ l16) << 4));
+    const int vk = l16 >> 2, vq = l16 & 3, vrow = grp * 4 + vk;
+    const uint32_t va_off = uint32_t(8192 + vrow * 256 + ((((vq >> 1) ^ vrow) & 15) << 4) + 8 * (vq & 1));
     auto scores = [&](int bb, f32x4 (&s)[2][NQ]) {                      // S^T of block bb from its slot
         const char *buf = lds + (bb % kRing) * kBlockBytes;
 #pragma unroll
@@ -563,16 +583,40 @@ __device__ __forceinline__ void dense_wave(const PacParams &P, const DevTask &t,
             }
         }
     };
-    // half h (channels 4h .. 4h+3 of the lane's 8) of the V row pieces of block bb; tokens past `valid`
-    // count as zero
-    auto values = [&](int bb, int h, int valid, unsigned int (&vh)[8][2]) {
-        const char *buf = lds + (bb % kRing) * kBlockBytes + h * 8;
+    // A operand of channel tile dt of block bb: 8 tokens (4 of each 16-token tile) of channel
+    // 16*dt + l16; tokens past `valid` count as zero
+    typedef __attribute__((ext_vector_type(4))) short s16x4;
+    typedef s16x4 __attribute__((address_space(3))) *lds_s16x4_ptr;
+    auto value_tile = [&](uint32_t slot_addr, int dt, int valid) {
+        u32x4 va;
 #pragma unroll
-        for (int e = 0; e < 8; ++e) {
-            const uint2 x = *reinterpret_cast<const uint2 *>(buf + (e >> 2) * 4096 + va_off[e & 3]);
-            const bool dead = (e >> 2) * 16 + grp * 4 + (e & 3) >= valid;
-            vh[e][0] = dead ? 0u : x.x;
-            vh[e][1] = dead ? 0u : x.y;
+        for (int j = 0; j < 2; ++j) {
+            const uint32_t addr = (slot_addr ^ uint32_t(dt << 5)) + j * 4096;
+            const s16x4 x = __builtin_amdgcn_ds_read_tr16_b64_v4i16(reinterpret_cast<lds_s16x4_ptr>(uintptr_t(addr)));
+            const uint2 w = __builtin_bit_cast(uint2, x);
+            va[2 * j] = w.x;
+            va[2 * j + 1] = w.y;
+        }
+        if (valid < 32) {
+#pragma unroll
+            for (int j = 0; j < 2; ++j)
+#pragma unroll
+                for (int h = 0; h < 2; ++h) {
+                    const int tok = j * 16 + grp * 4 + 2 * h;       // tokens tok (low half), tok+1 (high half)
+                    const unsigned int keep = (tok < valid ? 0x0000FFFFu : 0u) | (tok + 1 < valid ? 0xFFFF0000u : 0u);
+                    va[2 * j + h] &= keep;
+                }
+        }
+        return va;
+    };
+    // O^T += V^T P^T for block bb
+    auto accumulate_block = [&](int bb, int valid, const u32x4 (&pb)[NQ]) {
+        const uint32_t slot_addr = lds_base + uint32_t(bb % kRing) * kBlockBytes + va_off;
+#pragma unroll
+        for (int dt = 0; dt < 8; ++dt) {
+            const u32x4 va = value_tile(slot_addr, dt, valid);
+#pragma unroll
+            for (int nt = 0; nt < NQ; ++nt) st.o[nt][dt] = mfma16<DT>(va, pb[nt], st.o[nt][dt]);
         }
     };
 
@@ -584,9 +628,16 @@ __device__ __forceinline__ void dense_wave(const PacParams &P, const DevTask &t,
     // b+1 has landed once at most 2 * (blocks issued after it) loads are outstanding; when fewer than
     // kRing-3 blocks were issued after it the wait is for everything.
     const int nblk = (t.kv_len + 31) >> 5;
-#pragma unroll 1
-    for (int d = 0; d < kRing; ++d)
-        if (d < nblk) dma_block(d);
+    {
+        int pg[kRing];
+#pragma unroll
+        for (int d = 0; d < kRing; ++d) pg[d] = page_issue(d < nblk ? d : 0);
+#pragma unroll
+        for (int d = 0; d < kRing; ++d)
+            if (d < nblk) dma_block(d, pg[d]);
+    }
+    // page id of the block the next step will request (block kRing at step 1), loaded a step ahead
+    int pg_next = page_issue(kRing < nblk ? kRing : 0);
     switch (nblk < kRing ? nblk - 1 : kRing - 1) {                      // blocks issued after block 0
     case 0: __builtin_amdgcn_s_waitcnt(0x0F70); break;
     case 1: __builtin_amdgcn_s_waitcnt(0x0F72); break;
@@ -603,7 +654,10 @@ __device__ __forceinline__ void dense_wave(const PacParams &P, const DevTask &t,
         if (nblk - b >= kRing - 1) __builtin_amdgcn_s_waitcnt(0x0F7A);  // vmcnt(10): kRing-3 blocks behind
         else                       __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0)
         __syncthreads();                    // block b+1 is complete; everyone is done with block b-1
-        if (b >= 1 && b - 1 + kRing < nblk) dma_block(b - 1 + kRing);
+        if (b >= 1) {
+            if (b - 1 + kRing < nblk) dma_block(b - 1 + kRing, pg_next);
+            pg_next = page_issue(b + kRing < nblk ? b + kRing : 0);
+        }
     };
 
     if constexpr (NL > 0) {
@@ -614,13 +668,9 @@ __device__ __forceinline__ void dense_wave(const PacParams &P, const DevTask &t,
             enter_step(b);
             if (__any(outgrown<NL>(lm_cur, st))) raise_reference<NL>(lm_cur, st);
             u32x4 pb[NL];
-            unsigned int vh[8][2];
             scores(b + 1, s_nxt);
             probabilities<DT, NL, true>(s_cur, st, P.scale_log2e, pb);
-            values(b, 0, 32, vh);
-            accumulate_half<DT, NL, 0>(vh, pb, st);
-            values(b, 1, 32, vh);
-            accumulate_half<DT, NL, 1>(vh, pb, st);
+            accumulate_block(b, 32, pb);
             const int valid_nxt = c.kv_len - (b + 1) * 32;
             if (valid_nxt < 32) mask_scores<NL>(s_nxt, valid_nxt, grp);
             lane_maxima<NL>(s_nxt, P.scale_log2e, lm_nxt);
@@ -628,13 +678,8 @@ __device__ __forceinline__ void dense_wave(const PacParams &P, const DevTask &t,
         auto last = [&](int b, f32x4 (&s_cur)[2][NL], float (&lm_cur)[NL]) {
             if (__any(outgrown<NL>(lm_cur, st))) raise_reference<NL>(lm_cur, st);
             u32x4 pb[NL];
-            unsigned int vh[8][2];
-            const int valid = c.kv_len - b * 32;
             probabilities<DT, NL, true>(s_cur, st, P.scale_log2e, pb);
-            values(b, 0, valid, vh);
-            accumulate_half<DT, NL, 0>(vh, pb, st);
-            values(b, 1, valid, vh);
-            accumulate_half<DT, NL, 1>(vh, pb, st);
+            accumulate_block(b, c.kv_len - b * 32, pb);
         };
 
         scores(0, sa);
@@ -653,7 +698,7 @@ __device__ __forceinline__ void dense_wave(const PacParams &P, const DevTask &t,
             last(b, sa, lma);
         }
         st.template finish<false>();
-        store_partial<NL>(P, t, head, row0, rows, l16, grp, st);
+        store_partial<NL, true>(P, t, head, row0, rows, l16, grp, st);
     } else {
 #pragma unroll 1
         for (int b = 0; b + 1 < nblk; ++b) enter_step(b);
@@ -677,14 +722,21 @@ __device__ void run_dense(const PacParams &P, const DevTask &t, int head, char *
     }
 }
 
-extern __shared__ __attribute__((aligned(16))) char dyn_lds[];      // WIDE: kRingBytes of dynamic LDS
+// WIDE: kRingBytes of dynamic LDS.  The dense path XORs the channel tile into operand addresses, so
+// the ring must start on a 256-byte boundary (no static LDS in that variant).
+extern __shared__ __attribute__((aligned(1024))) char dyn_lds[];
 
 template <int DT, int WIDE>
 __global__ void __launch_bounds__(WIDE ? kWideWaves * 64 : kNarrowWaves * 64, 2) pac_kernel(const PacParams P)
 {
     constexpr int W = WIDE ? kWideWaves : kNarrowWaves;
-    __shared__ __attribute__((aligned(16))) char static_lds[WIDE ? 16 : merge_bytes(kNarrowWaves, 1)];
-    char *lds = WIDE ? dyn_lds : static_lds;
+    char *lds;
+    if constexpr (WIDE != 0) {
+        lds = dyn_lds;
+    } else {
+        __shared__ __attribute__((aligned(16))) char static_lds[merge_bytes(kNarrowWaves, 1)];
+        lds = static_lds;
+    }
     const int head = blockIdx.x % P.h_kv;
     const int slot = blockIdx.x / P.h_kv;
     const int t0 = P.slot_off[slot], t1 = P.slot_off[slot + 1];
