@@ -30,6 +30,8 @@
 //    barrier per block) and read by all waves.
 #include <hip/hip_runtime.h>
 
+#include <type_traits>
+
 #include "kernels.hpp"
 
 namespace codec {
@@ -706,20 +708,331 @@ __device__ __forceinline__ void dense_wave(const PacParams &P, const DevTask &t,
     __syncthreads();                        // the ring is reused by the slot's next task
 }
 
+// A dense task of at most 16 rows: wave 0 computes, the others help moving blocks.
 template <int DT>
-__device__ void run_dense(const PacParams &P, const DevTask &t, int head, char *lds)
+__device__ void run_dense16(const PacParams &P, const DevTask &t, int head, char *lds)
 {
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int rows = t.n_req * P.group;
-    const int tiles_per_wave = (rows + 127) >> 7;                       // ceil(rows / 128) row tiles of 16
-    const int row0 = wave * tiles_per_wave * 16;
-    int live = (rows - row0 + 15) >> 4;
-    live = live < 0 ? 0 : (live > tiles_per_wave ? tiles_per_wave : live);
-    switch (live) {
-    case 0: dense_wave<DT, 0>(P, t, head, lds, wave, row0, rows); break;
-    case 1: dense_wave<DT, 1>(P, t, head, lds, wave, row0, rows); break;
-    default: dense_wave<DT, 2>(P, t, head, lds, wave, row0, rows); break;
+    if (wave == 0) dense_wave<DT, 1>(P, t, head, lds, wave, 0, rows);
+    else           dense_wave<DT, 0>(P, t, head, lds, wave, 16 * wave, rows);
+}
+
+// ---- dense path with 32 query rows per wave ---------------------------------------------------------
+//
+// v_mfma_f32_32x32x16: A operand lane = (row lane%32, k-group lane/32), 8 k-values per lane; B operand
+// lane = (column lane%32, k-group lane/32); result register r of lane (column lane%32, group lane/32)
+// is row 8*(r/4) + 4*(lane/32) + r%4.  As in the 16-row tiles, S^T = K Q^T comes out with a query row
+// per lane column, which is the layout the B operand of O^T += V^T P^T wants: register 8t + i of the
+// scores becomes k-value i of k-step t, and the A operand (V^T) is read with the same token order.
+// Compared with 16 x 16 x 32 tiles a block costs half as many matrix instructions for the same
+// arithmetic; the path is bound by the instructions a wave can issue, not by the matrix unit.
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+
+template <int DT>
+__device__ __forceinline__ f32x16 mfma32(u32x4 a, u32x4 b, f32x16 c)
+{
+    if constexpr (DT == CODEC_DTYPE_FP16)
+        return __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8, a),
+                                                       __builtin_bit_cast(f16x8, b), c, 0, 0, 0);
+    else
+        return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a),
+                                                        __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
+}
+
+// Keeps the computation of `x` where it is written (the compiler otherwise sinks work whose result
+// is only used after the next barrier below that barrier).
+__device__ __forceinline__ void pin(u32x4 &x) { asm volatile("" : "+v"(x)); }
+__device__ __forceinline__ void pin(float &x) { asm volatile("" : "+v"(x)); }
+
+// One wave's share of a dense task.  LIVE: the wave owns task rows row0 .. row0+31 (otherwise it only
+// helps moving blocks; all eight waves run the same barriers).  VFIRST picks the order of the two
+// halves of a step; the two waves of a SIMD use opposite orders so that one's matrix work runs beside
+// the other's vector work.
+template <int DT, bool LIVE, bool VFIRST>
+__device__ __forceinline__ void dense32_wave(const PacParams &P, const DevTask &t, int head, char *lds,
+                                             int wave, int row0, int rows)
+{
+    static_assert(kRing == 8, "the waits below are written for a ring of 8 slots");
+    const int lane = threadIdx.x & 63;
+    const int l32 = lane & 31, kg = lane >> 5;
+    const int l16 = lane & 15, grp = lane >> 4;
+
+    u32x4 qb[8];            // B operand of the scores: row l32, channels 16*ks + 8*kg .. +7
+    f32x16 o[4];            // O^T: row l32, channel 32*ct + 8*(r/4) + 4*kg + r%4
+    float m = -INFINITY;    // reference, log2 units, integer-valued (same in the two lanes of a row)
+    float l = 0.f;          // this lane's share of the row sum
+    if constexpr (LIVE) {
+        const int row = row0 + l32;
+        const bool live = row < rows;
+        const int qi = live ? row / P.group : 0;
+        const int hj = live ? row - qi * P.group : 0;
+        const int req = P.node_q[t.q_off + qi];
+        const char *qp = static_cast<const char *>(P.q)
+                         + (int64_t(req) * P.h_q + int64_t(head) * P.group + hj) * (kHeadDim * 2) + kg * 16;
+#pragma unroll
+        for (int ks = 0; ks < 8; ++ks) qb[ks] = live ? ld16(qp + ks * 32) : u32x4{0u, 0u, 0u, 0u};
+#pragma unroll
+        for (int ct = 0; ct < 4; ++ct)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) o[ct][r] = 0.f;
     }
+    // every load the compiler knows about is complete before the first asynchronous copy is issued, so
+    // that it places no vector-memory wait of its own inside the loop (such a wait would also drain
+    // the copies in flight)
+    __builtin_amdgcn_s_waitcnt(0x0F70);
+    const SliceCtx c = make_ctx(P, t, head);
+
+    // Asynchronous copies.  Wave w moves tokens 4w .. 4w+3 of every block, 1 KB of K and 1 KB of V;
+    // lane (grp, l16) writes the 16-byte slot l16 of LDS row 4w + grp.  A K row keeps its 16-byte
+    // column g in slot g ^ (token & 15), a V row in slot g ^ (2*token & 15): the swizzles that make
+    // the operand reads below free of bank conflicts.
+    const uint32_t lds_base = uint32_t(uintptr_t(lds));
+    const int tok_w = wave * 4 + grp;
+    const uint32_t voff_k = uint32_t(grp) * c.token_bytes + uint32_t((l16 ^ (tok_w & 15)) << 4);
+    const uint32_t voff_v = uint32_t(grp) * c.token_bytes + uint32_t((l16 ^ ((2 * tok_w) & 15)) << 4);
+    // a group of four tokens past the end of the slice is redirected to token 0 (its rows are masked
+    // later) so that no address leaves the slice's pages
+    auto first_token = [&](int bb) {
+        const int tok0 = bb * 32 + wave * 4;
+        return tok0 >= c.kv_len ? 0 : tok0;
+    };
+    auto page_issue = [&](int bb) { return uniform_load(c.pages, first_token(bb) >> c.page_shift); };
+    auto dma_block = [&](int bb, int pg) {                              // pg: page id from page_issue(bb)
+        const int64_t off = page_offset(c, pg, first_token(bb) & c.page_mask);
+        const uint32_t slot = lds_base + uint32_t(bb % kRing) * kBlockBytes + uint32_t(wave) * 1024;
+        dma16(slot, voff_k, c.k_head + off);
+        dma16(slot + 8192, voff_v, c.v_head + off);
+    };
+
+    // Operand reads.
+    // K (A operand of the scores): lane (l32, kg) reads column 2*ks + kg of token row l32; with the
+    // swizzle its address is the ks = 0 address with (ks << 5) XORed in.
+    // V (A operand of the accumulation, channel tile ct, k-step t): ds_read_b64_tr_b16 hands lane i of a
+    // 16-lane group column i of the 4 x 16 tile whose row k the group's lanes 4k .. 4k+3 address 8 bytes
+    // apiece.  Lane group (kg, ch) = (lane/32, lane/16 % 2), lane (k, q) in it, addresses token
+    // 16*t + 8*h + 4*kg + k, channels 32*ct + 16*ch + 4*q .. +3: two reads (h = 0, 1) give the lane its
+    // channel 32*ct + lane%32 for the 8 tokens of its k-group.  ct is XORed into the address like ks.
+    const uint32_t ka_lane = uint32_t(l32 * 256 + ((kg ^ (l32 & 15)) << 4));
+    const int vk = l16 >> 2, vq = l16 & 3, vch = grp & 1;
+    const int vrow = 4 * kg + vk;
+    const uint32_t va_lane =
+        uint32_t(8192 + vrow * 256 + ((((2 * vch + (vq >> 1)) ^ (2 * vrow)) & 15) << 4) + 8 * (vq & 1));
+    u32x4 kr[8];            // K operands of one block, by k-step
+    u32x4 vr[4][2];         // V operands of one block, by channel tile and k-step
+    auto load_keys = [&](int bb) {
+        const uint32_t base = lds_base + uint32_t(bb % kRing) * kBlockBytes + ka_lane;
+#pragma unroll
+        for (int ks = 0; ks < 8; ++ks)
+            kr[ks] = *reinterpret_cast<const u32x4 __attribute__((address_space(3))) *>(uintptr_t(base ^ uint32_t(ks << 5)));
+    };
+    typedef __attribute__((ext_vector_type(4))) short s16x4;
+    typedef s16x4 __attribute__((address_space(3))) *lds_s16x4_ptr;
+    auto load_values = [&](int bb) {
+        const uint32_t base = lds_base + uint32_t(bb % kRing) * kBlockBytes + va_lane;
+#pragma unroll
+        for (int ct = 0; ct < 4; ++ct)
+#pragma unroll
+            for (int tt = 0; tt < 2; ++tt)
+#pragma unroll
+                for (int h = 0; h < 2; ++h) {
+                    const uint32_t addr = (base ^ uint32_t(ct << 6)) + tt * 4096 + h * 2048;
+                    const s16x4 x =
+                        __builtin_amdgcn_ds_read_tr16_b64_v4i16(reinterpret_cast<lds_s16x4_ptr>(uintptr_t(addr)));
+                    const uint2 w = __builtin_bit_cast(uint2, x);
+                    vr[ct][tt][2 * h] = w.x;
+                    vr[ct][tt][2 * h + 1] = w.y;
+                }
+    };
+    // tokens past `valid` count as zero in V (the slot may hold anything there, NaN patterns included)
+    // and as -inf in the scores
+    auto mask_values = [&](int valid) {
+#pragma unroll
+        for (int tt = 0; tt < 2; ++tt)
+#pragma unroll
+            for (int d = 0; d < 4; ++d) {
+                const int tok = 16 * tt + 8 * (d >> 1) + 4 * kg + 2 * (d & 1);  // low half; high half tok+1
+                const unsigned int keep = (tok < valid ? 0x0000FFFFu : 0u) | (tok + 1 < valid ? 0xFFFF0000u : 0u);
+#pragma unroll
+                for (int ct = 0; ct < 4; ++ct) vr[ct][tt][d] &= keep;
+            }
+    };
+    auto mask_scores32 = [&](f32x16 &s, int valid) {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const bool dead = 8 * (r >> 2) + 4 * kg + (r & 3) >= valid;
+            s[r] = dead ? -INFINITY : s[r];
+        }
+    };
+
+    // The matrix half of a step: O^T += V^T P^T of the block in vr (ACC) and the scores of the block in
+    // kr; the two alternate so that no instruction waits for the one before it.
+    f32x16 s;               // scores: row l32, token 8*(r/4) + 4*kg + r%4
+    u32x4 p[2];             // probabilities, B operand: k-step t holds registers 8t .. 8t+7 of the scores
+    auto matrix_half = [&](auto acc_tag) {
+        f32x16 acc;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[r] = 0.f;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            if constexpr (decltype(acc_tag)::value) o[i & 3] = mfma32<DT>(vr[i & 3][i >> 2], p[i >> 2], o[i & 3]);
+            acc = mfma32<DT>(kr[i], qb[i], acc);
+        }
+        s = acc;
+    };
+    auto accumulate32 = [&]() {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) o[i & 3] = mfma32<DT>(vr[i & 3][i >> 2], p[i >> 2], o[i & 3]);
+    };
+    // The vector half: the lane's maximum over its 16 scores; when a row has outgrown its reference by
+    // more than the lag, the reference moves up to the (rounded-up) row maximum and everything
+    // accumulated against the old one is rescaled; then P = exp2(scale * S - m) in B-operand layout
+    // and the lane's share of the row sum.
+    auto vector_half = [&]() {
+        float a = __builtin_fmaxf(__builtin_fmaxf(s[0], s[1]), s[2]);
+#pragma unroll
+        for (int r = 3; r + 1 < 16; r += 2) a = __builtin_fmaxf(__builtin_fmaxf(a, s[r]), s[r + 1]);
+        const float lm = __builtin_fmaxf(a, s[15]) * P.scale_log2e;
+        if (__any(lm > m + kLag)) {
+            const float mx = fmaxf(lm, __shfl_xor(lm, 32));
+            const float m_new = __builtin_ceilf(fmaxf(m, mx));
+            const float alpha = fast_exp2(m - m_new);                   // 0 on the first block (m = -inf)
+            l *= alpha;
+#pragma unroll
+            for (int ct = 0; ct < 4; ++ct)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) o[ct][r] *= alpha;
+            m = m_new;
+        }
+        float e[16];
+#pragma unroll
+        for (int r = 0; r < 16; ++r) e[r] = fast_exp2(__builtin_fmaf(s[r], P.scale_log2e, -m));
+        l += (((e[0] + e[1]) + (e[2] + e[3])) + ((e[4] + e[5]) + (e[6] + e[7])))
+             + (((e[8] + e[9]) + (e[10] + e[11])) + ((e[12] + e[13]) + (e[14] + e[15])));
+#pragma unroll
+        for (int tt = 0; tt < 2; ++tt)
+#pragma unroll
+            for (int d = 0; d < 4; ++d) p[tt][d] = pack2<DT>(e[8 * tt + 2 * d], e[8 * tt + 2 * d + 1]);
+        pin(p[0]);
+        pin(p[1]);
+        pin(l);
+    };
+
+    // Schedule.  Blocks 0 .. 7 are requested up front; interval b (b = 0 .. nblk-2) starts with a
+    // barrier behind which block b+8 is requested into the slot block b has left.  Per block a wave
+    // runs a vector half V(b) (scores of block b -> probabilities) and a matrix half M(b) (accumulation
+    // of block b, alternating with the scores of block b+1), in the order V(0) M(0) V(1) M(1) ...; right
+    // after M(b) has read its operands the operands of M(b+1) (K of block b+2, V of block b+1) are
+    // requested from LDS, to arrive during V(b+1).  A VFIRST wave places the barrier of interval b
+    // before V(b), the others before M(b): the two waves of a SIMD run in opposite phases, one's
+    // matrix work beside the other's vector work.  Either way block b+2 must have landed at the
+    // barrier of interval b: each wave issues 2 loads per block and loads complete in order, so it has
+    // once at most 2 * (blocks issued after it) loads are outstanding; near the end of the slice,
+    // where fewer than 5 blocks follow, the wait is for everything.
+    const int nblk = (t.kv_len + 31) >> 5;
+    {
+        int pg[kRing];
+#pragma unroll
+        for (int d = 0; d < kRing; ++d) pg[d] = page_issue(d < nblk ? d : 0);
+#pragma unroll
+        for (int d = 0; d < kRing; ++d)
+            if (d < nblk) dma_block(d, pg[d]);
+    }
+    int pg_next = page_issue(kRing < nblk ? kRing : 0);                 // page of the block interval 0 requests
+    if (nblk >= kRing) __builtin_amdgcn_s_waitcnt(0x0F7C);              // vmcnt(12): blocks 0 and 1 have landed
+    else               __builtin_amdgcn_s_waitcnt(0x0F70);
+    __syncthreads();
+
+    auto enter_interval = [&](int b) {                                  // b + 1 < nblk
+        const bool more = b + kRing < nblk;
+        if (more) __builtin_amdgcn_s_waitcnt(0x0F7A);                   // vmcnt(10): 5 blocks follow block b+2
+        else      __builtin_amdgcn_s_waitcnt(0x0F70);
+        __syncthreads();                    // block b+2 is complete; everyone is done with block b
+        if (more) {
+            dma_block(b + kRing, pg_next);
+            pg_next = page_issue(b + kRing + 1 < nblk ? b + kRing + 1 : 0);
+        }
+    };
+
+    if constexpr (LIVE) {
+        using yes = std::true_type;
+        using no = std::false_type;
+        auto vector_half_of = [&](int b) {                              // masks a short last block first
+            const int valid = c.kv_len - b * 32;
+            if (valid < 32) mask_scores32(s, valid);
+            vector_half();
+        };
+        auto matrix_half_and_loads = [&](int b) {                       // M(b), b + 1 < nblk
+            matrix_half(yes{});
+            __builtin_amdgcn_sched_barrier(0);
+            load_keys(b + 2);
+            load_values(b + 1);
+            __builtin_amdgcn_sched_barrier(0);
+        };
+
+        load_keys(0);
+        matrix_half(no{});
+        __builtin_amdgcn_sched_barrier(0);
+        load_keys(1);
+        load_values(0);
+        __builtin_amdgcn_sched_barrier(0);
+        if constexpr (VFIRST) {
+#pragma unroll 1
+            for (int b = 0; b + 1 < nblk; ++b) {
+                enter_interval(b);
+                vector_half_of(b);
+                __builtin_amdgcn_sched_barrier(0);
+                matrix_half_and_loads(b);
+            }
+            vector_half_of(nblk - 1);
+        } else {
+            vector_half_of(0);
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll 1
+            for (int b = 0; b + 1 < nblk; ++b) {
+                enter_interval(b);
+                matrix_half_and_loads(b);
+                vector_half_of(b + 1);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        }
+        const int valid = c.kv_len - (nblk - 1) * 32;
+        if (valid < 32) mask_values(valid);
+        accumulate32();
+
+        l += __shfl_xor(l, 32);
+        const int row = row0 + l32;
+        if (row < rows) {
+            const int64_t prow = int64_t(head) * P.part_rows + t.part_row_base + row;
+            float *po = P.part_o + prow * kHeadDim + kg * 4;
+#pragma unroll
+            for (int ct = 0; ct < 4; ++ct)
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const f32x4 x = {o[ct][4 * q], o[ct][4 * q + 1], o[ct][4 * q + 2], o[ct][4 * q + 3]};
+                    *reinterpret_cast<f32x4 *>(po + ct * 32 + q * 8) = x;
+                }
+            if (kg == 0) {
+                float2 ml = {m, l};
+                *reinterpret_cast<float2 *>(P.part_ml + prow * 2) = ml;
+            }
+        }
+    } else {
+#pragma unroll 1
+        for (int b = 0; b + 1 < nblk; ++b) enter_interval(b);
+    }
+    __syncthreads();                        // the ring is reused by the slot's next task
+}
+
+template <int DT>
+__device__ void run_dense32(const PacParams &P, const DevTask &t, int head, char *lds)
+{
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int rows = t.n_req * P.group;
+    const int row0 = wave * 32;
+    if (row0 >= rows)  dense32_wave<DT, false, false>(P, t, head, lds, wave, row0, rows);
+    else if (wave & 4) dense32_wave<DT, true, true>(P, t, head, lds, wave, row0, rows);
+    else               dense32_wave<DT, true, false>(P, t, head, lds, wave, row0, rows);
 }
 
 // WIDE: kRingBytes of dynamic LDS.  The dense path XORs the channel tile into operand addresses, so
@@ -744,10 +1057,12 @@ __global__ void __launch_bounds__(WIDE ? kWideWaves * 64 : kNarrowWaves * 64, 2)
     for (int i = t0; i < t1; ++i) {
         const DevTask t = P.tasks[P.slot_tasks[i]];
         const int rows = t.n_req * P.group;
-        if constexpr (WIDE != 0)
-            run_dense<DT>(P, t, head, lds);
-        else if (rows <= 16)
+        if constexpr (WIDE != 0) {
+            if (rows <= 16) run_dense16<DT>(P, t, head, lds);
+            else            run_dense32<DT>(P, t, head, lds);
+        } else if (rows <= 16) {
             run_stream<DT, 1, W>(P, t, head, lds);
+        }
     }
 }
 
