@@ -181,6 +181,9 @@ int codec_partial_attention(const codec_plan_t *plan, const void *q, const void 
     if (layout->page_stride < 1 || layout->token_stride < 128 || layout->head_stride < 128 ||
         layout->page_stride % 8 || layout->token_stride % 8 || layout->head_stride % 8)
         return CODEC_ERR_INVALID_ARGUMENT;
+    // the kernels keep a page's and a token's size in bytes in 32 bits
+    if (layout->page_stride > (int64_t(1) << 30) || layout->token_stride > (int64_t(1) << 30))
+        return CODEC_ERR_INVALID_ARGUMENT;
 
     const char *meta = static_cast<const char *>(plan->device_meta);
     const codec::DevLayout &L = d.layout;

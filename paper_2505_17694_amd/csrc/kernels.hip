@@ -8,26 +8,25 @@
 // (the on-chip query assembly of Sec. 4.1).  Every K and V byte of the slice is
 // fetched from HBM once per task and serves all rows.
 //
-// Arithmetic of one 32-token block, per wave: S^T = K Q^T (tokens x rows) with
-// v_mfma_f32_16x16x32, K rows as the A operand (16-byte pieces in operand
-// layout), Q as the B operand.  The accumulator layout (lane = row, 4 tokens per
-// lane and 16-token tile) is already the B-operand layout of the second product
-// O^T = V^T P^T once the eight tokens a lane holds are taken as its k-slice, so P
-// never moves between lanes.  V is fetched with the matching token-to-lane map
-// (lane group G takes tokens 4G..4G+3 of both tiles, 16 bytes = 8 channels each)
-// and becomes the A operand by an 8x8 16-bit transpose inside each lane
-// (v_perm_b32).  A lane ends up owning 32 consecutive channels of one row.
-// Softmax statistics stay in fp32, in log2 units.
+// Arithmetic of one 32-token block, per wave: S^T = K Q^T (tokens x rows) on the
+// matrix unit, K rows as the A operand, Q as the B operand.  The accumulator
+// layout (a query row per lane column, several tokens per lane) is already the
+// B-operand layout of the second product O^T = V^T P^T once the tokens a lane
+// holds are taken as its k-slice, so P never moves between lanes; V is brought in
+// with the matching token-to-lane map.  Softmax statistics stay in fp32, in log2
+// units.
 //
 // Two task shapes share that arithmetic:
 //  * "stream" (plans whose tasks all have at most 16 rows, e.g. the flat baseline):
-//    four waves take interleaved 32-token blocks of the slice, each with all rows;
-//    K and V go from HBM straight to registers (no LDS in the loop); the waves'
-//    states are merged through LDS at the end.
-//  * "dense" (every other plan, tasks of 1..256 rows): eight waves split the rows
-//    (up to 32 each) and walk the slice together; blocks are copied HBM -> LDS
-//    asynchronously into a ring of eight 16 KB slots (seven blocks in flight, one
-//    barrier per block) and read by all waves.
+//    16 x 16 x 32 tiles; four waves take interleaved 32-token blocks of the slice,
+//    each with all rows; K and V go from HBM straight to registers (no LDS in the
+//    loop; V becomes an A operand by an 8x8 16-bit transpose inside each lane,
+//    v_perm_b32); the waves' states are merged through LDS at the end.
+//  * "dense" (every other plan, tasks of 1..256 rows): 32 x 32 x 16 tiles; eight
+//    waves split the rows (32 each) and walk the slice together; blocks are copied
+//    HBM -> LDS asynchronously into a ring of eight 16 KB slots (six blocks in
+//    flight, one barrier per block) and read by all waves, V through transposing
+//    LDS reads (ds_read_b64_tr_b16).
 #include <hip/hip_runtime.h>
 
 #include <type_traits>
@@ -84,7 +83,7 @@ struct SliceCtx {
     const char *k_head;         // K pool + KV-head offset
     const char *v_head;
     const int32_t *pages;       // page ids of the slice, first page first
-    int64_t page_bytes;
+    uint32_t page_bytes;
     uint32_t token_bytes;
     int32_t kv_len;
     int32_t page_shift;         // log2(page_size)
@@ -99,13 +98,13 @@ struct SliceCtx {
 __device__ __forceinline__ int uniform_load(const int32_t *p, int index)
 {
     typedef const int32_t __attribute__((address_space(4))) *const_i32_ptr;
-    return ((const_i32_ptr)(uintptr_t)p)[__builtin_amdgcn_readfirstlane(index)];
+    return ((const_i32_ptr)(uintptr_t)p)[uint32_t(__builtin_amdgcn_readfirstlane(index))];
 }
 
 // Byte offset of a page slot: page id `pg`, token slot `slot` inside the page (wave-uniform).
 __device__ __forceinline__ int64_t page_offset(const SliceCtx &c, int pg, int slot)
 {
-    return int64_t(pg) * c.page_bytes + int64_t(slot) * c.token_bytes;
+    return int64_t(uint64_t(uint32_t(pg)) * c.page_bytes + uint64_t(uint32_t(slot) * c.token_bytes));
 }
 
 // K and V registers of one 32-token block (stream path).
@@ -375,7 +374,7 @@ __device__ __forceinline__ SliceCtx make_ctx(const PacParams &P, const DevTask &
     c.k_head = static_cast<const char *>(P.k_pages) + int64_t(head) * P.head_stride * 2;
     c.v_head = static_cast<const char *>(P.v_pages) + int64_t(head) * P.head_stride * 2;
     c.pages = P.page_ids + t.page_off;
-    c.page_bytes = P.page_stride * 2;
+    c.page_bytes = uint32_t(P.page_stride * 2);
     c.token_bytes = uint32_t(P.token_stride * 2);
     c.kv_len = t.kv_len;
     c.page_shift = P.page_shift;
@@ -486,14 +485,14 @@ __device__ void run_stream(const PacParams &P, const DevTask &t, int head, char 
     if (wave == 0) store_partial<NT, false>(P, t, head, 0, rows, l16, grp, st);
 }
 
-// ---- dense path: 1..256 rows, the 8 waves split the rows (up to 32 each) and share each block -----
+// ---- dense path: 1..256 rows, the 8 waves split the rows (32 each) and share each block ------------
 //
 // Blocks travel HBM -> LDS without passing through registers (global_load_lds_dwordx4: every lane
 // moves 16 bytes, a wave fills 1 KB of consecutive LDS).  A ring of kRing block slots (16 KB each:
-// 32 K rows then 32 V rows of 256 B) keeps kRing-1 blocks in flight per workgroup.  Rows are stored
-// unpadded; the 16-byte column index is XORed with (row & 15) so that both operand read patterns
-// (16 lanes down a column for K, 16 lanes along a row for V) spread over all banks.  The swizzle is
-// applied on the global side: the lane that fills LDS column c of row r fetches column c ^ (r & 15).
+// 32 K rows then 32 V rows of 256 B) keeps up to kRing-2 blocks in flight per workgroup.  Rows are
+// stored unpadded; the 16-byte column index is XORed with a function of the row so that the operand
+// reads spread over all banks.  The swizzle is applied on the global side: the lane that fills LDS
+// column c of a row fetches column c ^ f(row).
 //
 // The compiler does not see these loads (inline asm), so the waits are explicit: loads complete in
 // issue order, block b is in LDS once at most 2 * (blocks issued after b) of the wave's loads are
@@ -501,221 +500,27 @@ __device__ void run_stream(const PacParams &P, const DevTask &t, int head, char 
 constexpr int kRing = 8;
 constexpr int kBlockBytes = 16384;
 constexpr int kRingBytes = kRing * kBlockBytes;
+// s_waitcnt immediate that waits for the vector-memory counter only (gfx9 encoding: bits 3:0 and 15:14)
+constexpr int vmcnt_imm(int n) { return (n & 15) | ((n >> 4) << 14) | 0x0F70; }
 
-__device__ __forceinline__ void dma16(uint32_t lds_addr, uint32_t voff, const char *gbase)
+// One block's K piece and V piece for this wave: each lane fetches 16 bytes at gk + voff_k (gv + voff_v)
+// and the wave's 64 pieces land in 1 KB of consecutive LDS at lds_addr (the V piece 8 KB behind).  M0
+// holds the LDS address for the instruction and is put back afterwards.
+__device__ __forceinline__ void dma16_pair(uint32_t lds_addr, uint32_t voff_k, uint32_t voff_v, const char *gk,
+                                           const char *gv)
 {
     uint32_t m0_saved;
     asm volatile("s_mov_b32 %0, m0\n\t"
                  "s_mov_b32 m0, %1\n\t"
                  "s_nop 0\n\t"
-                 "global_load_lds_dwordx4 %2, %3\n\t"
+                 "global_load_lds_dwordx4 %2, %4\n\t"
+                 "s_add_u32 m0, m0, 0x2000\n\t"
+                 "s_nop 0\n\t"
+                 "global_load_lds_dwordx4 %3, %5\n\t"
                  "s_mov_b32 m0, %0\n"
                  : "=&s"(m0_saved)
-                 : "s"(lds_addr), "v"(voff), "s"(gbase)
-                 : "memory");
-}
-
-// One wave's share of a dense task: NL live row tiles starting at task row `row0` (NL = 0: the wave
-// only helps moving blocks).  All eight waves run the same number of barriers.
-template <int DT, int NL>
-__device__ __forceinline__ void dense_wave(const PacParams &P, const DevTask &t, int head, char *lds,
-                                           int wave, int row0, int rows)
-{
-    static_assert(kRing == 8, "the waits below are written for a ring of 8 slots");
-    const int lane = threadIdx.x & 63;
-    const int l16 = lane & 15, grp = lane >> 4;
-    constexpr int NQ = NL > 0 ? NL : 1;
-
-    u32x4 qb[NQ][4];
-    RowState<NQ> st;
-    if constexpr (NL > 0) {
-        gather_q<NL>(P, t, head, row0, rows, l16, grp, qb);
-        st.clear();
-    }
-    // every load the compiler knows about is complete before the first asynchronous copy is issued, so
-    // that it places no vector-memory wait of its own inside the loop (such a wait would also drain
-    // the copies in flight)
-    __builtin_amdgcn_s_waitcnt(0x0F70);
-    const SliceCtx c = make_ctx(P, t, head);
-
-    // wave w moves rows 4w .. 4w+3 of every block: one 1 KB piece of K and one of V
-    const uint32_t lds_base = uint32_t(uintptr_t(lds));
-    const int key = (wave * 4 + grp) & 15;                              // destination row & 15
-    const uint32_t voff = uint32_t(grp) * c.token_bytes + uint32_t((l16 ^ key) << 4);
-    // token (slice-relative) at which this wave's four rows of block bb start; a group past the end of
-    // the slice is redirected to token 0 (its rows are masked later) so that no address leaves the pages
-    auto first_token = [&](int bb) {
-        const int tok0 = bb * 32 + wave * 4;
-        return tok0 >= c.kv_len ? 0 : tok0;
-    };
-    auto page_issue = [&](int bb) { return uniform_load(c.pages, first_token(bb) >> c.page_shift); };
-    auto dma_block = [&](int bb, int pg) {                              // pg: page id from page_issue(bb)
-        const int64_t off = page_offset(c, pg, first_token(bb) & c.page_mask);
-        const uint32_t slot = lds_base + uint32_t(bb % kRing) * kBlockBytes + uint32_t(wave) * 1024;
-        dma16(slot, voff, c.k_head + off);
-        dma16(slot + 8192, voff, c.v_head + off);
-    };
-    // Lane-dependent parts of the operand addresses (the slot base is added per block).
-    // K: lane (grp, l16) reads the 16-byte column 4*ks + grp of row l16 of a tile.
-    // V: ds_read_b64_tr_b16 hands lane i of a 16-lane group the i-th 16-bit column of the 4 x 16 tile
-    //    whose row k the group's lanes 4k .. 4k+3 address 8 bytes (4 columns) apiece.  Lane (k, q)
-    //    therefore addresses token 4*grp + k, channels 16*dt + 4*q .. +3, and every lane receives its
-    //    own channel 16*dt + l16 for tokens 4*grp .. 4*grp+3: the A operand of O^T += V^T P^T without
-    //    a single vector instruction.  With the column swizzle the address for channel tile dt is the
-    //    address for tile 0 with (dt << 5) XORed in.
-    uint32_t ka_off[4];
-#pragma unroll
-    for (int x = 0; x < 4; ++x) ka_off[x] = uint32_t(l16 * 256 + (((x * 4 + grp) ^ l16) << 4));
-    const int vk = l16 >> 2, vq = l16 & 3, vrow = grp * 4 + vk;
-    const uint32_t va_off = uint32_t(8192 + vrow * 256 + ((((vq >> 1) ^ vrow) & 15) << 4) + 8 * (vq & 1));
-    auto scores = [&](int bb, f32x4 (&s)[2][NQ]) {                      // S^T of block bb from its slot
-        const char *buf = lds + (bb % kRing) * kBlockBytes;
-#pragma unroll
-        for (int j = 0; j < 2; ++j) {
-            u32x4 ka[4];
-#pragma unroll
-            for (int ks = 0; ks < 4; ++ks)
-                ka[ks] = *reinterpret_cast<const u32x4 *>(buf + j * 4096 + ka_off[ks]);
-#pragma unroll
-            for (int nt = 0; nt < NQ; ++nt) {
-                f32x4 acc = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-                for (int ks = 0; ks < 4; ++ks) acc = mfma16<DT>(ka[ks], qb[nt][ks], acc);
-                s[j][nt] = acc;
-            }
-        }
-    };
-    // A operand of channel tile dt of block bb: 8 tokens (4 of each 16-token tile) of channel
-    // 16*dt + l16; tokens past `valid` count as zero
-    typedef __attribute__((ext_vector_type(4))) short s16x4;
-    typedef s16x4 __attribute__((address_space(3))) *lds_s16x4_ptr;
-    auto value_tile = [&](uint32_t slot_addr, int dt, int valid) {
-        u32x4 va;
-#pragma unroll
-        for (int j = 0; j < 2; ++j) {
-            const uint32_t addr = (slot_addr ^ uint32_t(dt << 5)) + j * 4096;
-            const s16x4 x = __builtin_amdgcn_ds_read_tr16_b64_v4i16(reinterpret_cast<lds_s16x4_ptr>(uintptr_t(addr)));
-            const uint2 w = __builtin_bit_cast(uint2, x);
-            va[2 * j] = w.x;
-            va[2 * j + 1] = w.y;
-        }
-        if (valid < 32) {
-#pragma unroll
-            for (int j = 0; j < 2; ++j)
-#pragma unroll
-                for (int h = 0; h < 2; ++h) {
-                    const int tok = j * 16 + grp * 4 + 2 * h;       // tokens tok (low half), tok+1 (high half)
-                    const unsigned int keep = (tok < valid ? 0x0000FFFFu : 0u) | (tok + 1 < valid ? 0xFFFF0000u : 0u);
-                    va[2 * j + h] &= keep;
-                }
-        }
-        return va;
-    };
-    // O^T += V^T P^T for block bb
-    auto accumulate_block = [&](int bb, int valid, const u32x4 (&pb)[NQ]) {
-        const uint32_t slot_addr = lds_base + uint32_t(bb % kRing) * kBlockBytes + va_off;
-#pragma unroll
-        for (int dt = 0; dt < 8; ++dt) {
-            const u32x4 va = value_tile(slot_addr, dt, valid);
-#pragma unroll
-            for (int nt = 0; nt < NQ; ++nt) st.o[nt][dt] = mfma16<DT>(va, pb[nt], st.o[nt][dt]);
-        }
-    };
-
-    // Schedule.  The slots hold blocks b .. b+kRing-1 while block b is being worked on.  A step works on
-    // block b with its scores already in registers: behind one barrier it (1) refills the slot block
-    // b-1 has left, (2) computes the scores of block b+1 on the matrix unit while the vector unit turns
-    // the scores of block b into probabilities, and (3) accumulates block b.  The wait before the
-    // barrier is for block b+1: each wave issues 2 loads per block, loads complete in order, so block
-    // b+1 has landed once at most 2 * (blocks issued after it) loads are outstanding; when fewer than
-    // kRing-3 blocks were issued after it the wait is for everything.
-    const int nblk = (t.kv_len + 31) >> 5;
-    {
-        int pg[kRing];
-#pragma unroll
-        for (int d = 0; d < kRing; ++d) pg[d] = page_issue(d < nblk ? d : 0);
-#pragma unroll
-        for (int d = 0; d < kRing; ++d)
-            if (d < nblk) dma_block(d, pg[d]);
-    }
-    // page id of the block the next step will request (block kRing at step 1), loaded a step ahead
-    int pg_next = page_issue(kRing < nblk ? kRing : 0);
-    switch (nblk < kRing ? nblk - 1 : kRing - 1) {                      // blocks issued after block 0
-    case 0: __builtin_amdgcn_s_waitcnt(0x0F70); break;
-    case 1: __builtin_amdgcn_s_waitcnt(0x0F72); break;
-    case 2: __builtin_amdgcn_s_waitcnt(0x0F74); break;
-    case 3: __builtin_amdgcn_s_waitcnt(0x0F76); break;
-    case 4: __builtin_amdgcn_s_waitcnt(0x0F78); break;
-    case 5: __builtin_amdgcn_s_waitcnt(0x0F7A); break;
-    case 6: __builtin_amdgcn_s_waitcnt(0x0F7C); break;
-    default: __builtin_amdgcn_s_waitcnt(0x0F7E); break;
-    }
-    __syncthreads();
-
-    auto enter_step = [&](int b) {                                      // b + 1 < nblk
-        if (nblk - b >= kRing - 1) __builtin_amdgcn_s_waitcnt(0x0F7A);  // vmcnt(10): kRing-3 blocks behind
-        else                       __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0)
-        __syncthreads();                    // block b+1 is complete; everyone is done with block b-1
-        if (b >= 1) {
-            if (b - 1 + kRing < nblk) dma_block(b - 1 + kRing, pg_next);
-            pg_next = page_issue(b + kRing < nblk ? b + kRing : 0);
-        }
-    };
-
-    if constexpr (NL > 0) {
-        f32x4 sa[2][NL], sb[2][NL];
-        float lma[NL], lmb[NL];
-        auto step = [&](int b, f32x4 (&s_cur)[2][NL], float (&lm_cur)[NL],
-                        f32x4 (&s_nxt)[2][NL], float (&lm_nxt)[NL]) {   // full block b, b + 1 < nblk
-            enter_step(b);
-            if (__any(outgrown<NL>(lm_cur, st))) raise_reference<NL>(lm_cur, st);
-            u32x4 pb[NL];
-            scores(b + 1, s_nxt);
-            probabilities<DT, NL, true>(s_cur, st, P.scale_log2e, pb);
-            accumulate_block(b, 32, pb);
-            const int valid_nxt = c.kv_len - (b + 1) * 32;
-            if (valid_nxt < 32) mask_scores<NL>(s_nxt, valid_nxt, grp);
-            lane_maxima<NL>(s_nxt, P.scale_log2e, lm_nxt);
-        };
-        auto last = [&](int b, f32x4 (&s_cur)[2][NL], float (&lm_cur)[NL]) {
-            if (__any(outgrown<NL>(lm_cur, st))) raise_reference<NL>(lm_cur, st);
-            u32x4 pb[NL];
-            probabilities<DT, NL, true>(s_cur, st, P.scale_log2e, pb);
-            accumulate_block(b, c.kv_len - b * 32, pb);
-        };
-
-        scores(0, sa);
-        if (c.kv_len < 32) mask_scores<NL>(sa, c.kv_len, grp);
-        lane_maxima<NL>(sa, P.scale_log2e, lma);
-        int b = 0;
-#pragma unroll 1
-        for (; b + 2 < nblk; b += 2) {
-            step(b, sa, lma, sb, lmb);
-            step(b + 1, sb, lmb, sa, lma);
-        }
-        if (b + 1 < nblk) {
-            step(b, sa, lma, sb, lmb);
-            last(b + 1, sb, lmb);
-        } else {
-            last(b, sa, lma);
-        }
-        st.template finish<false>();
-        store_partial<NL, true>(P, t, head, row0, rows, l16, grp, st);
-    } else {
-#pragma unroll 1
-        for (int b = 0; b + 1 < nblk; ++b) enter_step(b);
-    }
-    __syncthreads();                        // the ring is reused by the slot's next task
-}
-
-// A dense task of at most 16 rows: wave 0 computes, the others help moving blocks.
-template <int DT>
-__device__ void run_dense16(const PacParams &P, const DevTask &t, int head, char *lds)
-{
-    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int rows = t.n_req * P.group;
-    if (wave == 0) dense_wave<DT, 1>(P, t, head, lds, wave, 0, rows);
-    else           dense_wave<DT, 0>(P, t, head, lds, wave, 16 * wave, rows);
+                 : "s"(lds_addr), "v"(voff_k), "v"(voff_v), "s"(gk), "s"(gv)
+                 : "memory", "scc");
 }
 
 // ---- dense path with 32 query rows per wave ---------------------------------------------------------
@@ -745,15 +550,17 @@ __device__ __forceinline__ f32x16 mfma32(u32x4 a, u32x4 b, f32x16 c)
 __device__ __forceinline__ void pin(u32x4 &x) { asm volatile("" : "+v"(x)); }
 __device__ __forceinline__ void pin(float &x) { asm volatile("" : "+v"(x)); }
 
-// One wave's share of a dense task.  LIVE: the wave owns task rows row0 .. row0+31 (otherwise it only
-// helps moving blocks; all eight waves run the same barriers).  VFIRST picks the order of the two
-// halves of a step; the two waves of a SIMD use opposite orders so that one's matrix work runs beside
-// the other's vector work.
-template <int DT, bool LIVE, bool VFIRST>
+// Roles of a wave in a dense task.  A wave with rows owns 32 of them and takes every block; in the two
+// live roles the halves of a step come in opposite orders, for the two waves of a SIMD.  Waves without
+// rows only help moving blocks.  All eight waves run the same barriers.
+enum { kHelper = 0, kMatrixFirst = 1, kVectorFirst = 2 };
+
+// One wave's share of a dense task: task rows row0 .. row0+31 (none for a helper).
+template <int DT, int ROLE>
 __device__ __forceinline__ void dense32_wave(const PacParams &P, const DevTask &t, int head, char *lds,
                                              int wave, int row0, int rows)
 {
-    static_assert(kRing == 8, "the waits below are written for a ring of 8 slots");
+    constexpr bool LIVE = ROLE != kHelper;
     const int lane = threadIdx.x & 63;
     const int l32 = lane & 31, kg = lane >> 5;
     const int l16 = lane & 15, grp = lane >> 4;
@@ -801,8 +608,7 @@ __device__ __forceinline__ void dense32_wave(const PacParams &P, const DevTask &
     auto dma_block = [&](int bb, int pg) {                              // pg: page id from page_issue(bb)
         const int64_t off = page_offset(c, pg, first_token(bb) & c.page_mask);
         const uint32_t slot = lds_base + uint32_t(bb % kRing) * kBlockBytes + uint32_t(wave) * 1024;
-        dma16(slot, voff_k, c.k_head + off);
-        dma16(slot + 8192, voff_v, c.v_head + off);
+        dma16_pair(slot, voff_k, voff_v, c.k_head + off, c.v_head + off);
     };
 
     // Operand reads.
@@ -865,30 +671,40 @@ __device__ __forceinline__ void dense32_wave(const PacParams &P, const DevTask &
         }
     };
 
-    // The matrix half of a step: O^T += V^T P^T of the block in vr (ACC) and the scores of the block in
-    // kr; the two alternate so that no instruction waits for the one before it.
     f32x16 s;               // scores: row l32, token 8*(r/4) + 4*kg + r%4
     u32x4 p[2];             // probabilities, B operand: k-step t holds registers 8t .. 8t+7 of the scores
-    auto matrix_half = [&](auto acc_tag) {
+    auto scores32 = [&]() {
         f32x16 acc;
 #pragma unroll
         for (int r = 0; r < 16; ++r) acc[r] = 0.f;
 #pragma unroll
-        for (int i = 0; i < 8; ++i) {
-            if constexpr (decltype(acc_tag)::value) o[i & 3] = mfma32<DT>(vr[i & 3][i >> 2], p[i >> 2], o[i & 3]);
-            acc = mfma32<DT>(kr[i], qb[i], acc);
-        }
+        for (int i = 0; i < 8; ++i) acc = mfma32<DT>(kr[i], qb[i], acc);
         s = acc;
     };
     auto accumulate32 = [&]() {
 #pragma unroll
         for (int i = 0; i < 8; ++i) o[i & 3] = mfma32<DT>(vr[i & 3][i >> 2], p[i >> 2], o[i & 3]);
     };
-    // The vector half: the lane's maximum over its 16 scores; when a row has outgrown its reference by
-    // more than the lag, the reference moves up to the (rounded-up) row maximum and everything
-    // accumulated against the old one is rescaled; then P = exp2(scale * S - m) in B-operand layout
-    // and the lane's share of the row sum.
-    auto vector_half = [&]() {
+    // The matrix half of a FULL step: O^T += V^T P^T of the block in vr and the scores of the block in
+    // kr; the two alternate so that no instruction waits for the one before it.
+    auto matrix_half = [&]() {
+        f32x16 acc;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[r] = 0.f;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            o[i & 3] = mfma32<DT>(vr[i & 3][i >> 2], p[i >> 2], o[i & 3]);
+            acc = mfma32<DT>(kr[i], qb[i], acc);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        s = acc;
+    };
+    // The vector work of a block, in three pieces.  reference(): the lane's maximum over its 16 scores;
+    // when a row has outgrown its reference by more than the lag, the reference moves up to the
+    // (rounded-up) row maximum and everything accumulated against the old one is rescaled.
+    // probabilities(t): P = exp2(scale * S - m) for k-step t in B-operand layout, and the lane's share
+    // of the row sum.
+    auto reference = [&]() {
         float a = __builtin_fmaxf(__builtin_fmaxf(s[0], s[1]), s[2]);
 #pragma unroll
         for (int r = 3; r + 1 < 16; r += 2) a = __builtin_fmaxf(__builtin_fmaxf(a, s[r]), s[r + 1]);
@@ -904,31 +720,24 @@ __device__ __forceinline__ void dense32_wave(const PacParams &P, const DevTask &
                 for (int r = 0; r < 16; ++r) o[ct][r] *= alpha;
             m = m_new;
         }
-        float e[16];
+    };
+    auto probabilities32 = [&](int tt) {
+        float e[8];
 #pragma unroll
-        for (int r = 0; r < 16; ++r) e[r] = fast_exp2(__builtin_fmaf(s[r], P.scale_log2e, -m));
-        l += (((e[0] + e[1]) + (e[2] + e[3])) + ((e[4] + e[5]) + (e[6] + e[7])))
-             + (((e[8] + e[9]) + (e[10] + e[11])) + ((e[12] + e[13]) + (e[14] + e[15])));
+        for (int i = 0; i < 8; ++i) e[i] = fast_exp2(__builtin_fmaf(s[8 * tt + i], P.scale_log2e, -m));
+        l += ((e[0] + e[1]) + (e[2] + e[3])) + ((e[4] + e[5]) + (e[6] + e[7]));
 #pragma unroll
-        for (int tt = 0; tt < 2; ++tt)
-#pragma unroll
-            for (int d = 0; d < 4; ++d) p[tt][d] = pack2<DT>(e[8 * tt + 2 * d], e[8 * tt + 2 * d + 1]);
-        pin(p[0]);
-        pin(p[1]);
+        for (int d = 0; d < 4; ++d) p[tt][d] = pack2<DT>(e[2 * d], e[2 * d + 1]);
+        pin(p[tt]);
         pin(l);
     };
 
-    // Schedule.  Blocks 0 .. 7 are requested up front; interval b (b = 0 .. nblk-2) starts with a
-    // barrier behind which block b+8 is requested into the slot block b has left.  Per block a wave
-    // runs a vector half V(b) (scores of block b -> probabilities) and a matrix half M(b) (accumulation
-    // of block b, alternating with the scores of block b+1), in the order V(0) M(0) V(1) M(1) ...; right
-    // after M(b) has read its operands the operands of M(b+1) (K of block b+2, V of block b+1) are
-    // requested from LDS, to arrive during V(b+1).  A VFIRST wave places the barrier of interval b
-    // before V(b), the others before M(b): the two waves of a SIMD run in opposite phases, one's
-    // matrix work beside the other's vector work.  Either way block b+2 must have landed at the
-    // barrier of interval b: each wave issues 2 loads per block and loads complete in order, so it has
-    // once at most 2 * (blocks issued after it) loads are outstanding; near the end of the slice,
-    // where fewer than 5 blocks follow, the wait is for everything.
+    // Common to all roles.  Blocks 0 .. 7 are requested up front; interval i (i = 0 .. nblk-2) starts
+    // with a barrier behind which block i+8 is requested into the slot block i has left, so block i is
+    // read from LDS before that barrier.  Block i+2 must have landed at the barrier of interval i: each
+    // wave issues 2 loads per block and loads complete in order, so it has once at most
+    // 2 * (blocks issued after it) loads are outstanding; near the end of the slice, where fewer than 5
+    // blocks follow, the wait is for everything.
     const int nblk = (t.kv_len + 31) >> 5;
     {
         int pg[kRing];
@@ -939,67 +748,84 @@ __device__ __forceinline__ void dense32_wave(const PacParams &P, const DevTask &
             if (d < nblk) dma_block(d, pg[d]);
     }
     int pg_next = page_issue(kRing < nblk ? kRing : 0);                 // page of the block interval 0 requests
-    if (nblk >= kRing) __builtin_amdgcn_s_waitcnt(0x0F7C);              // vmcnt(12): blocks 0 and 1 have landed
+    if (nblk >= kRing) __builtin_amdgcn_s_waitcnt(vmcnt_imm(2 * (kRing - 2)));     // blocks 0 and 1 have landed
     else               __builtin_amdgcn_s_waitcnt(0x0F70);
     __syncthreads();
 
-    auto enter_interval = [&](int b) {                                  // b + 1 < nblk
-        const bool more = b + kRing < nblk;
-        if (more) __builtin_amdgcn_s_waitcnt(0x0F7A);                   // vmcnt(10): 5 blocks follow block b+2
-        else      __builtin_amdgcn_s_waitcnt(0x0F70);
-        __syncthreads();                    // block b+2 is complete; everyone is done with block b
-        if (more) {
-            dma_block(b + kRing, pg_next);
-            pg_next = page_issue(b + kRing + 1 < nblk ? b + kRing + 1 : 0);
+    // more: block i+8 exists
+    auto enter_interval = [&](int i, auto more) {                       // i + 1 < nblk
+        if constexpr (decltype(more)::value) __builtin_amdgcn_s_waitcnt(vmcnt_imm(2 * (kRing - 3)));  // kRing-3 blocks follow i+2
+        else                                 __builtin_amdgcn_s_waitcnt(0x0F70);
+        __syncthreads();                    // block i+2 is complete; everyone is done with block i
+        if constexpr (decltype(more)::value) {
+            dma_block(i + kRing, pg_next);
+            pg_next = page_issue(i + kRing + 1);
         }
     };
+    using yes = std::true_type;
+    using no = std::false_type;
+    auto short_block = [&](int b) { return c.kv_len - b * 32; };        // valid tokens if below 32
 
     if constexpr (LIVE) {
-        using yes = std::true_type;
-        using no = std::false_type;
-        auto vector_half_of = [&](int b) {                              // masks a short last block first
-            const int valid = c.kv_len - b * 32;
-            if (valid < 32) mask_scores32(s, valid);
-            vector_half();
+        // Per block a vector half V(b) (scores of block b -> probabilities) and a matrix half M(b)
+        // (accumulation of block b, alternating with the scores of block b+1), in the order V(0) M(0)
+        // V(1) M(1) ...; right after M(b) has read its operands the operands of M(b+1) (K of block b+2, V
+        // of block b+1) are requested from LDS, to arrive during V(b+1).  A vector-first wave places the
+        // barrier of interval b before V(b), a matrix-first wave before M(b): the two waves of a SIMD run
+        // in opposite phases, one's matrix work beside the other's vector work.
+        constexpr bool VFIRST = ROLE == kVectorFirst;
+        auto vector_half_of = [&](int b) {
+            if (short_block(b) < 32) mask_scores32(s, short_block(b));
+            reference();
+            probabilities32(0);
+            probabilities32(1);
         };
         auto matrix_half_and_loads = [&](int b) {                       // M(b), b + 1 < nblk
-            matrix_half(yes{});
+            matrix_half();
             __builtin_amdgcn_sched_barrier(0);
             load_keys(b + 2);
             load_values(b + 1);
             __builtin_amdgcn_sched_barrier(0);
         };
-
-        load_keys(0);
-        matrix_half(no{});
-        __builtin_amdgcn_sched_barrier(0);
-        load_keys(1);
-        load_values(0);
-        __builtin_amdgcn_sched_barrier(0);
-        if constexpr (VFIRST) {
-#pragma unroll 1
-            for (int b = 0; b + 1 < nblk; ++b) {
-                enter_interval(b);
+        auto interval = [&](int b, auto more) {
+            enter_interval(b, more);
+            if constexpr (VFIRST) {
                 vector_half_of(b);
                 __builtin_amdgcn_sched_barrier(0);
                 matrix_half_and_loads(b);
-            }
-            vector_half_of(nblk - 1);
-        } else {
-            vector_half_of(0);
-            __builtin_amdgcn_sched_barrier(0);
-#pragma unroll 1
-            for (int b = 0; b + 1 < nblk; ++b) {
-                enter_interval(b);
+            } else {
                 matrix_half_and_loads(b);
                 vector_half_of(b + 1);
                 __builtin_amdgcn_sched_barrier(0);
             }
+        };
+        load_keys(0);
+        scores32();
+        __builtin_amdgcn_sched_barrier(0);
+        load_keys(1);
+        load_values(0);
+        __builtin_amdgcn_sched_barrier(0);
+        if constexpr (!VFIRST) {
+            vector_half_of(0);
+            __builtin_amdgcn_sched_barrier(0);
         }
-        const int valid = c.kv_len - (nblk - 1) * 32;
-        if (valid < 32) mask_values(valid);
+        int b = 0;
+#pragma unroll 1
+        for (; b + kRing < nblk; ++b) interval(b, yes{});
+#pragma unroll 1
+        for (; b + 1 < nblk; ++b) interval(b, no{});
+        if constexpr (VFIRST) vector_half_of(nblk - 1);
+        if (short_block(nblk - 1) < 32) mask_values(short_block(nblk - 1));
         accumulate32();
+    } else {
+        int b = 0;
+#pragma unroll 1
+        for (; b + kRing < nblk; ++b) enter_interval(b, yes{});
+#pragma unroll 1
+        for (; b + 1 < nblk; ++b) enter_interval(b, no{});
+    }
 
+    if constexpr (LIVE) {
         l += __shfl_xor(l, 32);
         const int row = row0 + l32;
         if (row < rows) {
@@ -1017,22 +843,21 @@ __device__ __forceinline__ void dense32_wave(const PacParams &P, const DevTask &
                 *reinterpret_cast<float2 *>(P.part_ml + prow * 2) = ml;
             }
         }
-    } else {
-#pragma unroll 1
-        for (int b = 0; b + 1 < nblk; ++b) enter_interval(b);
     }
-    __syncthreads();                        // the ring is reused by the slot's next task
+    __syncthreads();                        // every block has been read: the ring is free for the next task
 }
 
+// Dense task: wave w owns rows 32w .. 32w+31; waves 4 .. 7 share their SIMDs with waves 0 .. 3 and run
+// in the opposite phase.
 template <int DT>
 __device__ void run_dense32(const PacParams &P, const DevTask &t, int head, char *lds)
 {
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int rows = t.n_req * P.group;
     const int row0 = wave * 32;
-    if (row0 >= rows)  dense32_wave<DT, false, false>(P, t, head, lds, wave, row0, rows);
-    else if (wave & 4) dense32_wave<DT, true, true>(P, t, head, lds, wave, row0, rows);
-    else               dense32_wave<DT, true, false>(P, t, head, lds, wave, row0, rows);
+    if (row0 >= rows)  dense32_wave<DT, kHelper>(P, t, head, lds, wave, 0, 0);
+    else if (wave & 4) dense32_wave<DT, kVectorFirst>(P, t, head, lds, wave, row0, rows);
+    else               dense32_wave<DT, kMatrixFirst>(P, t, head, lds, wave, row0, rows);
 }
 
 // WIDE: kRingBytes of dynamic LDS.  The dense path XORs the channel tile into operand addresses, so
@@ -1058,8 +883,7 @@ __global__ void __launch_bounds__(WIDE ? kWideWaves * 64 : kNarrowWaves * 64, 2)
         const DevTask t = P.tasks[P.slot_tasks[i]];
         const int rows = t.n_req * P.group;
         if constexpr (WIDE != 0) {
-            if (rows <= 16) run_dense16<DT>(P, t, head, lds);
-            else            run_dense32<DT>(P, t, head, lds);
+            run_dense32<DT>(P, t, head, lds);
         } else if (rows <= 16) {
             run_stream<DT, 1, W>(P, t, head, lds);
         }

@@ -2,8 +2,9 @@
 //
 // The paper states the solver in prose (Sec. 5.1): fix b_q = 1, find a lower
 // bound cost_l of the makespan by binary search on the average-load inequality
-// (Eq. 4), bound every node's slice count by ceil(C_est / cost_l) (Eq. 5), grid
-// search the slice counts and schedule greedily.  Everything it leaves open is
+// (Eq. 4), bound every node's slice count (Eq. 5: by ceil(C_est / cost_l), carried
+// on here while a piece still costs more than cost_l), grid search the slice
+// counts and schedule greedily.  Everything it leaves open is
 // fixed here in integers so that the result can be re-derived bit for bit:
 // integer costs, round-half-up bilinear interpolation, slices of equal length
 // on aligned boundaries, one grid-search pass in order of decreasing node cost
@@ -133,17 +134,17 @@ const CostTable &builtin_cost_table(bool wide)
     static const CostTable narrow_table = {
         {1, 16},
         {32, 128, 512, 2048, 8192, 32768},
-        {4260, 4760, 23898, 92029, 366774, 1477695,
-         5719, 6420, 29116, 100567, 373773, 1472995}};
+        {4079, 5179, 24737, 93649, 368698, 1471049,
+         5459, 6459, 29336, 100148, 377095, 1470742}};
     static const CostTable wide_table = {
         {1, 16, 32, 64, 128, 256},
         {32, 128, 512, 2048, 8192, 32768},
-        {2420, 6119, 13478, 48855, 181258, 732448,
-         2939, 6339, 14198, 51093, 183796, 739667,
-         3280, 6780, 16118, 53953, 190116, 746086,
-         5699, 8819, 18718, 58073, 195855, 745126,
-         9379, 11979, 24517, 65492, 263267, 964959,
-         16018, 18857, 41775, 102047, 364255, 1340991}};
+        {2140, 7159, 13999, 47014, 182318, 746569,
+         3239, 7139, 16278, 50174, 187097, 750429,
+         3099, 7419, 17998, 52714, 192456, 751968,
+         4980, 8499, 18178, 56133, 193317, 747368,
+         8219, 10079, 22857, 65132, 240850, 851216,
+         11499, 14898, 34716, 77330, 334079, 1224150}};
     return wide ? wide_table : narrow_table;
 }
 
@@ -304,8 +305,17 @@ int build_plan(const codec_tree &tree, const codec_head_config &head,
         }
         p.cost_l = lo;
     }
+    // Eq. 5 stops dividing a node once a piece costs no more than cost_l and writes that point as the
+    // quotient C_est / cost_l, which it is when cost is proportional to length.  The measured tables
+    // have a large fixed part per task, so the count is carried on from the quotient while a piece
+    // still costs more than cost_l, to at most four times the quotient.
     for (size_t j = 0; j < J; ++j) {
-        p.items[j].ub = slice_node(p.items[j].len, slices_at(j, p.cost_l), align).count;
+        int64_t want = slices_at(j, p.cost_l);
+        const int64_t limit = std::min(max_b[j], 4 * want);
+        while (want < limit
+               && table->estimate(p.items[j].rows, slice_node(p.items[j].len, want, align).length) > p.cost_l)
+            ++want;
+        p.items[j].ub = slice_node(p.items[j].len, want, align).count;
         p.items[j].b = p.items[j].ub;
     }
 
