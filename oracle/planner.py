@@ -8,18 +8,6 @@ found by binary search on the average-load inequality (Eq. 4), the per-node
 upper bound on the number of KV slices (Eq. 5), a grid search over each node's
 slice count, and greedy longest-first scheduling onto m slots (Eq. 3).
 
-Reading of Eq. 5.  The paper bounds a node's slice count by the quotient
-ceil(C_est / cost_l) and gives the reason in words: division stops once a
-piece costs no more than the average load, since finer pieces only add
-overhead.  The quotient is the slice count at which that happens when cost is
-proportional to length.  With a profiled table whose per-task fixed part is
-large (many query rows: the partial outputs alone are 512 bytes per row) a
-piece at the quotient still costs well above cost_l, so here the bound is
-carried on in the paper's own terms: starting from the quotient, the count
-grows while a piece's estimated cost is still above cost_l, up to four times
-the quotient (the cap bounds the search).  For proportional costs the two
-coincide.
-
 The paper gives the solver in prose; where it is silent this file fixes:
 integer costs; round-half-up bilinear interpolation, clamped below the grid
 and linearly extrapolated above it; slice boundaries on multiples of
@@ -170,11 +158,7 @@ def plan(parent, node_len, req_node, group: int, num_slots: int, align: int,
         cost_l = lo
 
     for it in items:
-        want = b_of(it, cost_l)                       # Eq. 5: the quotient
-        limit = min(it["max_b"], 4 * want)
-        while want < limit and c_est(table, it["rows"], slices(it["len"], want, align)[1]) > cost_l:
-            want += 1
-        it["ub"] = slices(it["len"], want, align)[0]
+        it["ub"] = slices(it["len"], b_of(it, cost_l), align)[0]
         it["b"] = it["ub"]
 
     def subtasks():

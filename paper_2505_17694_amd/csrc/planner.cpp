@@ -2,9 +2,8 @@
 //
 // The paper states the solver in prose (Sec. 5.1): fix b_q = 1, find a lower
 // bound cost_l of the makespan by binary search on the average-load inequality
-// (Eq. 4), bound every node's slice count (Eq. 5: by ceil(C_est / cost_l), carried
-// on here while a piece still costs more than cost_l), grid search the slice
-// counts and schedule greedily.  Everything it leaves open is
+// (Eq. 4), bound every node's slice count by ceil(C_est / cost_l) (Eq. 5), grid
+// search the slice counts and schedule greedily.  Everything it leaves open is
 // fixed here in integers so that the result can be re-derived bit for bit:
 // integer costs, round-half-up bilinear interpolation, slices of equal length
 // on aligned boundaries, one grid-search pass in order of decreasing node cost
@@ -305,17 +304,8 @@ int build_plan(const codec_tree &tree, const codec_head_config &head,
         }
         p.cost_l = lo;
     }
-    // Eq. 5 stops dividing a node once a piece costs no more than cost_l and writes that point as the
-    // quotient C_est / cost_l, which it is when cost is proportional to length.  The measured tables
-    // have a large fixed part per task, so the count is carried on from the quotient while a piece
-    // still costs more than cost_l, to at most four times the quotient.
     for (size_t j = 0; j < J; ++j) {
-        int64_t want = slices_at(j, p.cost_l);
-        const int64_t limit = std::min(max_b[j], 4 * want);
-        while (want < limit
-               && table->estimate(p.items[j].rows, slice_node(p.items[j].len, want, align).length) > p.cost_l)
-            ++want;
-        p.items[j].ub = slice_node(p.items[j].len, want, align).count;
+        p.items[j].ub = slice_node(p.items[j].len, slices_at(j, p.cost_l), align).count;
         p.items[j].b = p.items[j].ub;
     }
 

@@ -123,45 +123,6 @@ def test_hand_worked_three_node_plan():
     assert p["part_rows"] == 8
 
 
-def test_slice_bound_equals_the_quotient_for_proportional_cost():
-    """Eq. 5 as printed: with cost proportional to length a piece at the quotient costs at most cost_l."""
-    for seed in range(6):
-        f = random_forest(30, 4, 2.0, 700, 1.0, 16, 20000, seed=seed)
-        p = P.plan(f.parent, f.node_len, f.req_node, group=1, num_slots=16, align=1,
-                   max_rows=64, share=True, table=LINEAR)
-        for it in p["items"]:
-            assert it["ub"] == min(-(-it["cost"] // p["cost_l"]), it["max_b"])
-
-
-def test_slice_bound_is_carried_on_while_a_piece_costs_more_than_cost_l():
-    """A fixed 1000 per task on top of 1 per token: root 8000 tokens, 6 leaves of 100, 8 slots.
-
-    Costs: root 9000, leaves 1100 each (6600).  With 4 root pieces (2000 tokens, 3000 each) the total
-    is 18600, which fits 8 * T from T = 2325 on; below T = 2250 the induced division has 5 pieces
-    (13000 + 6600 > 8 * T): cost_l = 2325.  The quotient of Eq. 5 is ceil(9000 / 2325) = 4, but a
-    piece still costs 3000 there, 2600 at 5 pieces, 2334 at 6 and 2143 <= cost_l at 7: the bound is 7.
-    Makespans for 4, 5, 6, 7 pieces: 3000, 2600, 3300, 3243 -> 5 pieces, which the quotient alone
-    would have excluded.
-    """
-    table = {"row_grid": [1], "len_grid": [1, 10001], "cost": [[1001, 11001]]}
-    f = two_level_forest(8000, [100] * 6)
-    p = P.plan(f.parent, f.node_len, f.req_node, group=1, num_slots=8, align=1,
-               max_rows=64, share=True, table=table)
-    assert P.c_est(table, 6, 2000) == 3000 and P.c_est(table, 1, 100) == 1100
-    assert p["cost_l"] == 2325
-    assert p["items"][0]["ub"] == 7
-    assert (p["items"][0]["b"], p["makespan"]) == (5, 2600)
-    # brute force over the root's slice count
-    ms_of = {}
-    for b in range(1, 8):
-        count, length, last = P.slices(8000, b, 1)
-        sub = [(P.c_est(table, 6, length if c < count - 1 else last), 0, c) for c in range(count)]
-        sub += [(1100, 1 + i, 0) for i in range(6)]
-        ms_of[count] = P.lpt(sub, 8)[0]
-    assert [ms_of[b] for b in (4, 5, 6, 7)] == [3000, 2600, 3300, 3243]
-    assert min(ms_of.values()) == 2600
-
-
 def _check_invariants(f, p, group, m, align):
     n_q = np.zeros(f.num_nodes, dtype=np.int64)
     for r in range(f.num_requests):
@@ -187,14 +148,9 @@ def _check_invariants(f, p, group, m, align):
     assert max(loads) == p["makespan"]
     total = sum(t["cost"] for t in p["tasks"])
     assert p["makespan"] >= max(-(-total // m), max(t["cost"] for t in p["tasks"]))
-    # Eq. 5: slice counts stay within the bound derived from cost_l: the quotient, carried on (to at
-    # most four times the quotient) only while a piece still costs more than cost_l
+    # Eq. 5: slice counts stay within the bound derived from cost_l
     for it in p["items"]:
-        quotient = max(1, -(-it["cost"] // p["cost_l"]))
-        assert 1 <= it["b"] <= it["ub"] <= 4 * quotient
-        if it["ub"] > quotient:
-            finer = P.slices(it["len"], it["ub"] - 1, align)
-            assert finer[0] < it["ub"] or P.c_est(p["table"], it["rows"], finer[1]) > p["cost_l"]
+        assert 1 <= it["b"] <= it["ub"] <= max(1, -(-it["cost"] // p["cost_l"]))
     # Eq. 4 at cost_l: the division it induces fits m slots on average, the next finer T does not
     def tot(T):
         return sum(P.division_cost(p["table"], it["rows"], it["len"],
