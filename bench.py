@@ -145,6 +145,12 @@ def run_config(name, args, steps, warmup, want_flat):
             "est_makespan": view["makespan"], "cost_l": view["cost_l"],
         }
         res[key]["_raw"] = t
+        if share:
+            # carrying the plan over to the next step's lengths (host work + metadata upload) against
+            # planning again: what a serving loop pays per step between two plannings
+            t0 = time.perf_counter()
+            pa.refresh(w.forest.node_len)
+            res[key]["refresh_ms"] = round((time.perf_counter() - t0) * 1e3, 3)
         pa.close()
     if want_flat:
         res["speedup_vs_flat"] = round(res["flat"]["us_per_step"] / res["tree"]["us_per_step"], 3)

@@ -189,6 +189,32 @@ int codec_plan_destroy(codec_plan_t *plan);
 int codec_plan_export(const codec_plan_t *plan, codec_plan_view *view);
 
 /*
+ * Carry a plan over to the next decoding steps without planning again.  The
+ * paper divides tasks only every few decoding steps (Implementation section,
+ * task division module) while every step appends tokens to the requests' last
+ * nodes; in between, the division and the slot assignment are kept: every slice
+ * keeps its boundaries, the last slice of a node takes up the node's change in
+ * length, costs and the estimated makespan (see codec_plan_export) are
+ * recomputed.  The forest itself (parents, requests) must be the one the plan
+ * was created for; node_len[num_nodes], node_page_off[num_nodes + 1] and
+ * page_ids[node_page_off[num_nodes]] are host arrays with the meaning they have
+ * in codec_tree and are copied.  Host only.
+ *
+ * The device copy of the metadata becomes stale: codec_plan_device_bytes may
+ * have grown (longer page lists) and codec_plan_upload must be called again
+ * before the next launch (launches return CODEC_ERR_NOT_UPLOADED until then).
+ * Pointers obtained from codec_plan_export before the call are invalid after it.
+ *
+ * Errors (the plan is left unchanged): CODEC_ERR_INVALID_TREE for a length
+ * below 1, a page list shorter than its node or a negative page id;
+ * CODEC_ERR_INVALID_ARGUMENT for NULL arrays or a length that would leave a
+ * node's last slice empty (the node shrank below the start of that slice: plan
+ * again).
+ */
+int codec_plan_refresh_lengths(codec_plan_t *plan, const int32_t *node_len,
+                               const int32_t *node_page_off, const int32_t *page_ids);
+
+/*
  * C_est(rows, len) of Eq. 6 on `table`; returns the cost, or a negative status.  NULL = the
  * built-in table of the kernel variant a task of `rows` rows needs (wide above 16 rows).
  */

@@ -222,3 +222,39 @@ def plan(parent, node_len, req_node, group: int, num_slots: int, align: int,
             "node_q_off": node_q_off, "node_q": node_q_flat,
             "req_part_off": req_part_off, "req_part": req_part,
             "part_rows": base, "paths": paths}
+
+
+def refresh(plan_out: Dict, table: Dict, new_node_len) -> Dict:
+    """Carry a plan over to new node lengths without dividing or scheduling again.
+
+    The paper divides tasks only every few decoding steps (Implementation section, task division
+    module) while every step appends a token to each request's last node.  Between two plannings the division and the
+    slot assignment are kept: a node's slices keep their boundaries, its last slice takes up the
+    change in length, costs and the makespan are re-estimated for the new lengths.  Returns a new
+    dict with the same keys as ``plan``; raises ValueError when a last slice would become empty.
+    """
+    new_node_len = [int(x) for x in new_node_len]
+    out = dict(plan_out)
+    items = [dict(it) for it in plan_out["items"]]
+    tasks = [dict(t) for t in plan_out["tasks"]]
+    first = {}
+    for i, t in enumerate(tasks):
+        first.setdefault(t["item"], i)
+    for j, it in enumerate(items):
+        n = new_node_len[it["node"]]
+        b = it["b"]
+        t0 = first[j]
+        start = tasks[t0 + b - 1]["kv_begin"]
+        if n < 1 or n - start < 1:
+            raise ValueError("node %d: length %d leaves its last slice empty" % (it["node"], n))
+        it["len"] = n
+        it["cost"] = c_est(table, it["rows"], n)
+        last = tasks[t0 + b - 1]
+        last["kv_len"] = n - start
+        last["cost"] = c_est(table, it["rows"], last["kv_len"])
+    m = len(plan_out["slot_off"]) - 1
+    loads = [sum(tasks[i]["cost"] for i in plan_out["slot_tasks"][plan_out["slot_off"][s]:plan_out["slot_off"][s + 1]])
+             for s in range(m)]
+    out["items"], out["tasks"] = items, tasks
+    out["makespan"] = max(loads) if loads else 0
+    return out

@@ -33,6 +33,7 @@ EXPORTED_SYMBOLS = [
     "codec_default_cost_table", "codec_plan_device_bytes", "codec_plan_upload",
     "codec_plan_workspace_bytes", "codec_decode_attention", "codec_partial_attention",
     "codec_partial_reduction", "codec_status_string", "codec_last_error_message",
+    "codec_plan_refresh_lengths",
 ]
 
 _i32p = POINTER(c_int32)
@@ -107,6 +108,8 @@ _lib.codec_plan_destroy.restype = c_int
 _lib.codec_plan_destroy.argtypes = [c_void_p]
 _lib.codec_plan_export.restype = c_int
 _lib.codec_plan_export.argtypes = [c_void_p, POINTER(codec_plan_view)]
+_lib.codec_plan_refresh_lengths.restype = c_int
+_lib.codec_plan_refresh_lengths.argtypes = [c_void_p, _i32p, _i32p, _i32p]
 _lib.codec_cost_estimate.restype = c_int64
 _lib.codec_cost_estimate.argtypes = [POINTER(codec_cost_table), c_int32, c_int32]
 _lib.codec_default_cost_table.restype = POINTER(codec_cost_table)
@@ -214,6 +217,11 @@ def codec_plan_export(plan):
     out["node_q"] = _arr(v.node_q, int(out["node_q_off"][-1]) if v.num_nodes else 0)
     out["req_part"] = _arr(v.req_part, int(out["req_part_off"][-1]))
     return st, out
+
+
+def codec_plan_refresh_lengths(plan, node_len, node_page_off, page_ids) -> int:
+    node_len, node_page_off, page_ids = _i32(node_len), _i32(node_page_off), _i32(page_ids)
+    return _lib.codec_plan_refresh_lengths(plan, _ptr(node_len), _ptr(node_page_off), _ptr(page_ids))
 
 
 def codec_cost_estimate(cost_table, rows: int, length: int) -> int:

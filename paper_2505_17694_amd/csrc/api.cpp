@@ -108,6 +108,23 @@ int codec_plan_export(const codec_plan_t *plan, codec_plan_view *v)
     return CODEC_OK;
 }
 
+int codec_plan_refresh_lengths(codec_plan_t *plan, const int32_t *node_len,
+                               const int32_t *node_page_off, const int32_t *page_ids)
+{
+    if (!plan) return CODEC_ERR_INVALID_ARGUMENT;
+    int st;
+    try {
+        st = codec::refresh_plan(plan->d, node_len, node_page_off, page_ids);
+    } catch (const std::bad_alloc &) {
+        return CODEC_ERR_OUT_OF_MEMORY;
+    }
+    if (st != CODEC_OK) return st;
+    plan->device_meta = nullptr;
+    plan->max_page_id = -1;
+    for (int32_t id : plan->d.page_ids) plan->max_page_id = id > plan->max_page_id ? id : plan->max_page_id;
+    return CODEC_OK;
+}
+
 int64_t codec_cost_estimate(const codec_cost_table *table, int32_t rows, int32_t len)
 {
     if (rows < 1 || len < 1) return CODEC_ERR_INVALID_ARGUMENT;

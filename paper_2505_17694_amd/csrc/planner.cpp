@@ -94,6 +94,42 @@ void schedule_lpt(const std::vector<Sub> &sub, int m, bool keep_lists, Schedule 
 
 size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
+// Host image of the device metadata: task records, slot lists, query lists, page table, partial lists.
+void build_device_image(PlanData &p)
+{
+    const int32_t ps = p.head.page_size;
+    DevLayout &L = p.layout;
+    size_t off = 0;
+    auto place = [&](size_t bytes) { size_t at = off; off = align_up(off + bytes, 256); return at; };
+    L.tasks = place(p.tasks.size() * sizeof(DevTask));
+    L.slot_off = place(p.slot_off.size() * 4);
+    L.slot_tasks = place(p.slot_tasks.size() * 4);
+    L.node_q = place(p.node_q.size() * 4);
+    L.page_ids = place(p.page_ids.size() * 4);
+    L.req_part_off = place(p.req_part_off.size() * 4);
+    L.req_part = place(p.req_part.size() * 4);
+    L.total = std::max<size_t>(off, 256);
+    p.blob.assign(L.total, 0);
+    DevTask *dt = reinterpret_cast<DevTask *>(p.blob.data() + L.tasks);
+    for (size_t i = 0; i < p.tasks.size(); ++i) {
+        const codec_task &t = p.tasks[i];
+        dt[i].page_off = p.node_page_off[t.node] + t.kv_begin / ps;
+        dt[i].kv_len = t.kv_len;
+        dt[i].q_off = t.q_off;
+        dt[i].n_req = t.n_req;
+        dt[i].part_row_base = t.part_row_base;
+    }
+    auto put = [&](size_t at, const std::vector<int32_t> &v) {
+        if (!v.empty()) std::memcpy(p.blob.data() + at, v.data(), v.size() * 4);
+    };
+    put(L.slot_off, p.slot_off);
+    put(L.slot_tasks, p.slot_tasks);
+    put(L.node_q, p.node_q);
+    put(L.page_ids, p.page_ids);
+    put(L.req_part_off, p.req_part_off);
+    put(L.req_part, p.req_part);
+}
+
 }  // namespace
 
 int CostTable::validate() const
@@ -274,6 +310,7 @@ int build_plan(const codec_tree &tree, const codec_head_config &head,
     const int32_t m = opt.num_slots > 0 ? opt.num_slots : std::max(1, (wide ? 256 : 512) / head.num_kv_heads);
     p.num_slots = m;
     if (!table) table = &builtin_cost_table(wide);
+    p.table = *table;
     for (codec_item &it : p.items) it.cost = table->estimate(it.rows, it.len);       // a2: Eq. 6
     std::vector<int64_t> max_b(J);
     for (size_t j = 0; j < J; ++j) max_b[j] = ceil_div(p.items[j].len, align);
@@ -402,40 +439,54 @@ int build_plan(const codec_tree &tree, const codec_head_config &head,
         p.req_part_off[r + 1] = int32_t(p.req_part.size());
     }
 
-    // ---- device image ------------------------------------------------------------------------------
-    const int32_t ps = head.page_size;
-    DevLayout &L = p.layout;
-    size_t off = 0;
-    auto place = [&](size_t bytes) { size_t at = off; off = align_up(off + bytes, 256); return at; };
-    L.tasks = place(p.tasks.size() * sizeof(DevTask));
-    L.slot_off = place(p.slot_off.size() * 4);
-    L.slot_tasks = place(p.slot_tasks.size() * 4);
-    L.node_q = place(p.node_q.size() * 4);
-    L.page_ids = place(p.page_ids.size() * 4);
-    L.req_part_off = place(p.req_part_off.size() * 4);
-    L.req_part = place(p.req_part.size() * 4);
-    L.total = std::max<size_t>(off, 256);
-    p.blob.assign(L.total, 0);
-    {
-        DevTask *dt = reinterpret_cast<DevTask *>(p.blob.data() + L.tasks);
-        for (size_t i = 0; i < p.tasks.size(); ++i) {
-            const codec_task &t = p.tasks[i];
-            dt[i].page_off = p.node_page_off[t.node] + t.kv_begin / ps;
-            dt[i].kv_len = t.kv_len;
-            dt[i].q_off = t.q_off;
-            dt[i].n_req = t.n_req;
-            dt[i].part_row_base = t.part_row_base;
-        }
-        auto put = [&](size_t at, const std::vector<int32_t> &v) {
-            if (!v.empty()) std::memcpy(p.blob.data() + at, v.data(), v.size() * 4);
-        };
-        put(L.slot_off, p.slot_off);
-        put(L.slot_tasks, p.slot_tasks);
-        put(L.node_q, p.node_q);
-        put(L.page_ids, p.page_ids);
-        put(L.req_part_off, p.req_part_off);
-        put(L.req_part, p.req_part);
+    build_device_image(p);
+    return CODEC_OK;
+}
+
+int refresh_plan(PlanData &p, const int32_t *node_len, const int32_t *node_page_off, const int32_t *page_ids)
+{
+    const int32_t N = p.num_nodes;
+    if (N == 0) return CODEC_OK;
+    if (!node_len || !node_page_off) return CODEC_ERR_INVALID_ARGUMENT;
+    const int32_t ps = p.head.page_size;
+    // ---- checks first: nothing is changed on error ----------------------------------------------
+    if (node_page_off[0] < 0) return CODEC_ERR_INVALID_TREE;
+    for (int32_t i = 0; i < N; ++i) {
+        if (node_len[i] < 1) return CODEC_ERR_INVALID_TREE;
+        const int64_t have = int64_t(node_page_off[i + 1]) - node_page_off[i];
+        if (have < ceil_div(node_len[i], ps)) return CODEC_ERR_INVALID_TREE;
     }
+    if (node_page_off[N] > 0 && !page_ids) return CODEC_ERR_INVALID_ARGUMENT;
+    for (int32_t i = node_page_off[0]; i < node_page_off[N]; ++i)
+        if (page_ids[i] < 0) return CODEC_ERR_INVALID_TREE;
+    std::vector<int32_t> first_task(p.items.size(), -1);
+    for (size_t i = 0; i < p.tasks.size(); ++i)
+        if (first_task[p.tasks[i].item] < 0) first_task[p.tasks[i].item] = int32_t(i);
+    for (size_t j = 0; j < p.items.size(); ++j) {
+        const codec_item &it = p.items[j];
+        const codec_task &last = p.tasks[first_task[j] + it.b - 1];
+        if (int64_t(node_len[it.node]) - last.kv_begin < 1) return CODEC_ERR_INVALID_ARGUMENT;
+    }
+    // ---- carry over ---------------------------------------------------------------------------------
+    p.node_len.assign(node_len, node_len + N);
+    p.node_page_off.assign(node_page_off, node_page_off + N + 1);
+    p.page_ids.assign(page_ids, page_ids + node_page_off[N]);
+    for (size_t j = 0; j < p.items.size(); ++j) {
+        codec_item &it = p.items[j];
+        it.len = p.node_len[it.node];
+        it.cost = p.table.estimate(it.rows, it.len);
+        codec_task &last = p.tasks[first_task[j] + it.b - 1];
+        last.kv_len = it.len - last.kv_begin;
+        last.cost = p.table.estimate(it.rows, last.kv_len);
+    }
+    int64_t makespan = 0;
+    for (int32_t s = 0; s < p.num_slots; ++s) {
+        int64_t load = 0;
+        for (int32_t i = p.slot_off[s]; i < p.slot_off[s + 1]; ++i) load += p.tasks[p.slot_tasks[i]].cost;
+        makespan = std::max(makespan, load);
+    }
+    p.makespan = makespan;
+    build_device_image(p);
     return CODEC_OK;
 }
 

@@ -50,6 +50,8 @@ struct PlanData {
     int64_t cost_l = 0, makespan = 0;
     int32_t part_rows = 0;
 
+    CostTable table;                    // the table the plan was estimated with (for refresh_plan)
+
     DevLayout layout;
     std::vector<unsigned char> blob;    // host image of the device metadata
 };
@@ -59,5 +61,11 @@ const CostTable &builtin_cost_table(bool wide);
 // Fills `plan` from the caller's forest; returns a CODEC_* status.
 int build_plan(const codec_tree &tree, const codec_head_config &head,
                const codec_plan_options &opt, PlanData &plan);
+
+// Carries `plan` over to new node lengths and page lists without dividing or scheduling again (the
+// paper divides tasks only every few decoding steps: Implementation section, task division module):
+// slices keep their boundaries, a node's last slice takes up the change in length, costs and the
+// makespan are re-estimated, the device image is rebuilt.  On error `plan` is left as it was.
+int refresh_plan(PlanData &plan, const int32_t *node_len, const int32_t *node_page_off, const int32_t *page_ids);
 
 }  // namespace codec

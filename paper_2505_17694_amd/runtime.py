@@ -40,6 +40,22 @@ class PlannedAttention:
             self.workspace = torch.empty(B.codec_plan_workspace_bytes(plan), dtype=torch.uint8,
                                          device=self.device)
 
+    def refresh(self, node_len, paged=None):
+        """New node lengths (and page lists) for the same forest: keeps the division and the schedule."""
+        if paged is not None:
+            self.paged = paged
+        st = B.codec_plan_refresh_lengths(self.plan, node_len, self.paged.node_page_off, self.paged.page_ids)
+        if st != B.CODEC_OK:
+            raise B.CodecError(st, "codec_plan_refresh_lengths")
+        if self.device.type == "cuda":
+            need = B.codec_plan_device_bytes(self.plan)
+            if self.meta.numel() < need:
+                self.meta = torch.empty(need, dtype=torch.uint8, device=self.device)
+            stream = torch.cuda.current_stream(self.device).cuda_stream
+            st = B.codec_plan_upload(self.plan, self.meta.data_ptr(), self.meta.numel(), stream)
+            if st != B.CODEC_OK:
+                raise B.CodecError(st, "codec_plan_upload")
+
     def export(self):
         st, view = B.codec_plan_export(self.plan)
         if st != B.CODEC_OK:

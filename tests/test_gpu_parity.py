@@ -162,6 +162,39 @@ def test_same_plan_decodes_repeatedly_and_with_new_queries():
     pa.close()
 
 
+@pytest.mark.parametrize("share", [1, 0])
+def test_plan_carried_over_to_grown_lengths(share):
+    """codec_plan_refresh_lengths: same division and schedule, longer last slices, new page lists."""
+    C = _C()
+    f_old = three_level_forest(700, [1300, 450], 3, [5, 33, 64, 1, 17, 48])
+    head = HeadConfig(16, 4, 128, DTYPE_BF16)
+    rng = np.random.Generator(np.random.PCG64(3))
+    growth = rng.integers(0, 40, size=f_old.num_nodes).astype(np.int32)
+    growth[-1] = 1                                          # the usual decode step: one more token
+    f_new = Forest(f_old.parent, f_old.node_len + growth, f_old.req_node)
+    w_new = make_workload("grown", f_new, head, seed=31, poison=True)
+    w_old = make_workload("before", f_old, head, seed=31, paged=w_new.paged)
+    w_old.q[:] = w_new.q
+    w_old.k_pool[:] = w_new.k_pool
+    w_old.v_pool[:] = w_new.v_pool
+    wd = w_new.to("cuda:0")
+    pa = C.PlannedAttention(f_old, w_new.paged, head, device="cuda:0", share=share, num_slots=16, split_align=32)
+    tasks_before = pa.export()["tasks"]
+    for w, lens in ((w_old, None), (w_new, f_new.node_len)):
+        if lens is not None:
+            pa.refresh(lens)
+        out = pa.decode(wd.q, wd.k_pool, wd.v_pool)
+        torch.cuda.synchronize()
+        ref, _ = A.decode_attention_workload(w)
+        got = out.to(torch.float64).cpu().numpy()
+        assert not np.any(np.isnan(got))
+        assert np.abs(got - ref).max() <= TOL
+    tasks_after = pa.export()["tasks"]
+    assert [(t["kv_begin"], t["slot"]) for t in tasks_after] == [(t["kv_begin"], t["slot"]) for t in tasks_before]
+    assert sum(t["kv_len"] for t in tasks_after) > sum(t["kv_len"] for t in tasks_before)
+    pa.close()
+
+
 def test_tree_equals_flat_on_the_gpu():
     w = make_small_config("cfg3", 16, 2, poison=True)
     tree, _ = run_gpu(w, share=1)

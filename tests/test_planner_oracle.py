@@ -236,3 +236,62 @@ def test_cpu_replay_of_the_task_list_equals_the_definition(share, dtype, hq, hkv
     got = M.replay_tasks(w, tasks, p["node_q"], p["req_part_off"], p["req_part"])
     ref, _ = A.decode_attention_workload(w)
     assert np.max(np.abs(got - ref)) < 1e-13
+
+
+# ---- carrying a plan over to new lengths (task division only every few decoding steps) -----------
+
+def test_refresh_hand_worked():
+    """The three-node plan above after growth: root 1200 -> 1250, leaves 100 -> 101 and 100 -> 164.
+
+    Slices keep their boundaries (0, 400, 800): the root's last slice becomes 450 tokens; slot loads
+    with cost = tokens: 400, 400, 450, 101 + 164 -> makespan 450.
+    """
+    f = two_level_forest(1200, [100, 100])
+    p = P.plan(f.parent, f.node_len, f.req_node, group=1, num_slots=4, align=100,
+               max_rows=64, share=True, table=LINEAR)
+    q = P.refresh(p, LINEAR, [1250, 101, 164])
+    assert [(t["node"], t["kv_begin"], t["kv_len"], t["cost"]) for t in q["tasks"]] == \
+        [(0, 0, 400, 400), (0, 400, 400, 400), (0, 800, 450, 450), (1, 0, 101, 101), (2, 0, 164, 164)]
+    assert [t["slot"] for t in q["tasks"]] == [t["slot"] for t in p["tasks"]]
+    assert [it["len"] for it in q["items"]] == [1250, 101, 164]
+    assert q["makespan"] == 450
+    for k in ("slot_off", "slot_tasks", "node_q", "node_q_off", "req_part", "req_part_off", "part_rows", "cost_l"):
+        assert q[k] == p[k]
+    # the original plan is not touched
+    assert p["tasks"][2]["kv_len"] == 400 and p["makespan"] == 400
+    # unchanged lengths: identity
+    same = P.refresh(p, LINEAR, [1200, 100, 100])
+    assert same["tasks"] == p["tasks"] and same["makespan"] == p["makespan"]
+    # shrinking the root to the start of its last slice leaves that slice empty
+    with pytest.raises(ValueError):
+        P.refresh(p, LINEAR, [800, 100, 100])
+    assert P.refresh(p, LINEAR, [801, 100, 100])["tasks"][2]["kv_len"] == 1
+
+
+@pytest.mark.parametrize("name", sorted(FORESTS))
+def test_refresh_keeps_the_invariants(name):
+    f = FORESTS[name]()
+    group, m, align = 4, 8, 256
+    p = P.plan(f.parent, f.node_len, f.req_node, group, m, align, 64, True, TABLE2)
+    p["table"] = TABLE2
+    rng = np.random.Generator(np.random.PCG64(5))
+    grown = f.node_len + rng.integers(0, 40, size=f.num_nodes)
+    q = P.refresh(p, TABLE2, grown)
+    q["table"] = TABLE2
+    g = Forest(f.parent, grown.astype(np.int32), f.req_node)
+    # every invariant of a plan except those of the search (cost_l, bounds) holds for the carried plan
+    by_item = {}
+    for t in q["tasks"]:
+        by_item.setdefault(t["item"], []).append(t)
+    for j, ts in by_item.items():
+        pos = 0
+        for t in ts:
+            assert t["kv_begin"] == pos and t["kv_len"] > 0
+            assert t["cost"] == P.c_est(TABLE2, q["items"][j]["rows"], t["kv_len"])
+            pos += t["kv_len"]
+        assert pos == g.node_len[q["items"][j]["node"]]
+    loads = [sum(q["tasks"][i]["cost"] for i in q["slot_tasks"][q["slot_off"][s]:q["slot_off"][s + 1]])
+             for s in range(m)]
+    assert max(loads) == q["makespan"]
+    assert [(t["kv_begin"], t["slot"], t["part_row_base"]) for t in q["tasks"]] == \
+        [(t["kv_begin"], t["slot"], t["part_row_base"]) for t in p["tasks"]]

@@ -114,3 +114,63 @@ def test_measured_configurations_with_library_defaults(name, share):
     ref = P.plan(f.parent, f.node_len, f.req_node, head.group, m, 256, 256, share,
                  _default_table(widest > 16))
     _compare(view, ref)
+
+
+# ---- codec_plan_refresh_lengths against the oracle's refresh ---------------------------------------
+
+def _grow_paged(f, head, grown, seed):
+    g = Forest(f.parent, np.asarray(grown, dtype=np.int32), f.req_node)
+    return g, build_paged_kv(g, head, seed=seed)
+
+
+@pytest.mark.parametrize("name", sorted(FORESTS))
+@pytest.mark.parametrize("share", [True, False])
+def test_refresh_matches_oracle(name, share):
+    f = FORESTS[name]()
+    head = HeadConfig(32, 8, 128, 1)
+    m, align, max_rows = 16, 64, 64
+    table = _default_table(1)
+    paged = build_paged_kv(f, head, seed=1)
+    st, plan = C.codec_plan_create(f.parent, f.node_len, f.req_node, paged.node_page_off, paged.page_ids,
+                                   head.num_q_heads, head.num_kv_heads, head.head_dim, head.dtype,
+                                   head.page_size, head.scale, m, align, max_rows, int(share), _tuple(table))
+    assert st == C.CODEC_OK
+    ref = P.plan(f.parent, f.node_len, f.req_node, 4, m, align, max_rows, share, table)
+    rng = np.random.Generator(np.random.PCG64(11))
+    lens = f.node_len.astype(np.int64)
+    before = C.codec_plan_device_bytes(plan)
+    for step in range(4):
+        lens = lens + rng.integers(0, 3 if step < 3 else 70, size=f.num_nodes)
+        g, gp = _grow_paged(f, head, lens, seed=2 + step)
+        assert C.codec_plan_refresh_lengths(plan, g.node_len, gp.node_page_off, gp.page_ids) == C.CODEC_OK
+        ref = P.refresh(ref, table, lens)
+        st, view = C.codec_plan_export(plan)
+        assert st == C.CODEC_OK
+        _compare(view, ref)
+    assert C.codec_plan_device_bytes(plan) >= before
+    C.codec_plan_destroy(plan)
+
+
+def test_refresh_error_paths_leave_the_plan_unchanged():
+    f = two_level_forest(5000, [300, 40, 77])
+    head = HeadConfig(8, 2, 128, 0)
+    paged = build_paged_kv(f, head, seed=1)
+    st, plan = C.codec_plan_create(f.parent, f.node_len, f.req_node, paged.node_page_off, paged.page_ids,
+                                   8, 2, 128, 0, 16, head.scale, 8, 32, 64, 1, None)
+    assert st == C.CODEC_OK
+    _, before = C.codec_plan_export(plan)
+    assert max(it["b"] for it in before["items"]) > 1
+    root_last = max(t["kv_begin"] for t in before["tasks"] if t["node"] == 0)
+    bad = f.node_len.copy()
+    bad[0] = root_last                              # the root's last slice would be empty
+    assert C.codec_plan_refresh_lengths(plan, bad, paged.node_page_off, paged.page_ids) == C.CODEC_ERR_INVALID_ARGUMENT
+    zero = f.node_len.copy()
+    zero[1] = 0
+    assert C.codec_plan_refresh_lengths(plan, zero, paged.node_page_off, paged.page_ids) == C.CODEC_ERR_INVALID_TREE
+    longer = f.node_len.copy()
+    longer[2] += 64                                 # pages of the old layout do not cover it
+    assert C.codec_plan_refresh_lengths(plan, longer, paged.node_page_off, paged.page_ids) == C.CODEC_ERR_INVALID_TREE
+    assert C.codec_plan_refresh_lengths(None, f.node_len, paged.node_page_off, paged.page_ids) == C.CODEC_ERR_INVALID_ARGUMENT
+    _, after = C.codec_plan_export(plan)
+    assert after["tasks"] == before["tasks"] and after["makespan"] == before["makespan"]
+    C.codec_plan_destroy(plan)
