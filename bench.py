@@ -47,6 +47,8 @@ def parse_args():
     ap.add_argument("--split-align", type=int, default=0)
     ap.add_argument("--max-rows", type=int, default=0)
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU time of the oracle sample")
+    ap.add_argument("--sweep", default="", help="run one of the paper-shaped synthetic sweeps instead of the "
+                    "configurations: seqlen, batch, depth, ratio, shape, ablation, granularity")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a plain 1 GiB device copy 3 times (reference for scaling FETCH_SIZE / "
                          "WRITE_SIZE counters when the run is profiled)")
@@ -158,6 +160,76 @@ def run_config(name, args, steps, warmup, want_flat):
     return res, w, outs[1]
 
 
+NO_DIVISION = 1 << 20          # split_align above every node length: no node is divided
+
+
+def run_sweep(args):
+    """Paper-shaped synthetic sweeps (Sec. 7): tree vs flat per point; the ablation grid; fixed slice counts."""
+    import torch
+    import paper_2505_17694_amd as C
+    from workloads import make_workload, forest_stats
+    from workloads.sweeps import sweep_points, sweep_head, SWEEP_SEED
+
+    head = sweep_head()
+    if args.sweep == "granularity":
+        points = sweep_points("ablation") + [p for p in sweep_points("batch") if p[0] == "requests=32"]
+        variants = [("adaptive", {})] + [(f"fixed={n}", {"fixed_slices": n}) for n in (1, 2, 4, 8, 16, 32, 64)]
+    elif args.sweep == "ablation":
+        points = sweep_points("ablation")
+        variants = [("none", {"share": 0, "split_align": NO_DIVISION}),
+                    ("tree_only", {"share": 1, "split_align": NO_DIVISION}),
+                    ("division_only", {"share": 0}), ("all", {"share": 1})]
+    else:
+        points = sweep_points(args.sweep)
+        variants = [("tree", {"share": 1}), ("flat", {"share": 0}), ("best_of_three", {"share": 2})]
+    steps = max(5, min(args.steps, 20))
+    out_points = []
+    for label, forest in points:
+        w = make_workload(label, forest, head, SWEEP_SEED, device="cuda:0", layout=args.layout)
+        st = forest_stats(forest)
+        unique_bytes = st["unique_tokens"] * head.bytes_per_token
+        pool_bytes = 2 * w.k_pool.numel() * 2
+        copies = max(1, min(int(math.ceil(COLD_FOOTPRINT_BYTES / max(pool_bytes, 1))), 64))
+        free, _ = torch.cuda.mem_get_info()
+        copies = max(1, min(copies, int(free * 0.8 // max(pool_bytes, 1)) + 1))
+        rot = Rotating(w, copies)
+        pt = {"point": label, "requests": st["num_requests"], "nodes": st["num_nodes"],
+              "unique_kv_bytes": unique_bytes, "mean_sharing": round(st["mean_sharing"], 3)}
+        for key, kw in variants:
+            opts = {"share": 1, "num_slots": args.num_slots, "split_align": args.split_align, "max_rows": args.max_rows}
+            opts.update(kw)
+            pa = C.PlannedAttention(w.forest, w.paged, w.head, device="cuda:0", **opts)
+            view = pa.export()
+            t, _ = time_plan(pa, w, rot, steps, args.warmup)
+            pt[key] = {"us_per_step": round(t["step_ms"] * 1e3, 2),
+                       "unique_kv_GBps": round(unique_bytes / (t["step_ms"] * 1e-3) / 1e9, 1),
+                       "tasks": len(view["tasks"]), "est_makespan": view["makespan"]}
+            if opts["share"] == 2:
+                pt[key]["picked"] = {"share": view["share"], "max_rows": view["max_rows"]}
+            pa.close()
+        base = {"ablation": "none", "granularity": "fixed=1"}.get(args.sweep, "flat")
+        best = {"ablation": "all", "granularity": "adaptive"}.get(args.sweep, "tree")
+        pt["speedup"] = round(pt[base]["us_per_step"] / pt[best]["us_per_step"], 3)
+        if args.sweep == "granularity":
+            fixed_best = min(v["us_per_step"] for k, v in pt.items() if isinstance(v, dict) and k.startswith("fixed="))
+            pt["adaptive_vs_best_fixed"] = round(fixed_best / pt["adaptive"]["us_per_step"], 3)
+        print(f"[sweep {args.sweep}] {label}: " + ", ".join(
+            f"{k} {v['us_per_step']} us" for k, v in pt.items() if isinstance(v, dict)) + f", speedup {pt['speedup']}x",
+              file=sys.stderr, flush=True)
+        out_points.append(pt)
+        del rot, w
+        torch.cuda.empty_cache()
+    speedups = [p["speedup"] for p in out_points]
+    geo = math.exp(sum(math.log(x) for x in speedups) / len(speedups))
+    line = {"metric": f"sweep_{args.sweep}_speedup_geomean", "value": round(geo, 3), "unit": "x",
+            "n_gpus": 1, "steps": steps, "warmup": args.warmup, "higher_is_better": True, "scaling": "weak",
+            "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+            "config": {"workload": f"sweep:{args.sweep}", "q_heads": head.num_q_heads, "kv_heads": head.num_kv_heads,
+                       "head_dim": head.head_dim, "page_size": head.page_size, "kv_layout": args.layout},
+            "points": out_points}
+    print(json.dumps(line))
+
+
 def cpu_baseline(w, gpu_out, seconds):
     """The fp64 oracle, as it stands, on a bounded sample of (request, head) pairs of the workload."""
     import numpy as np
@@ -209,6 +281,10 @@ def main():
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(2)
+
+    if args.sweep:
+        run_sweep(args)
+        return
 
     names = [c for c in args.configs.split(",") if c]
     if args.workload not in names:

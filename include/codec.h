@@ -100,8 +100,18 @@ typedef struct {
     int32_t max_rows;       /* most query rows (requests x group) one task may hold, 1..256,
                                >= group; 0 = 256.  Larger query sets are cut into row tiles.       */
     int32_t share;          /* 1 = prefix-shared plan; 0 = flat baseline: every request gets its
-                               own tasks for every node on its path, nothing shared across requests */
+                               own tasks for every node on its path, nothing shared across requests;
+                               2 = whichever of three plans has the lowest estimated makespan: the
+                               prefix-shared plan with row tiles of max_rows, the prefix-shared plan
+                               with row tiles of at most 16 rows (a query-dimension split, b_q > 1
+                               in the terms of Sec. 5.1, that fits the narrow kernel variant) and
+                               the flat plan; ties go to the earlier of the three.  The plan view
+                               reports the share and max_rows that won.                              */
     const codec_cost_table *cost;   /* NULL = built-in table of the kernel variant the plan needs     */
+    int32_t fixed_slices;   /* 0 = the paper's adaptive division (Eq. 4-5 and the grid search);
+                               n > 0 = the naive strategy it is compared with (Sec. 7, impact of
+                               division granularity): every node is cut evenly into n slices (fewer
+                               when the node is too short), then scheduled the same way            */
 } codec_plan_options;
 
 /* One work item of the division problem: a node (or a row tile of it) with its queries. */

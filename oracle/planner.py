@@ -108,7 +108,7 @@ def build_index(parent, node_len, req_node):
 
 
 def plan(parent, node_len, req_node, group: int, num_slots: int, align: int,
-         max_rows: int, share: bool, table: Dict) -> Dict:
+         max_rows: int, share: bool, table: Dict, fixed_slices: int = 0) -> Dict:
     parent = [int(x) for x in parent]
     node_len = [int(x) for x in node_len]
     req_node = [int(x) for x in req_node]
@@ -172,6 +172,12 @@ def plan(parent, node_len, req_node, group: int, num_slots: int, align: int,
 
     order = sorted((j for j in range(len(items)) if items[j]["ub"] > 1),
                    key=lambda j: (-items[j]["cost"], j))
+    if fixed_slices > 0:
+        # the naive strategy the paper compares with (impact of division granularity): the same
+        # slice count for every node, no bound, no search
+        order = []
+        for it in items:
+            it["b"] = slices(it["len"], min(fixed_slices, it["max_b"]), align)[0]
     for j in order:
         it = items[j]
         best_b, best_ms, seen = None, None, set()
@@ -258,3 +264,31 @@ def refresh(plan_out: Dict, table: Dict, new_node_len) -> Dict:
     out["items"], out["tasks"] = items, tasks
     out["makespan"] = max(loads) if loads else 0
     return out
+
+
+def plan_best(parent, node_len, req_node, group: int, align: int, max_rows: int, tables: Dict,
+              num_slots_of) -> Dict:
+    """share = 2 of the library: the candidate with the lowest estimated makespan, ties to the earlier.
+
+    Candidates: the prefix-shared plan with row tiles of ``max_rows``; the prefix-shared plan with row
+    tiles of at most 16 rows (a query-dimension split, b_q > 1 in the terms of Sec. 5.1); the flat plan.
+    ``tables`` = {"narrow": .., "wide": ..} and ``num_slots_of(wide)`` give each candidate the table and
+    slot count of the kernel variant its widest task selects, as the library does.
+    """
+    cands = [(True, max_rows)]
+    small = 16 // group * group if group <= 16 else 0
+    if small >= group and small < max_rows:
+        cands.append((True, small))
+    cands.append((False, max_rows))
+    best = None
+    for share, rows in cands:
+        paths, node_q = build_index([int(x) for x in parent], [int(x) for x in node_len], [int(x) for x in req_node])
+        qpt = max(1, rows // group) if share else 1
+        widest = max((min(qpt, len(q) - a) * group for q in node_q for a in range(0, len(q), qpt)), default=0)
+        wide = widest > 16
+        p = plan(parent, node_len, req_node, group, num_slots_of(wide), align, rows, share,
+                 tables["wide" if wide else "narrow"])
+        p["share"], p["max_rows"] = share, rows
+        if best is None or p["makespan"] < best["makespan"]:
+            best = p
+    return best

@@ -58,7 +58,7 @@ class codec_cost_table(Structure):
 
 class codec_plan_options(Structure):
     _fields_ = [("num_slots", c_int32), ("split_align", c_int32), ("max_rows", c_int32),
-                ("share", c_int32), ("cost", POINTER(codec_cost_table))]
+                ("share", c_int32), ("cost", POINTER(codec_cost_table)), ("fixed_slices", c_int32)]
 
 
 class codec_item(Structure):
@@ -168,7 +168,7 @@ def codec_last_error_message() -> str:
 
 def codec_plan_create(parent, node_len, req_node, node_page_off, page_ids,
                       num_q_heads, num_kv_heads, head_dim, dtype, page_size, scale,
-                      num_slots=0, split_align=0, max_rows=0, share=1, cost_table=None):
+                      num_slots=0, split_align=0, max_rows=0, share=1, cost_table=None, fixed_slices=0):
     """Returns (status, plan handle or None).  ``cost_table``: (row_grid, len_grid, cost) or None."""
     parent, node_len, req_node = _i32(parent), _i32(node_len), _i32(req_node)
     node_page_off, page_ids = _i32(node_page_off), _i32(page_ids)
@@ -180,7 +180,7 @@ def codec_plan_create(parent, node_len, req_node, node_page_off, page_ids,
     if cost_table is not None:
         ct, keep = make_cost_table(*cost_table)
         ct_ptr = ctypes.pointer(ct)
-    opt = codec_plan_options(num_slots, split_align, max_rows, share, ct_ptr)
+    opt = codec_plan_options(num_slots, split_align, max_rows, share, ct_ptr, fixed_slices)
     handle = c_void_p()
     st = _lib.codec_plan_create(byref(tree), byref(head), byref(opt), byref(handle))
     del keep

@@ -59,7 +59,7 @@ int codec_plan_create(const codec_tree *tree, const codec_head_config *head,
     if (!p) return CODEC_ERR_OUT_OF_MEMORY;
     int st;
     try {
-        st = codec::build_plan(*tree, *head, opt, p->d);
+        st = codec::build_best_plan(*tree, *head, opt, p->d);
     } catch (const std::bad_alloc &) {
         st = CODEC_ERR_OUT_OF_MEMORY;
     }

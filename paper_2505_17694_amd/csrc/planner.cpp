@@ -209,6 +209,7 @@ int build_plan(const codec_tree &tree, const codec_head_config &head,
     if (align % 32 != 0 || align % head.page_size != 0) return CODEC_ERR_INVALID_ARGUMENT;
     if (max_rows > 256 || max_rows < group) return CODEC_ERR_INVALID_ARGUMENT;
     if (opt.share != 0 && opt.share != 1) return CODEC_ERR_INVALID_ARGUMENT;
+    if (opt.fixed_slices < 0) return CODEC_ERR_INVALID_ARGUMENT;
 
     CostTable user;
     const CostTable *table = nullptr;           // nullptr: the built-in table of the kernel variant
@@ -361,7 +362,11 @@ int build_plan(const codec_tree &tree, const codec_head_config &head,
             }
         }
     };
-    {
+    if (opt.fixed_slices > 0) {
+        // the naive strategy of the granularity study: the same slice count for every node
+        for (size_t j = 0; j < J; ++j)
+            p.items[j].b = slice_node(p.items[j].len, std::min<int64_t>(opt.fixed_slices, max_b[j]), align).count;
+    } else {
         std::vector<int32_t> order;
         for (size_t j = 0; j < J; ++j)
             if (p.items[j].ub > 1) order.push_back(int32_t(j));
@@ -440,6 +445,38 @@ int build_plan(const codec_tree &tree, const codec_head_config &head,
     }
 
     build_device_image(p);
+    return CODEC_OK;
+}
+
+int build_best_plan(const codec_tree &tree, const codec_head_config &head,
+                    const codec_plan_options &opt, PlanData &plan)
+{
+    if (opt.share != 2) return build_plan(tree, head, opt, plan);
+    if (head.num_kv_heads < 1 || head.num_q_heads < 1 || head.num_q_heads % head.num_kv_heads != 0)
+        return CODEC_ERR_INVALID_ARGUMENT;
+    const int32_t group = head.num_q_heads / head.num_kv_heads;
+    codec_plan_options cand[3] = {opt, opt, opt};
+    int n = 0;
+    cand[n].share = 1;                                          // row tiles of max_rows (default 256)
+    ++n;
+    const int32_t small = group <= 16 ? 16 / group * group : 0; // row tiles of at most 16 rows
+    if (small >= group && (opt.max_rows == 0 || small < opt.max_rows)) {
+        cand[n].share = 1;
+        cand[n].max_rows = small;
+        ++n;
+    }
+    cand[n].share = 0;                                          // flat
+    ++n;
+    bool have = false;
+    for (int i = 0; i < n; ++i) {
+        PlanData trial;
+        const int st = build_plan(tree, head, cand[i], trial);
+        if (st != CODEC_OK) return st;
+        if (!have || trial.makespan < plan.makespan) {
+            plan = std::move(trial);
+            have = true;
+        }
+    }
     return CODEC_OK;
 }
 

@@ -62,6 +62,11 @@ const CostTable &builtin_cost_table(bool wide);
 int build_plan(const codec_tree &tree, const codec_head_config &head,
                const codec_plan_options &opt, PlanData &plan);
 
+// options.share == 2: builds the candidate plans named in codec.h and keeps the one with the lowest
+// estimated makespan (ties: the earlier candidate).  Other values: build_plan.
+int build_best_plan(const codec_tree &tree, const codec_head_config &head,
+                    const codec_plan_options &opt, PlanData &plan);
+
 // Carries `plan` over to new node lengths and page lists without dividing or scheduling again (the
 // paper divides tasks only every few decoding steps: Implementation section, task division module):
 // slices keep their boundaries, a node's last slice takes up the change in length, costs and the

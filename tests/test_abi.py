@@ -62,7 +62,7 @@ def test_bad_head_configs(head, status):
 
 
 @pytest.mark.parametrize("kw", [dict(num_slots=-1), dict(split_align=48), dict(split_align=16),
-                                dict(max_rows=257), dict(max_rows=2), dict(share=2),
+                                dict(max_rows=257), dict(max_rows=2), dict(share=3), dict(share=-1), dict(fixed_slices=-1),
                                 dict(cost_table=([1, 1], [10], [[1], [2]])),
                                 dict(cost_table=([1], [10, 5], [[1, 2]])),
                                 dict(cost_table=([1], [10], [[0]]))])

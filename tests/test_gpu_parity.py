@@ -195,6 +195,19 @@ def test_plan_carried_over_to_grown_lengths(share):
     pa.close()
 
 
+def test_best_of_three_plans_on_the_gpu():
+    """share = 2 on a forest where private leaves dominate and on one where the shared root does."""
+    low = two_level_forest(960, [2900, 3100, 2800, 3000])
+    high = two_level_forest(6000, [40] * 24)
+    head = HeadConfig(32, 8, 128, DTYPE_BF16)
+    picked = []
+    for i, f in enumerate((low, high)):
+        w = make_workload(f"best{i}", f, head, seed=40 + i, poison=True)
+        _, view = check(w, share=2)
+        picked.append((view["share"], view["max_rows"]))
+    assert picked[1] == (1, 256)
+
+
 def test_tree_equals_flat_on_the_gpu():
     w = make_small_config("cfg3", 16, 2, poison=True)
     tree, _ = run_gpu(w, share=1)

@@ -295,3 +295,50 @@ def test_refresh_keeps_the_invariants(name):
     assert max(loads) == q["makespan"]
     assert [(t["kv_begin"], t["slot"], t["part_row_base"]) for t in q["tasks"]] == \
         [(t["kv_begin"], t["slot"], t["part_row_base"]) for t in p["tasks"]]
+
+
+def test_fixed_slice_count_is_the_naive_even_division():
+    """Granularity study: every node cut evenly into n slices (fewer when it is too short)."""
+    f = two_level_forest(1200, [100, 250])
+    p = P.plan(f.parent, f.node_len, f.req_node, group=1, num_slots=4, align=100,
+               max_rows=64, share=True, table=LINEAR, fixed_slices=3)
+    assert [it["b"] for it in p["items"]] == [3, 1, 3]
+    assert [(t["node"], t["kv_begin"], t["kv_len"]) for t in p["tasks"]] == \
+        [(0, 0, 400), (0, 400, 400), (0, 800, 400), (1, 0, 100), (2, 0, 100), (2, 100, 100), (2, 200, 50)]
+    # longest first onto 4 slots: 400, 400, 400 | 100, 100, 100, 50 -> 350
+    assert p["makespan"] == 400
+    _check_invariants_of_division(f, p, 1, 4, 100)
+    one = P.plan(f.parent, f.node_len, f.req_node, 1, 4, 100, 64, True, LINEAR, fixed_slices=1)
+    assert [it["b"] for it in one["items"]] == [1, 1, 1] and one["makespan"] == 1200
+
+
+def _check_invariants_of_division(f, p, group, m, align):
+    by_item = {}
+    for t in p["tasks"]:
+        by_item.setdefault(t["item"], []).append(t)
+    for j, ts in by_item.items():
+        pos = 0
+        for t in ts:
+            assert t["kv_begin"] == pos and t["kv_begin"] % align == 0 and t["kv_len"] > 0
+            pos += t["kv_len"]
+        assert pos == f.node_len[p["items"][j]["node"]]
+    loads = [sum(p["tasks"][i]["cost"] for i in p["slot_tasks"][p["slot_off"][s]:p["slot_off"][s + 1]])
+             for s in range(m)]
+    assert max(loads) == p["makespan"]
+
+
+def test_best_of_three_plans_hand_worked():
+    """Two requests under a 100-token root, 100-token leaves, group 8, 2 slots, cost = rows * tokens.
+
+    Shared plan (16-row tiles cover both requests): root 16 * 100 = 1600, leaves 800 each -> loads
+    1600 | 1600 -> 1600.  Flat: four tasks of 800 -> 1600 as well: the tie goes to the shared plan.
+    With a table that charges rows beyond 8 triple, the shared root costs 8*100 + 3*8*100 = 3200
+    -> makespan 3200 and the flat plan (1600) wins.
+    """
+    f = two_level_forest(100, [100, 100])
+    prop = {"row_grid": [1, 17], "len_grid": [1, 101], "cost": [[1, 101], [17, 1717]]}          # rows * tokens
+    steep = {"row_grid": [8, 16], "len_grid": [1, 101], "cost": [[8, 808], [32, 3232]]}
+    for table, want_share, want_ms in ((prop, True, 1600), (steep, False, 1600)):
+        p = P.plan_best(f.parent, f.node_len, f.req_node, 8, 100, 16, {"narrow": table, "wide": table},
+                        lambda wide: 2)
+        assert (p["share"], p["makespan"]) == (want_share, want_ms)

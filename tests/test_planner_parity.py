@@ -174,3 +174,57 @@ def test_refresh_error_paths_leave_the_plan_unchanged():
     _, after = C.codec_plan_export(plan)
     assert after["tasks"] == before["tasks"] and after["makespan"] == before["makespan"]
     C.codec_plan_destroy(plan)
+
+
+@pytest.mark.parametrize("name", sorted(FORESTS))
+@pytest.mark.parametrize("fixed", [1, 2, 7, 64])
+def test_fixed_slice_count_matches_oracle(name, fixed):
+    f = FORESTS[name]()
+    head = HeadConfig(32, 8, 128, 1)
+    m, align, max_rows = 16, 64, 64
+    table = _default_table(1)
+    paged = build_paged_kv(f, head, seed=1)
+    st, plan = C.codec_plan_create(f.parent, f.node_len, f.req_node, paged.node_page_off, paged.page_ids,
+                                   head.num_q_heads, head.num_kv_heads, head.head_dim, head.dtype,
+                                   head.page_size, head.scale, m, align, max_rows, 1, _tuple(table),
+                                   fixed_slices=fixed)
+    assert st == C.CODEC_OK
+    st, view = C.codec_plan_export(plan)
+    C.codec_plan_destroy(plan)
+    _compare(view, P.plan(f.parent, f.node_len, f.req_node, 4, m, align, max_rows, True, table, fixed_slices=fixed))
+
+
+# ---- share = 2: best of three candidate plans ------------------------------------------------------
+
+BEST_CASES = {
+    # heavy sharing: the 256-row plan wins
+    "docqa": (lambda: two_level_forest(20000, [64] * 48), HeadConfig(32, 8, 128, 1)),
+    # a quarter of every context shared: the long private leaves decide, small row tiles or flat win
+    "quarter": (lambda: two_level_forest(30720, [92160] * 16), HeadConfig(32, 8, 128, 1)),
+    "nothing": (lambda: unshared_forest([40000] * 12), HeadConfig(32, 8, 128, 1)),
+    "random": (lambda: random_forest(60, 5, 2.0, 512, 1.0, 16, 32768, seed=8), HeadConfig(64, 8, 128, 1)),
+    "mha": (lambda: three_level_forest(2048, [8192] * 4, 5, [37 + 13 * i for i in range(20)]), HeadConfig(8, 8, 128, 0)),
+}
+
+
+@pytest.mark.parametrize("name", sorted(BEST_CASES))
+def test_best_of_three_plans_matches_oracle(name):
+    make, head = BEST_CASES[name]
+    f = make()
+    group = head.num_q_heads // head.num_kv_heads
+    paged = build_paged_kv(f, head, seed=1)
+    st, plan = C.codec_plan_create(f.parent, f.node_len, f.req_node, paged.node_page_off, paged.page_ids,
+                                   head.num_q_heads, head.num_kv_heads, head.head_dim, head.dtype,
+                                   head.page_size, head.scale, share=2)
+    assert st == C.CODEC_OK
+    st, view = C.codec_plan_export(plan)
+    C.codec_plan_destroy(plan)
+    tables = {"narrow": _default_table(0), "wide": _default_table(1)}
+    ref = P.plan_best(f.parent, f.node_len, f.req_node, group, 256, 256, tables,
+                      lambda wide: (256 if wide else 512) // head.num_kv_heads)
+    assert (view["share"], view["max_rows"]) == (int(ref["share"]), ref["max_rows"])
+    _compare(view, ref)
+    if name == "docqa":
+        assert (view["share"], view["max_rows"]) == (1, 256)
+    if name == "quarter":
+        assert (view["share"], view["max_rows"]) != (1, 256)
