@@ -327,6 +327,16 @@ def main():
 
     unique = res["unique_kv_bytes"]
     achieved = unique / (raw["pac_ms_avg"] * 1e-3) / 1e9
+    # HBM bytes per launch of the partial-attention kernel as counted by rocprofv3 (--pmc FETCH_SIZE and
+    # WRITE_SIZE, scaled by a known copy): a committed measurement of the same command, not taken live
+    traffic = None
+    try:
+        with open(os.path.join(ROOT, "profiles", "pac_kernel_traffic.json")) as f:
+            t = json.load(f).get(args.workload)
+        if t and args.layout == "htd" and not (args.num_slots or args.split_align or args.max_rows):
+            traffic = t["fetch_bytes"] + t["write_bytes"]
+    except OSError:
+        pass
     line = {
         "metric": "decode_attention_unique_kv_bandwidth",
         "value": res["tree"]["unique_kv_GBps"],
@@ -344,7 +354,7 @@ def main():
         "speedup_vs_flat": res.get("speedup_vs_flat"),
         "roofline": {"bound": "hbm", "kernel": "pac_kernel (partial attention)",
                      "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                     "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": None,
+                     "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": traffic,
                      "algorithmic_bytes_per_launch": unique,
                      "avg_launch_us": round(raw["pac_ms_avg"] * 1e3, 2)},
         "cpu_baseline": cpu,
