@@ -184,6 +184,9 @@ struct RowState {
 // rarely afterwards).
 constexpr float kLag = 8.f;
 
+// Wide variant: a task of at most 16 rows and at most this many tokens may be run by a single wave.
+constexpr int kSoloMaxLen = 1024;
+
 // Scores of tokens past `valid` become -inf (ragged last block of a slice).
 template <int NT>
 __device__ __forceinline__ void mask_scores(f32x4 (&s)[2][NT], int valid, int grp)
@@ -386,12 +389,13 @@ __device__ __forceinline__ SliceCtx make_ctx(const PacParams &P, const DevTask &
 // (keeps "-inf minus -inf" of a wave that saw no token out of the arithmetic).
 __device__ __forceinline__ float weight(float a, float m) { return a == m ? 1.f : fast_exp2(a - m); }
 
-// ---- stream path: rows <= 16*NT (NT = 1 in use), the W waves split the tokens ---------------------
+// ---- stream path: rows <= 16*NT (NT = 1 in use), a team of W waves splits the tokens ---------------
+// `wave` is the wave's index in its team.  A team of one wave (W = 1) uses no LDS and no barrier, so
+// several such waves may work on different tasks at the same time.
 template <int DT, int NT, int W>
-__device__ void run_stream(const PacParams &P, const DevTask &t, int head, char *lds_raw)
+__device__ void run_stream(const PacParams &P, const DevTask &t, int head, char *lds_raw, int wave)
 {
     const int lane = threadIdx.x & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int l16 = lane & 15, grp = lane >> 4;
     const int rows = t.n_req * P.group;
 
@@ -878,14 +882,38 @@ __global__ void __launch_bounds__(WIDE ? kWideWaves * 64 : kNarrowWaves * 64, 2)
     const int head = blockIdx.x % P.h_kv;
     const int slot = blockIdx.x / P.h_kv;
     const int t0 = P.slot_off[slot], t1 = P.slot_off[slot + 1];
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    if constexpr (WIDE != 0) {
+        // Tasks of more than 16 rows take the dense path.  Tasks of at most 16 rows take the stream path:
+        // as a rule with all eight waves as one team; runs of two or more short ones (they are neighbours
+        // in a slot's list, which is sorted by cost) up to eight at a time, one wave each, so that the
+        // latencies of a short task (descriptor, query rows, page ids, first blocks, merge of the team)
+        // overlap with the other tasks' instead of adding up.
+        auto solo = [&](const DevTask &t) { return t.n_req * P.group <= 16 && t.kv_len <= kSoloMaxLen; };
+        int i = t0;
 #pragma unroll 1
-    for (int i = t0; i < t1; ++i) {
-        const DevTask t = P.tasks[P.slot_tasks[i]];
-        const int rows = t.n_req * P.group;
-        if constexpr (WIDE != 0) {
-            run_dense32<DT>(P, t, head, lds);
-        } else if (rows <= 16) {
-            run_stream<DT, 1, W>(P, t, head, lds);
+        while (i < t1) {
+            const DevTask t = P.tasks[P.slot_tasks[i]];
+            int n = 1;
+            if (solo(t))
+                while (n < W && i + n < t1 && solo(P.tasks[P.slot_tasks[i + n]])) ++n;
+            if (n >= 2) {
+                if (wave < n) {
+                    const DevTask mine = P.tasks[P.slot_tasks[i + wave]];
+                    run_stream<DT, 1, 1>(P, mine, head, lds, 0);
+                }
+                i += n;
+            } else {
+                if (t.n_req * P.group <= 16) run_stream<DT, 1, W>(P, t, head, lds, wave);
+                else                         run_dense32<DT>(P, t, head, lds);
+                ++i;
+            }
+        }
+    } else {
+#pragma unroll 1
+        for (int i = t0; i < t1; ++i) {
+            const DevTask t = P.tasks[P.slot_tasks[i]];
+            if (t.n_req * P.group <= 16) run_stream<DT, 1, W>(P, t, head, lds, wave);
         }
     }
 }

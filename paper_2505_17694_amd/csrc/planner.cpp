@@ -169,17 +169,17 @@ const CostTable &builtin_cost_table(bool wide)
     static const CostTable narrow_table = {
         {1, 16},
         {32, 128, 512, 2048, 8192, 32768},
-        {4079, 5179, 24737, 93649, 368698, 1471049,
-         5459, 6459, 29336, 100148, 377095, 1470742}};
+        {4060, 4960, 24278, 92849, 368280, 1466307,
+         5479, 5959, 29436, 101128, 374916, 1472026}};
     static const CostTable wide_table = {
         {1, 16, 32, 64, 128, 256},
         {32, 128, 512, 2048, 8192, 32768},
-        {2140, 7159, 13999, 47014, 182318, 746569,
-         3239, 7139, 16278, 50174, 187097, 750429,
-         3099, 7419, 17998, 52714, 192456, 751968,
-         4980, 8499, 18178, 56133, 193317, 747368,
-         8219, 10079, 22857, 65132, 240850, 851216,
-         11499, 14898, 34716, 77330, 334079, 1224150}};
+        {120, 3859, 10439, 46714, 180198, 740511,
+         740, 4299, 10518, 49454, 183498, 754168,
+         3339, 7899, 16897, 52254, 190697, 740890,
+         6859, 8759, 20197, 57673, 196336, 737290,
+         8859, 11099, 23658, 64272, 247110, 876172,
+         11919, 15638, 34116, 77711, 312482, 1211731}};
     return wide ? wide_table : narrow_table;
 }
 
