@@ -184,9 +184,6 @@ struct RowState {
 // rarely afterwards).
 constexpr float kLag = 8.f;
 
-// Wide variant: a task of at most 16 rows and at most this many tokens may be run by a single wave.
-constexpr int kSoloMaxLen = 1024;
-
 // Scores of tokens past `valid` become -inf (ragged last block of a slice).
 template <int NT>
 __device__ __forceinline__ void mask_scores(f32x4 (&s)[2][NT], int valid, int grp)
@@ -883,37 +880,36 @@ __global__ void __launch_bounds__(WIDE ? kWideWaves * 64 : kNarrowWaves * 64, 2)
     const int slot = blockIdx.x / P.h_kv;
     const int t0 = P.slot_off[slot], t1 = P.slot_off[slot + 1];
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    if constexpr (WIDE != 0) {
-        // Tasks of more than 16 rows take the dense path.  Tasks of at most 16 rows take the stream path:
-        // as a rule with all eight waves as one team; runs of two or more short ones (they are neighbours
-        // in a slot's list, which is sorted by cost) up to eight at a time, one wave each, so that the
-        // latencies of a short task (descriptor, query rows, page ids, first blocks, merge of the team)
-        // overlap with the other tasks' instead of adding up.
-        auto solo = [&](const DevTask &t) { return t.n_req * P.group <= 16 && t.kv_len <= kSoloMaxLen; };
-        int i = t0;
+    // Tasks of more than 16 rows take the dense path (wide variant only).  Tasks of at most 16 rows take
+    // the stream path, as a rule with all waves of the workgroup as one team.  Runs of two or more short
+    // ones (the plan marks them; they are neighbours in a slot's list, which is sorted by cost) are
+    // handed out one wave each through a counter in LDS: the latencies of a short task (descriptor,
+    // query rows, page ids, first blocks, merge of a team) then overlap with the other tasks' instead of
+    // adding up.
+    int i = t0;
 #pragma unroll 1
-        while (i < t1) {
-            const DevTask t = P.tasks[P.slot_tasks[i]];
-            int n = 1;
-            if (solo(t))
-                while (n < W && i + n < t1 && solo(P.tasks[P.slot_tasks[i + n]])) ++n;
-            if (n >= 2) {
-                if (wave < n) {
-                    const DevTask mine = P.tasks[P.slot_tasks[i + wave]];
-                    run_stream<DT, 1, 1>(P, mine, head, lds, 0);
-                }
-                i += n;
-            } else {
-                if (t.n_req * P.group <= 16) run_stream<DT, 1, W>(P, t, head, lds, wave);
-                else                         run_dense32<DT>(P, t, head, lds);
-                ++i;
+    while (i < t1) {
+        const DevTask t = P.tasks[P.slot_tasks[i]];
+        const int n = t.solo_run;
+        if (n >= 2) {
+            int *next = reinterpret_cast<int *>(lds);
+            if (threadIdx.x == 0) *next = 0;
+            __syncthreads();
+#pragma unroll 1
+            for (;;) {
+                int k = 0;
+                if ((threadIdx.x & 63) == 0) k = atomicAdd(next, 1);
+                k = __builtin_amdgcn_readfirstlane(k);
+                if (k >= n) break;
+                const DevTask mine = P.tasks[P.slot_tasks[i + k]];
+                run_stream<DT, 1, 1>(P, mine, head, lds, 0);
             }
-        }
-    } else {
-#pragma unroll 1
-        for (int i = t0; i < t1; ++i) {
-            const DevTask t = P.tasks[P.slot_tasks[i]];
+            __syncthreads();                // the counter is done with before LDS is used again
+            i += n;
+        } else {
             if (t.n_req * P.group <= 16) run_stream<DT, 1, W>(P, t, head, lds, wave);
+            else if constexpr (WIDE != 0) run_dense32<DT>(P, t, head, lds);
+            ++i;
         }
     }
 }

@@ -119,6 +119,14 @@ void build_device_image(PlanData &p)
         dt[i].n_req = t.n_req;
         dt[i].part_row_base = t.part_row_base;
     }
+    for (int32_t sl = 0; sl < p.num_slots; ++sl) {                      // runs of single-wave tasks, back to front
+        int32_t run = 0;
+        for (int32_t i = p.slot_off[sl + 1] - 1; i >= p.slot_off[sl]; --i) {
+            const codec_task &t = p.tasks[p.slot_tasks[i]];
+            run = (t.n_req * p.group <= kSoloMaxRows && t.kv_len <= kSoloMaxLen) ? run + 1 : 0;
+            dt[p.slot_tasks[i]].solo_run = run;
+        }
+    }
     auto put = [&](size_t at, const std::vector<int32_t> &v) {
         if (!v.empty()) std::memcpy(p.blob.data() + at, v.data(), v.size() * 4);
     };
@@ -169,17 +177,17 @@ const CostTable &builtin_cost_table(bool wide)
     static const CostTable narrow_table = {
         {1, 16},
         {32, 128, 512, 2048, 8192, 32768},
-        {4060, 4960, 24278, 92849, 368280, 1466307,
-         5479, 5959, 29436, 101128, 374916, 1472026}};
+        {3060, 3299, 23398, 92892, 364391, 1467712,
+         5079, 4939, 27417, 100390, 373084, 1460054}};
     static const CostTable wide_table = {
         {1, 16, 32, 64, 128, 256},
         {32, 128, 512, 2048, 8192, 32768},
-        {120, 3859, 10439, 46714, 180198, 740511,
-         740, 4299, 10518, 49454, 183498, 754168,
-         3339, 7899, 16897, 52254, 190697, 740890,
-         6859, 8759, 20197, 57673, 196336, 737290,
-         8859, 11099, 23658, 64272, 247110, 876172,
-         11919, 15638, 34116, 77711, 312482, 1211731}};
+        {1, 3620, 9959, 46515, 179042, 741701,
+         680, 4499, 10819, 49995, 183860, 745060,
+         3480, 7739, 17018, 50815, 187480, 737899,
+         6959, 8660, 18898, 56054, 195338, 746798,
+         8379, 11338, 22658, 63333, 245413, 850906,
+         12439, 15818, 32897, 85311, 310806, 1198527}};
     return wide ? wide_table : narrow_table;
 }
 

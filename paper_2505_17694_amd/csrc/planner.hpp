@@ -19,6 +19,11 @@ struct CostTable {
     int64_t estimate(int64_t rows, int64_t len) const;
 };
 
+// A task of at most kSoloMaxRows rows and kSoloMaxLen tokens may be run by a single wave; the kernels
+// take runs of such tasks in a slot's list one wave each (see solo_run below).
+constexpr int32_t kSoloMaxRows = 16;
+constexpr int32_t kSoloMaxLen = 1024;
+
 // Task record as the kernels read it (32 bytes).
 struct DevTask {
     int32_t page_off;       // index into the device copy of page_ids of the slice's first page
@@ -26,7 +31,8 @@ struct DevTask {
     int32_t q_off;          // first request of the task in node_q
     int32_t n_req;          // requests in the task
     int32_t part_row_base;  // first partial row
-    int32_t reserved[3];
+    int32_t solo_run;       // number of consecutive single-wave tasks in the slot's list from this one on
+    int32_t reserved[2];
 };
 
 // Byte offsets of the arrays inside the device metadata blob.
