@@ -208,6 +208,25 @@ def test_best_of_three_plans_on_the_gpu():
     assert picked[1] == (1, 256)
 
 
+@pytest.mark.parametrize("slots", [1, 3])
+@pytest.mark.parametrize("upside_down", [False, True])
+def test_many_short_tasks_per_slot(slots, upside_down):
+    """Long runs of single-wave tasks in a slot's list, before, between and behind team and dense tasks.
+
+    With the upside-down cost table short tasks count as the most expensive, so longest-first
+    scheduling puts them in front of the long ones; lengths around the single-wave limit (1024) and
+    request counts around the 16-row limit mix the three task shapes in every slot.
+    """
+    lens = [7, 40, 1024, 33, 1025, 64, 300, 5, 2000, 96, 17, 1000, 31, 640, 1, 129] * 3
+    f = concat_forests(two_level_forest(1500, lens), two_level_forest(200, [50, 60, 70, 80, 90]))
+    head = HeadConfig(8, 2, 128, DTYPE_BF16)                    # group 4: the 5-request root has 20 rows
+    w = make_workload(f"short{slots}", f, head, seed=23, poison=True)
+    table = ([1, 256], [1, 4096], [[5000, 100], [6000, 200]]) if upside_down else None
+    _, view = check(w, num_slots=slots, split_align=32, cost_table=table)
+    per_slot = np.bincount([t["slot"] for t in view["tasks"]], minlength=slots)
+    assert per_slot.max() >= 16
+
+
 def test_tree_equals_flat_on_the_gpu():
     w = make_small_config("cfg3", 16, 2, poison=True)
     tree, _ = run_gpu(w, share=1)
