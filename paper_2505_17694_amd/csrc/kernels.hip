@@ -1,12 +1,13 @@
 // gfx950 kernels: partial attention computation (paper Alg. 2) over the scheduled
 // task lists, and partial output reduction (Alg. 3) per query (Alg. 4).
 //
-// Partial attention.  One persistent 256-thread workgroup per (slot, KV head)
-// walks the slot's task list.  A task is a KV slice of a node together with the
-// query rows of the requests below the node: rows = requests x heads of the GQA
-// group, gathered straight from the query tensor into MFMA operand registers
-// (the on-chip query assembly of Sec. 4.1).  Every K and V byte of the slice is
-// fetched from HBM once per task and serves all rows.
+// Partial attention.  One persistent workgroup per (slot, KV head) walks the
+// slot's task list (256 threads in the narrow launch variant, 512 in the wide one).
+// A task is a KV slice of a node together with the query rows of the requests
+// below the node: rows = requests x heads of the GQA group, gathered straight from
+// the query tensor into MFMA operand registers (the on-chip query assembly of
+// Sec. 4.1).  Every K and V byte of the slice is fetched from HBM once per task and
+// serves all rows.
 //
 // Arithmetic of one 32-token block, per wave: S^T = K Q^T (tokens x rows) on the
 // matrix unit, K rows as the A operand, Q as the B operand.  The accumulator
@@ -17,16 +18,17 @@
 // units.
 //
 // Two task shapes share that arithmetic:
-//  * "stream" (plans whose tasks all have at most 16 rows, e.g. the flat baseline):
-//    16 x 16 x 32 tiles; four waves take interleaved 32-token blocks of the slice,
-//    each with all rows; K and V go from HBM straight to registers (no LDS in the
-//    loop; V becomes an A operand by an 8x8 16-bit transpose inside each lane,
-//    v_perm_b32); the waves' states are merged through LDS at the end.
-//  * "dense" (every other plan, tasks of 1..256 rows): 32 x 32 x 16 tiles; eight
-//    waves split the rows (32 each) and walk the slice together; blocks are copied
-//    HBM -> LDS asynchronously into a ring of eight 16 KB slots (six blocks in
-//    flight, one barrier per block) and read by all waves, V through transposing
-//    LDS reads (ds_read_b64_tr_b16).
+//  * "stream" (tasks of at most 16 rows, in both launch variants): 16 x 16 x 32
+//    tiles; the waves of the workgroup take interleaved 32-token blocks of the
+//    slice as one team, each with all rows; K and V go from HBM straight to
+//    registers (no LDS in the loop; V becomes an A operand by an 8x8 16-bit
+//    transpose inside each lane, v_perm_b32); the waves' states are merged through
+//    LDS at the end.  Runs of short tasks are handed out one wave each instead.
+//  * "dense" (tasks of 17..256 rows, wide variant): 32 x 32 x 16 tiles; eight waves
+//    split the rows (32 each) and walk the slice together; blocks are copied HBM ->
+//    LDS asynchronously into a ring of eight 16 KB slots (six blocks in flight, one
+//    barrier per block) and read by all waves, V through transposing LDS reads
+//    (ds_read_b64_tr_b16).
 #include <hip/hip_runtime.h>
 
 #include <type_traits>
@@ -138,13 +140,11 @@ __device__ __forceinline__ void load_block(const SliceCtx &c, int tb, uint32_t k
 
 template <int NT>
 struct RowState {
-    f32x4 o[NT][8];     // [row tile][dt]: row = 16*nt + lane%16; channel of component e: stream path
-                        // 32*(lane/16) + 8*e + dt, dense path 16*dt + 4*(lane/16) + e
-    f32x4 lsum[NT];     // row sum of exponentials, accumulated by the matrix unit against an all-ones
-                        // A operand: four equal copies per lane, complete over all 32 tokens of a block
+    f32x4 o[NT][8];     // [row tile][dt]: row = 16*nt + lane%16; channel of component e is
+                        // 32*(lane/16) + 8*e + dt
     float m[NT];        // reference subtracted before exponentiation, log2 units (same in the 4 lanes
                         // that share a row)
-    float l[NT];        // final row sum, filled by finish()
+    float l[NT];        // the lane's share of the row sum; the row sum after finish()
 
     __device__ __forceinline__ void clear()
     {
@@ -152,24 +152,17 @@ struct RowState {
         for (int nt = 0; nt < NT; ++nt) {
             m[nt] = -INFINITY;
             l[nt] = 0.f;
-            lsum[nt] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
             for (int dt = 0; dt < 8; ++dt) o[nt][dt] = f32x4{0.f, 0.f, 0.f, 0.f};
         }
     }
-    // MSUM: the row sums were accumulated by the matrix unit; otherwise each lane summed its own 8
-    // tokens per block and the four lanes of a row are added up here.
-    template <bool MSUM>
+    // each lane summed its own 8 tokens per block: the four lanes of a row are added up
     __device__ __forceinline__ void finish()
     {
 #pragma unroll
         for (int nt = 0; nt < NT; ++nt) {
-            if constexpr (MSUM) {
-                l[nt] = lsum[nt][0];
-            } else {
-                l[nt] += __shfl_xor(l[nt], 16);
-                l[nt] += __shfl_xor(l[nt], 32);
-            }
+            l[nt] += __shfl_xor(l[nt], 16);
+            l[nt] += __shfl_xor(l[nt], 32);
         }
     }
 };
@@ -242,7 +235,6 @@ __device__ __forceinline__ void raise_reference(const float (&lm)[NT], RowState<
         mx = fmaxf(mx, __shfl_xor(mx, 32));
         const float m_new = fmaxf(st.m[nt], mx);
         const float alpha = fast_exp2(st.m[nt] - m_new);       // 0 on the first block (m = -inf)
-        st.lsum[nt] *= alpha;
         st.l[nt] *= alpha;
 #pragma unroll
         for (int dt = 0; dt < 8; ++dt) st.o[nt][dt] *= alpha;
@@ -250,9 +242,9 @@ __device__ __forceinline__ void raise_reference(const float (&lm)[NT], RowState<
     }
 }
 
-// P = exp2(scale * S - m), rounded to 16 bits in B-operand layout.  With VSUM the lane also adds its
-// 8 exponentials to its share of the row sum.
-template <int DT, int NT, bool VSUM>
+// P = exp2(scale * S - m), rounded to 16 bits in B-operand layout; the lane adds its 8 exponentials to
+// its share of the row sum.
+template <int DT, int NT>
 __device__ __forceinline__ void probabilities(const f32x4 (&s)[2][NT], RowState<NT> &st,
                                               float scale_log2e, u32x4 (&pb)[NT])
 {
@@ -264,21 +256,10 @@ __device__ __forceinline__ void probabilities(const f32x4 (&s)[2][NT], RowState<
 #pragma unroll
             for (int e = 0; e < 4; ++e)
                 p[j][e] = fast_exp2(__builtin_fmaf(s[j][nt][e], scale_log2e, -st.m[nt]));
-        if constexpr (VSUM)
-            st.l[nt] += ((p[0][0] + p[0][1]) + (p[0][2] + p[0][3])) + ((p[1][0] + p[1][1]) + (p[1][2] + p[1][3]));
+        st.l[nt] += ((p[0][0] + p[0][1]) + (p[0][2] + p[0][3])) + ((p[1][0] + p[1][1]) + (p[1][2] + p[1][3]));
         pb[nt] = u32x4{pack2<DT>(p[0][0], p[0][1]), pack2<DT>(p[0][2], p[0][3]),
                        pack2<DT>(p[1][0], p[1][1]), pack2<DT>(p[1][2], p[1][3])};
     }
-}
-
-// Row sums += 1^T P^T on the matrix unit (an all-ones A operand: every output row is the column sum).
-template <int DT, int NT>
-__device__ __forceinline__ void accumulate_row_sums(const u32x4 (&pb)[NT], RowState<NT> &st)
-{
-    constexpr unsigned int one2 = DT == CODEC_DTYPE_FP16 ? 0x3C003C00u : 0x3F803F80u;
-    const u32x4 ones = {one2, one2, one2, one2};
-#pragma unroll
-    for (int nt = 0; nt < NT; ++nt) st.lsum[nt] = mfma16<DT>(ones, pb[nt], st.lsum[nt]);
 }
 
 // O^T += V^T P^T for the channel tiles dt = 4*HALF .. 4*HALF+3.  `vh[e]` holds dwords 2*HALF and
@@ -335,9 +316,7 @@ __device__ __forceinline__ void gather_q(const PacParams &P, const DevTask &t, i
 }
 
 // Write one wave's rows of the partial result: unnormalised output, (reference, sum) per row.
-// TR selects the channel map of the accumulators: false (stream path) channel = 32*grp + 8*e + dt,
-// true (dense path, transposing V reads) channel = 16*dt + 4*grp + e.
-template <int NT, bool TR>
+template <int NT>
 __device__ __forceinline__ void store_partial(const PacParams &P, const DevTask &t, int head, int row0, int rows,
                                               int l16, int grp, const RowState<NT> &st)
 {
@@ -346,19 +325,13 @@ __device__ __forceinline__ void store_partial(const PacParams &P, const DevTask 
         const int row = row0 + nt * 16 + l16;
         if (row < rows) {
             const int64_t prow = int64_t(head) * P.part_rows + t.part_row_base + row;
-            if constexpr (TR) {
-                float *po = P.part_o + prow * kHeadDim + grp * 4;
+            float *po = P.part_o + prow * kHeadDim + grp * 32;
 #pragma unroll
-                for (int dt = 0; dt < 8; ++dt) *reinterpret_cast<f32x4 *>(po + dt * 16) = st.o[nt][dt];
-            } else {
-                float *po = P.part_o + prow * kHeadDim + grp * 32;
-#pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    f32x4 lo = {st.o[nt][0][e], st.o[nt][1][e], st.o[nt][2][e], st.o[nt][3][e]};
-                    f32x4 hi = {st.o[nt][4][e], st.o[nt][5][e], st.o[nt][6][e], st.o[nt][7][e]};
-                    *reinterpret_cast<f32x4 *>(po + e * 8) = lo;
-                    *reinterpret_cast<f32x4 *>(po + e * 8 + 4) = hi;
-                }
+            for (int e = 0; e < 4; ++e) {
+                f32x4 lo = {st.o[nt][0][e], st.o[nt][1][e], st.o[nt][2][e], st.o[nt][3][e]};
+                f32x4 hi = {st.o[nt][4][e], st.o[nt][5][e], st.o[nt][6][e], st.o[nt][7][e]};
+                *reinterpret_cast<f32x4 *>(po + e * 8) = lo;
+                *reinterpret_cast<f32x4 *>(po + e * 8 + 4) = hi;
             }
             if (grp == 0) {
                 float2 ml = {st.m[nt], st.l[nt]};
@@ -425,7 +398,7 @@ __device__ void run_stream(const PacParams &P, const DevTask &t, int head, char 
         lane_maxima<NT>(s, P.scale_log2e, lm);
         if (__any(outgrown<NT>(lm, st))) raise_reference<NT>(lm, st);
         u32x4 pb[NT];
-        probabilities<DT, NT, true>(s, st, P.scale_log2e, pb);
+        probabilities<DT, NT>(s, st, P.scale_log2e, pb);
         accumulate<DT, NT>(r.v, pb, st);
     };
 
@@ -446,7 +419,7 @@ __device__ void run_stream(const PacParams &P, const DevTask &t, int head, char 
         tb = nb;
     }
 
-    st.template finish<false>();
+    st.finish();
 
     // merge the waves' states pairwise through LDS: waves [h, 2h) hand theirs to waves [0, h), h = W/2 .. 1
     constexpr int kState = NT * 8 * 64 * 4 + NT * 64 * 2;              // floats per handed-over state
@@ -483,7 +456,7 @@ __device__ void run_stream(const PacParams &P, const DevTask &t, int head, char 
         }
         __syncthreads();
     }
-    if (wave == 0) store_partial<NT, false>(P, t, head, 0, rows, l16, grp, st);
+    if (wave == 0) store_partial<NT>(P, t, head, 0, rows, l16, grp, st);
 }
 
 // ---- dense path: 1..256 rows, the 8 waves split the rows (32 each) and share each block ------------
