@@ -888,26 +888,47 @@ __global__ void __launch_bounds__(WIDE ? kWideWaves * 64 : kNarrowWaves * 64, 2)
 }
 
 // Partial output reduction (Alg. 3), n-ary: one wave per (request, query head) folds the request's
-// partials in list order; each lane owns two channels.
+// partials in list order; each lane owns two channels.  Partials are taken eight at a time: their
+// loads are issued together, then the eight are folded against their common maximum (by
+// associativity of the reduction this equals any binary bracketing).
 template <int DT>
 __global__ void __launch_bounds__(kMergeWaves * 64) merge_kernel(const MergeParams P)
 {
+    constexpr int kChunk = 8;
     const int lane = threadIdx.x & 63;
     const int row = blockIdx.x * kMergeWaves + (threadIdx.x >> 6);
     if (row >= P.num_requests * P.h_q) return;
     const int r = row / P.h_q, hq = row - r * P.h_q;
     const int head = hq / P.group, hj = hq - head * P.group;
     const int e0 = P.req_part_off[r], e1 = P.req_part_off[r + 1];
+    const int64_t head_base = int64_t(head) * P.part_rows + hj;
     float M = -INFINITY, L = 0.f, a0 = 0.f, a1 = 0.f;
-    for (int e = e0; e < e1; ++e) {
-        const int64_t prow = int64_t(head) * P.part_rows + P.req_part[e] + hj;
-        const float2 ml = *reinterpret_cast<const float2 *>(P.part_ml + prow * 2);
-        const float2 o = *reinterpret_cast<const float2 *>(P.part_o + prow * kHeadDim + lane * 2);
-        const float mm = fmaxf(M, ml.x);
-        const float wa = weight(M, mm), wb = weight(ml.x, mm);
-        L = L * wa + ml.y * wb;
-        a0 = a0 * wa + o.x * wb;
-        a1 = a1 * wa + o.y * wb;
+#pragma unroll 1
+    for (int base = e0; base < e1; base += kChunk) {
+        const int cnt = e1 - base < kChunk ? e1 - base : kChunk;
+        float2 ml[kChunk], o[kChunk];
+#pragma unroll
+        for (int j = 0; j < kChunk; ++j) {
+            const int64_t prow = head_base + P.req_part[base + (j < cnt ? j : 0)];
+            ml[j] = *reinterpret_cast<const float2 *>(P.part_ml + prow * 2);
+            o[j] = *reinterpret_cast<const float2 *>(P.part_o + prow * kHeadDim + lane * 2);
+        }
+        float mm = M;
+#pragma unroll
+        for (int j = 0; j < kChunk; ++j)
+            if (j < cnt) mm = fmaxf(mm, ml[j].x);
+        const float wa = weight(M, mm);
+        L *= wa;
+        a0 *= wa;
+        a1 *= wa;
+#pragma unroll
+        for (int j = 0; j < kChunk; ++j)
+            if (j < cnt) {
+                const float wb = weight(ml[j].x, mm);
+                L += ml[j].y * wb;
+                a0 += o[j].x * wb;
+                a1 += o[j].y * wb;
+            }
         M = mm;
     }
     const float inv = 1.f / L;
