@@ -227,6 +227,31 @@ def test_many_short_tasks_per_slot(slots, upside_down):
     assert per_slot.max() >= 16
 
 
+def test_limits_of_the_interface():
+    """Largest page size (4096 tokens), largest GQA group (64: four requests fill a 256-row task), and a
+    context of a million tokens divided over every slot (sampled outputs: the oracle needs seconds per pair)."""
+    head = HeadConfig(8, 2, 128, DTYPE_BF16, page_size=4096)
+    w = make_workload("page4096", two_level_forest(5000, [4097, 100, 4096]), head, seed=51, poison=True)
+    check(w, split_align=4096, num_slots=4)
+    head = HeadConfig(64, 1, 128, DTYPE_FP16)
+    w = make_workload("group64", two_level_forest(700, [33, 5, 90, 64, 17]), head, seed=52, poison=True)
+    _, view = check(w, num_slots=8, split_align=32)
+    assert max(t["n_req"] * 64 for t in view["tasks"]) == 256
+    head = HeadConfig(8, 8, 128, DTYPE_BF16)
+    w = make_workload("million", unshared_forest([1 << 20]), head, seed=53, device="cuda:0")
+    C = _C()
+    pa = C.PlannedAttention(w.forest, w.paged, w.head, device="cuda:0")
+    out = pa.decode(w.q, w.k_pool, w.v_pool)
+    torch.cuda.synchronize()
+    view = pa.export()
+    pa.close()
+    assert len(view["tasks"]) >= view["num_slots"]
+    sel = [(0, 0), (0, 5)]
+    ref, _ = A.decode_attention_workload(w, sel=sel)
+    got = np.stack([out[r, h].to(torch.float64).cpu().numpy() for r, h in sel])
+    assert np.abs(got - ref).max() <= TOL
+
+
 def test_tree_equals_flat_on_the_gpu():
     w = make_small_config("cfg3", 16, 2, poison=True)
     tree, _ = run_gpu(w, share=1)
