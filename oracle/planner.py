@@ -8,6 +8,14 @@ found by binary search on the average-load inequality (Eq. 4), the per-node
 upper bound on the number of KV slices (Eq. 5), a grid search over each node's
 slice count, and greedy longest-first scheduling onto m slots (Eq. 3).
 
+Reading of Eq. 5.  The bound ceil(C_est / cost_l) exists to prune the search:
+the paper notes that it leaves most nodes, whose cost is far below the average
+load, undivided.  Taken to the letter it also forbids the one extra slice that
+lets a few nodes of 0.3 .. 1 average loads pack evenly onto the slots (64
+contexts of 0.4 loads each on 32 slots: two per slot, or three), so a node
+whose cost is at least a quarter of cost_l may take one slice more than the
+quotient; every other node keeps the printed bound.
+
 The paper gives the solver in prose; where it is silent this file fixes:
 integer costs; round-half-up bilinear interpolation, clamped below the grid
 and linearly extrapolated above it; slice boundaries on multiples of
@@ -158,7 +166,10 @@ def plan(parent, node_len, req_node, group: int, num_slots: int, align: int,
         cost_l = lo
 
     for it in items:
-        it["ub"] = slices(it["len"], b_of(it, cost_l), align)[0]
+        want = b_of(it, cost_l)                                   # Eq. 5: the quotient
+        if 4 * it["cost"] >= cost_l:
+            want = min(want + 1, it["max_b"])                     # one slice of slack for nodes that matter
+        it["ub"] = slices(it["len"], want, align)[0]
         it["b"] = it["ub"]
 
     def subtasks():

@@ -350,8 +350,13 @@ int build_plan(const codec_tree &tree, const codec_head_config &head,
         }
         p.cost_l = lo;
     }
+    // Eq. 5 prunes the search (most nodes cost far less than the average load and stay whole).  A node
+    // whose cost is at least a quarter of cost_l may take one slice more than the quotient: without it
+    // a few nodes of 0.3 .. 1 average loads cannot be packed evenly onto the slots.
     for (size_t j = 0; j < J; ++j) {
-        p.items[j].ub = slice_node(p.items[j].len, slices_at(j, p.cost_l), align).count;
+        int64_t want = slices_at(j, p.cost_l);
+        if (4 * p.items[j].cost >= p.cost_l) want = std::min(want + 1, max_b[j]);
+        p.items[j].ub = slice_node(p.items[j].len, want, align).count;
         p.items[j].b = p.items[j].ub;
     }
 

@@ -148,9 +148,11 @@ def _check_invariants(f, p, group, m, align):
     assert max(loads) == p["makespan"]
     total = sum(t["cost"] for t in p["tasks"])
     assert p["makespan"] >= max(-(-total // m), max(t["cost"] for t in p["tasks"]))
-    # Eq. 5: slice counts stay within the bound derived from cost_l
+    # Eq. 5: slice counts stay within the bound derived from cost_l (the quotient, plus one slice for a
+    # node whose cost is at least a quarter of cost_l)
     for it in p["items"]:
-        assert 1 <= it["b"] <= it["ub"] <= max(1, -(-it["cost"] // p["cost_l"]))
+        slack = 1 if 4 * it["cost"] >= p["cost_l"] else 0
+        assert 1 <= it["b"] <= it["ub"] <= max(1, -(-it["cost"] // p["cost_l"])) + slack
     # Eq. 4 at cost_l: the division it induces fits m slots on average, the next finer T does not
     def tot(T):
         return sum(P.division_cost(p["table"], it["rows"], it["len"],
@@ -342,3 +344,26 @@ def test_best_of_three_plans_hand_worked():
         p = P.plan_best(f.parent, f.node_len, f.req_node, 8, 100, 16, {"narrow": table, "wide": table},
                         lambda wide: 2)
         assert (p["share"], p["makespan"]) == (want_share, want_ms)
+
+
+def test_slice_bound_slack_hand_worked():
+    """Eight 1000-token contexts and a 100-token one on 4 slots, cost = tokens, slices of 100 tokens.
+
+    Total 8100 -> cost_l = 2025; every quotient is 1.  The printed bound keeps all nodes whole: two
+    long contexts per slot and the short one on top, makespan 2100.  With one slice of slack for
+    nodes of at least cost_l / 4 = 507 (the long ones; not the short one) the search may halve a long
+    context; it does so for none, because two per slot already is the best packing, and the short
+    node stays whole in any case.
+    """
+    f = unshared_forest([1000] * 8 + [100])
+    p = P.plan(f.parent, f.node_len, f.req_node, group=1, num_slots=4, align=100,
+               max_rows=64, share=True, table=LINEAR)
+    assert p["cost_l"] == 2025
+    assert [it["ub"] for it in p["items"]] == [2] * 8 + [1]
+    assert p["makespan"] == 2100
+    # three contexts of 1000 on 2 slots: whole -> 2000; the slack lets one be halved -> 1500
+    g = unshared_forest([1000] * 3)
+    q = P.plan(g.parent, g.node_len, g.req_node, group=1, num_slots=2, align=100,
+               max_rows=64, share=True, table=LINEAR)
+    assert q["cost_l"] == 1500 and [it["ub"] for it in q["items"]] == [2, 2, 2]
+    assert q["makespan"] == 1500 and sorted(it["b"] for it in q["items"]) == [1, 1, 2]
