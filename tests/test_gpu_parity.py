@@ -252,6 +252,35 @@ def test_limits_of_the_interface():
     assert np.abs(got - ref).max() <= TOL
 
 
+def test_decode_replayed_from_a_hip_graph():
+    """The decode call is two kernel launches on the caller's stream and nothing else, so it can be
+    captured; every replay (with eager work and new queries in between) must equal the eager result."""
+    C = _C()
+    w = make_small_config("cfg3", 16, 2, poison=True)
+    wd = w.to("cuda:0")
+    pa = C.PlannedAttention(w.forest, w.paged, w.head, device="cuda:0")
+    q = wd.q.clone()
+    out = torch.empty_like(q)
+    pa.decode(q, wd.k_pool, wd.v_pool, out)                         # warm-up outside the capture
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        pa.decode(q, wd.k_pool, wd.v_pool, out)
+    gen = torch.Generator(device="cuda:0").manual_seed(9)
+    for i in range(4):
+        q.copy_(torch.randn(q.shape, device="cuda:0", generator=gen).to(q.dtype))      # eager work in between
+        graph.replay()
+        torch.cuda.synchronize()
+        replayed = out.clone()
+        eager = pa.decode(q, wd.k_pool, wd.v_pool)
+        torch.cuda.synchronize()
+        assert torch.equal(replayed.view(torch.int16), eager.view(torch.int16)), f"replay {i}"
+    w.q[:] = q.cpu()
+    ref, _ = A.decode_attention_workload(w)
+    assert np.abs(out.double().cpu().numpy() - ref).max() <= TOL
+    pa.close()
+
+
 def test_tree_equals_flat_on_the_gpu():
     w = make_small_config("cfg3", 16, 2, poison=True)
     tree, _ = run_gpu(w, share=1)
