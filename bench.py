@@ -275,7 +275,8 @@ def main():
     args = parse_args()
     if args.gpus != 1:
         print(f"bench.py: this build runs on ONE GPU; --gpus {args.gpus} is not supported "
-              "(no collectives, no sharding: see DESIGN.md, 'More than one GPU')", file=sys.stderr)
+              "(no collectives, no sharding: the path would shard over KV heads, each head on its own GPU, "
+              "with no exchange inside attention)", file=sys.stderr)
         sys.exit(2)
     import torch
     if not torch.cuda.is_available():
