@@ -35,7 +35,7 @@ def parse_args():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
-    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", default="cfg2", help="headline configuration")
     ap.add_argument("--configs", default="cfg1,cfg2,cfg3,cfg4,cfg5a,cfg5b,cfg5c",
                     help="configurations reported in per_config ('' = headline only)")

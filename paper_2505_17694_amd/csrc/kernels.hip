@@ -79,6 +79,14 @@ __device__ __forceinline__ unsigned int pack2(float lo, float hi)
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
 __device__ __forceinline__ u32x4 ld16(const char *p) { return *reinterpret_cast<const u32x4 *>(p); }
+// The same load with the streaming hint (the `nt` bit).  K and V slices that one task alone reads are
+// fetched this way: bytes on their way through then do not displace each other, nor the slices that
+// several tasks read, in the caches.  Slices with several readers keep plain loads: their re-reads live
+// on cache hits.
+__device__ __forceinline__ u32x4 ld16_once(const char *p)
+{
+    return __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(p));
+}
 
 // Slice being processed: wave-uniform values only, so that addresses are SGPR base + 32-bit lane offset.
 struct SliceCtx {
@@ -90,6 +98,7 @@ struct SliceCtx {
     int32_t kv_len;
     int32_t page_shift;         // log2(page_size)
     int32_t page_mask;
+    int32_t read_once;          // no other task reads this slice
 };
 
 // Page ids are read through the scalar data path (s_load_dword, a read-only access): a vector load
@@ -116,7 +125,8 @@ struct BlockRegs {
 };
 
 // Issue the loads of block `tb`.  A tile that starts beyond the slice is redirected to tile 0 so that
-// no address leaves the slice's pages; its scores are masked later.
+// no address leaves the slice's pages; its scores are masked later.  ONCE: with the streaming hint.
+template <bool ONCE>
 __device__ __forceinline__ void load_block(const SliceCtx &c, int tb, uint32_t koff, uint32_t voff, BlockRegs &r)
 {
     int tok[2], pg[2];
@@ -132,9 +142,12 @@ __device__ __forceinline__ void load_block(const SliceCtx &c, int tb, uint32_t k
         const char *kt = c.k_head + off;
         const char *vt = c.v_head + off;
 #pragma unroll
-        for (int ks = 0; ks < 4; ++ks) r.k[j][ks] = ld16(kt + koff + ks * 64);
+        for (int ks = 0; ks < 4; ++ks) r.k[j][ks] = ONCE ? ld16_once(kt + koff + ks * 64) : ld16(kt + koff + ks * 64);
 #pragma unroll
-        for (int e = 0; e < 4; ++e) r.v[j * 4 + e] = ld16(vt + size_t(e) * c.token_bytes + voff);
+        for (int e = 0; e < 4; ++e) {
+            const char *p = vt + size_t(e) * c.token_bytes + voff;
+            r.v[j * 4 + e] = ONCE ? ld16_once(p) : ld16(p);
+        }
     }
 }
 
@@ -352,6 +365,7 @@ __device__ __forceinline__ SliceCtx make_ctx(const PacParams &P, const DevTask &
     c.kv_len = t.kv_len;
     c.page_shift = P.page_shift;
     c.page_mask = (1 << P.page_shift) - 1;
+    c.read_once = t.read_once;
     return c;
 }
 
@@ -362,7 +376,7 @@ __device__ __forceinline__ float weight(float a, float m) { return a == m ? 1.f 
 // ---- stream path: rows <= 16*NT (NT = 1 in use), a team of W waves splits the tokens ---------------
 // `wave` is the wave's index in its team.  A team of one wave (W = 1) uses no LDS and no barrier, so
 // several such waves may work on different tasks at the same time.
-template <int DT, int NT, int W>
+template <int DT, bool ONCE, int NT, int W>
 __device__ void run_stream(const PacParams &P, const DevTask &t, int head, char *lds_raw, int wave)
 {
     const int lane = threadIdx.x & 63;
@@ -406,15 +420,15 @@ __device__ void run_stream(const PacParams &P, const DevTask &t, int head, char 
     const int nblk = (t.kv_len + 31) >> 5;
     BlockRegs ra, rb;
     int tb = wave;
-    if (tb < nblk) load_block(c, tb, koff, voff, ra);
+    if (tb < nblk) load_block<ONCE>(c, tb, koff, voff, ra);
     while (tb < nblk) {
         int nb = tb + W;
-        if (nb < nblk) load_block(c, nb, koff, voff, rb);
+        if (nb < nblk) load_block<ONCE>(c, nb, koff, voff, rb);
         compute(tb, ra);
         tb = nb;
         if (tb >= nblk) break;
         nb = tb + W;
-        if (nb < nblk) load_block(c, nb, koff, voff, ra);
+        if (nb < nblk) load_block<ONCE>(c, nb, koff, voff, ra);
         compute(tb, rb);
         tb = nb;
     }
@@ -481,20 +495,34 @@ constexpr int vmcnt_imm(int n) { return (n & 15) | ((n >> 4) << 14) | 0x0F70; }
 // and the wave's 64 pieces land in 1 KB of consecutive LDS at lds_addr (the V piece 8 KB behind).  M0
 // holds the LDS address for the instruction and is put back afterwards.
 __device__ __forceinline__ void dma16_pair(uint32_t lds_addr, uint32_t voff_k, uint32_t voff_v, const char *gk,
-                                           const char *gv)
+                                           const char *gv, int read_once)
 {
     uint32_t m0_saved;
-    asm volatile("s_mov_b32 %0, m0\n\t"
-                 "s_mov_b32 m0, %1\n\t"
-                 "s_nop 0\n\t"
-                 "global_load_lds_dwordx4 %2, %4\n\t"
-                 "s_add_u32 m0, m0, 0x2000\n\t"
-                 "s_nop 0\n\t"
-                 "global_load_lds_dwordx4 %3, %5\n\t"
-                 "s_mov_b32 m0, %0\n"
-                 : "=&s"(m0_saved)
-                 : "s"(lds_addr), "v"(voff_k), "v"(voff_v), "s"(gk), "s"(gv)
-                 : "memory", "scc");
+    if (read_once) {
+        asm volatile("s_mov_b32 %0, m0\n\t"
+                     "s_mov_b32 m0, %1\n\t"
+                     "s_nop 0\n\t"
+                     "global_load_lds_dwordx4 %2, %4 nt\n\t"
+                     "s_add_u32 m0, m0, 0x2000\n\t"
+                     "s_nop 0\n\t"
+                     "global_load_lds_dwordx4 %3, %5 nt\n\t"
+                     "s_mov_b32 m0, %0\n"
+                     : "=&s"(m0_saved)
+                     : "s"(lds_addr), "v"(voff_k), "v"(voff_v), "s"(gk), "s"(gv)
+                     : "memory", "scc");
+    } else {
+        asm volatile("s_mov_b32 %0, m0\n\t"
+                     "s_mov_b32 m0, %1\n\t"
+                     "s_nop 0\n\t"
+                     "global_load_lds_dwordx4 %2, %4\n\t"
+                     "s_add_u32 m0, m0, 0x2000\n\t"
+                     "s_nop 0\n\t"
+                     "global_load_lds_dwordx4 %3, %5\n\t"
+                     "s_mov_b32 m0, %0\n"
+                     : "=&s"(m0_saved)
+                     : "s"(lds_addr), "v"(voff_k), "v"(voff_v), "s"(gk), "s"(gv)
+                     : "memory", "scc");
+    }
 }
 
 // ---- dense path with 32 query rows per wave ---------------------------------------------------------
@@ -582,7 +610,7 @@ __device__ __forceinline__ void dense32_wave(const PacParams &P, const DevTask &
     auto dma_block = [&](int bb, int pg) {                              // pg: page id from page_issue(bb)
         const int64_t off = page_offset(c, pg, first_token(bb) & c.page_mask);
         const uint32_t slot = lds_base + uint32_t(bb % kRing) * kBlockBytes + uint32_t(wave) * 1024;
-        dma16_pair(slot, voff_k, voff_v, c.k_head + off, c.v_head + off);
+        dma16_pair(slot, voff_k, voff_v, c.k_head + off, c.v_head + off, c.read_once);
     };
 
     // Operand reads.
@@ -875,12 +903,16 @@ __global__ void __launch_bounds__(WIDE ? kWideWaves * 64 : kNarrowWaves * 64, 2)
                 k = __builtin_amdgcn_readfirstlane(k);
                 if (k >= n) break;
                 const DevTask mine = P.tasks[P.slot_tasks[i + k]];
-                run_stream<DT, 1, 1>(P, mine, head, lds, 0);
+                if (mine.read_once) run_stream<DT, true, 1, 1>(P, mine, head, lds, 0);
+                else                run_stream<DT, false, 1, 1>(P, mine, head, lds, 0);
             }
             __syncthreads();                // the counter is done with before LDS is used again
             i += n;
         } else {
-            if (t.n_req * P.group <= 16) run_stream<DT, 1, W>(P, t, head, lds, wave);
+            if (t.n_req * P.group <= 16) {
+                if (t.read_once) run_stream<DT, true, 1, W>(P, t, head, lds, wave);
+                else             run_stream<DT, false, 1, W>(P, t, head, lds, wave);
+            }
             else if constexpr (WIDE != 0) run_dense32<DT>(P, t, head, lds);
             ++i;
         }

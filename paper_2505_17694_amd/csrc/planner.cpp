@@ -111,8 +111,11 @@ void build_device_image(PlanData &p)
     L.total = std::max<size_t>(off, 256);
     p.blob.assign(L.total, 0);
     DevTask *dt = reinterpret_cast<DevTask *>(p.blob.data() + L.tasks);
+    std::vector<int32_t> readers(size_t(p.num_nodes), 0);               // items (row tiles, or requests of a
+    for (const codec_item &it : p.items) ++readers[it.node];            // flat plan) that read each node
     for (size_t i = 0; i < p.tasks.size(); ++i) {
         const codec_task &t = p.tasks[i];
+        dt[i].read_once = readers[t.node] == 1;
         dt[i].page_off = p.node_page_off[t.node] + t.kv_begin / ps;
         dt[i].kv_len = t.kv_len;
         dt[i].q_off = t.q_off;
@@ -177,17 +180,17 @@ const CostTable &builtin_cost_table(bool wide)
     static const CostTable narrow_table = {
         {1, 16},
         {32, 128, 512, 2048, 8192, 32768},
-        {3060, 3299, 23398, 92892, 364391, 1467712,
-         5079, 4939, 27417, 100390, 373084, 1460054}};
+        {1440, 5839, 22657, 89908, 359916, 1437084,
+         3059, 7420, 24877, 101148, 373734, 1448403}};
     static const CostTable wide_table = {
         {1, 16, 32, 64, 128, 256},
         {32, 128, 512, 2048, 8192, 32768},
-        {1, 3620, 9959, 46515, 179042, 741701,
-         680, 4499, 10819, 49995, 183860, 745060,
-         3480, 7739, 17018, 50815, 187480, 737899,
-         6959, 8660, 18898, 56054, 195338, 746798,
-         8379, 11338, 22658, 63333, 245413, 850906,
-         12439, 15818, 32897, 85311, 310806, 1198527}};
+        {240, 2700, 10859, 45695, 180538, 721192,
+         621, 3820, 12039, 49194, 184597, 725231,
+         3240, 6960, 17237, 52573, 179478, 679017,
+         5200, 8419, 20217, 54893, 189277, 691436,
+         8459, 11159, 22217, 59512, 242370, 886711,
+         11678, 16278, 31816, 76451, 310641, 1201513}};
     return wide ? wide_table : narrow_table;
 }
 

@@ -32,7 +32,8 @@ struct DevTask {
     int32_t n_req;          // requests in the task
     int32_t part_row_base;  // first partial row
     int32_t solo_run;       // number of consecutive single-wave tasks in the slot's list from this one on
-    int32_t reserved[2];
+    int32_t read_once;      // 1 = no other task reads this KV slice (its node has a single row tile)
+    int32_t reserved;
 };
 
 // Byte offsets of the arrays inside the device metadata blob.
