@@ -88,6 +88,17 @@ __device__ __forceinline__ u32x4 ld16_once(const char *p)
     return __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(p));
 }
 
+// The lane index as a value the optimiser cannot trace back to the thread id.  Each task path derives
+// its lane constants (operand addresses, row and channel positions) from it, which keeps them inside
+// the path: hoisted out of the task loop they would stay live across all paths and cost the dense
+// path, which needs nearly every register, a dozen spills.
+__device__ __forceinline__ int opaque_lane()
+{
+    int lane = threadIdx.x & 63;
+    asm volatile("" : "+v"(lane));
+    return lane;
+}
+
 // Slice being processed: wave-uniform values only, so that addresses are SGPR base + 32-bit lane offset.
 struct SliceCtx {
     const char *k_head;         // K pool + KV-head offset
@@ -379,7 +390,7 @@ __device__ __forceinline__ float weight(float a, float m) { return a == m ? 1.f 
 template <int DT, bool ONCE, int NT, int W>
 __device__ void run_stream(const PacParams &P, const DevTask &t, int head, char *lds_raw, int wave)
 {
-    const int lane = threadIdx.x & 63;
+    const int lane = opaque_lane();
     const int l16 = lane & 15, grp = lane >> 4;
     const int rows = t.n_req * P.group;
 
@@ -488,6 +499,8 @@ __device__ void run_stream(const PacParams &P, const DevTask &t, int head, char 
 constexpr int kRing = 8;
 constexpr int kBlockBytes = 16384;
 constexpr int kRingBytes = kRing * kBlockBytes;
+constexpr int kSplitBlocksMaxRows = 128;     // dense tasks up to this many rows, and at least
+constexpr int kSplitBlocksMinLen = 1024;     // this many tokens: two waves per row group
 // s_waitcnt immediate that waits for the vector-memory counter only (gfx9 encoding: bits 3:0 and 15:14)
 constexpr int vmcnt_imm(int n) { return (n & 15) | ((n >> 4) << 14) | 0x0F70; }
 
@@ -552,18 +565,28 @@ __device__ __forceinline__ f32x16 mfma32(u32x4 a, u32x4 b, f32x16 c)
 __device__ __forceinline__ void pin(u32x4 &x) { asm volatile("" : "+v"(x)); }
 __device__ __forceinline__ void pin(float &x) { asm volatile("" : "+v"(x)); }
 
-// Roles of a wave in a dense task.  A wave with rows owns 32 of them and takes every block; in the two
-// live roles the halves of a step come in opposite orders, for the two waves of a SIMD.  Waves without
-// rows only help moving blocks.  All eight waves run the same barriers.
+// Roles of a wave in a dense task.  A wave with rows owns 32 of them; in the two live roles the halves
+// of a step come in opposite orders, for the two waves of a SIMD.  Waves without rows only help moving
+// blocks.  All eight waves run the same barriers.
+//
+// STRIDE = 1: a live wave takes every block (tasks of more than 128 rows: eight row groups).
+// STRIDE = 2: tasks of at most 128 rows have at most four row groups; waves w and w+4 (one SIMD) share
+// group w, the first takes the even blocks, the second the odd ones, and their two states are merged
+// through LDS when the slice is done.  An interval then covers two blocks.  Without the split a SIMD
+// would hold a single computing wave, whose matrix and vector work cannot overlap.
 enum { kHelper = 0, kMatrixFirst = 1, kVectorFirst = 2 };
 
 // One wave's share of a dense task: task rows row0 .. row0+31 (none for a helper).
-template <int DT, int ROLE>
+template <int DT, int ROLE, int STRIDE>
 __device__ __forceinline__ void dense32_wave(const PacParams &P, const DevTask &t, int head, char *lds,
                                              int wave, int row0, int rows)
 {
     constexpr bool LIVE = ROLE != kHelper;
-    const int lane = threadIdx.x & 63;
+    static_assert(STRIDE == 1 || STRIDE == 2, "a row group is shared by one or two waves");
+    // the wave's blocks are first, first + STRIDE, ...
+    const int first = (STRIDE == 2 && ROLE == kVectorFirst) ? 1 : 0;
+    auto blk = [&](int k) { return first + k * STRIDE; };
+    const int lane = opaque_lane();
     const int l32 = lane & 31, kg = lane >> 5;
     const int l16 = lane & 15, grp = lane >> 4;
 
@@ -734,13 +757,15 @@ __device__ __forceinline__ void dense32_wave(const PacParams &P, const DevTask &
         pin(l);
     };
 
-    // Common to all roles.  Blocks 0 .. 7 are requested up front; interval i (i = 0 .. nblk-2) starts
-    // with a barrier behind which block i+8 is requested into the slot block i has left, so block i is
-    // read from LDS before that barrier.  Block i+2 must have landed at the barrier of interval i: each
-    // wave issues 2 loads per block and loads complete in order, so it has once at most
-    // 2 * (blocks issued after it) loads are outstanding; near the end of the slice, where fewer than 5
-    // blocks follow, the wait is for everything.
+    // Common to all roles.  Blocks 0 .. 7 are requested up front; interval j (j = 0 .. nint-1) starts
+    // with a barrier behind which blocks S*j+8 .. S*j+8+S-1 (S = STRIDE) are requested into the slots
+    // that blocks S*j .. S*j+S-1 have left, so those are read from LDS before that barrier.  The LDS
+    // reads of interval j reach up to block S*j + 3*S - 1, which must have landed at its barrier: each
+    // wave issues 2 loads per block and loads complete in order, so a block has landed once at most
+    // 2 * (blocks issued after it) loads are outstanding; near the end of the slice, where fewer blocks
+    // follow, the wait is for everything.
     const int nblk = (t.kv_len + 31) >> 5;
+    const int nint = (nblk + STRIDE - 1) / STRIDE - 1;                  // the same for every wave
     {
         int pg[kRing];
 #pragma unroll
@@ -749,85 +774,129 @@ __device__ __forceinline__ void dense32_wave(const PacParams &P, const DevTask &
         for (int d = 0; d < kRing; ++d)
             if (d < nblk) dma_block(d, pg[d]);
     }
-    int pg_next = page_issue(kRing < nblk ? kRing : 0);                 // page of the block interval 0 requests
-    if (nblk >= kRing) __builtin_amdgcn_s_waitcnt(vmcnt_imm(2 * (kRing - 2)));     // blocks 0 and 1 have landed
+    int pg_next[STRIDE];                                                // pages of the blocks interval 0 requests
+#pragma unroll
+    for (int u = 0; u < STRIDE; ++u) pg_next[u] = page_issue(kRing + u);
+    if (nblk >= kRing) __builtin_amdgcn_s_waitcnt(vmcnt_imm(2 * (kRing - 2 * STRIDE)));    // blocks 0 .. 2S-1 have landed
     else               __builtin_amdgcn_s_waitcnt(0x0F70);
     __syncthreads();
 
-    // more: block i+8 exists
-    auto enter_interval = [&](int i, auto more) {                       // i + 1 < nblk
-        if constexpr (decltype(more)::value) __builtin_amdgcn_s_waitcnt(vmcnt_imm(2 * (kRing - 3)));  // kRing-3 blocks follow i+2
+    // more: blocks S*j+8 .. S*j+8+S-1 all exist
+    auto enter_interval = [&](int j, auto more) {                       // j < nint
+        if constexpr (decltype(more)::value) __builtin_amdgcn_s_waitcnt(vmcnt_imm(2 * (kRing - 3 * STRIDE)));
         else                                 __builtin_amdgcn_s_waitcnt(0x0F70);
-        __syncthreads();                    // block i+2 is complete; everyone is done with block i
+        __syncthreads();                    // blocks up to S*j+3S-1 are complete; everyone is done with block(s) S*j ..
         if constexpr (decltype(more)::value) {
-            dma_block(i + kRing, pg_next);
-            pg_next = page_issue(i + kRing + 1);
+#pragma unroll
+            for (int u = 0; u < STRIDE; ++u) dma_block(STRIDE * j + kRing + u, pg_next[u]);
+#pragma unroll
+            for (int u = 0; u < STRIDE; ++u) pg_next[u] = page_issue(STRIDE * (j + 1) + kRing + u);
+        } else if constexpr (STRIDE == 2) {
+            if (2 * j + kRing < nblk) dma_block(2 * j + kRing, pg_next[0]);         // an odd block left over
         }
     };
     using yes = std::true_type;
     using no = std::false_type;
     auto short_block = [&](int b) { return c.kv_len - b * 32; };        // valid tokens if below 32
+    auto more_follow = [&](int j) { return STRIDE * j + kRing + STRIDE - 1 < nblk; };
 
     if constexpr (LIVE) {
-        // Per block a vector half V(b) (scores of block b -> probabilities) and a matrix half M(b)
-        // (accumulation of block b, alternating with the scores of block b+1), in the order V(0) M(0)
-        // V(1) M(1) ...; right after M(b) has read its operands the operands of M(b+1) (K of block b+2, V
-        // of block b+1) are requested from LDS, to arrive during V(b+1).  A vector-first wave places the
-        // barrier of interval b before V(b), a matrix-first wave before M(b): the two waves of a SIMD run
-        // in opposite phases, one's matrix work beside the other's vector work.
+        // The wave's k-th block is b_k = blk(k), nmine of them.  Per block a vector half V(b_k) (scores
+        // of the block -> probabilities) and a matrix half M(b_k) (accumulation of b_k, alternating with
+        // the scores of b_k+1), in the order V(b_0) M(b_0) V(b_1) M(b_1) ...; right after M(b_k) has read
+        // its operands the operands of M(b_k+1) (K of block b_k+2, V of block b_k+1) are requested from
+        // LDS, to arrive during V(b_k+1).  A vector-first wave places the barrier of interval k before
+        // V(b_k), a matrix-first wave before M(b_k): the two waves of a SIMD run in opposite phases,
+        // one's matrix work beside the other's vector work.
         constexpr bool VFIRST = ROLE == kVectorFirst;
+        const int nmine = nblk > first ? (nblk - first + STRIDE - 1) / STRIDE : 0;
         auto vector_half_of = [&](int b) {
             if (short_block(b) < 32) mask_scores32(s, short_block(b));
             reference();
             probabilities32(0);
             probabilities32(1);
         };
-        auto matrix_half_and_loads = [&](int b) {                       // M(b), b + 1 < nblk
+        auto matrix_half_and_loads = [&](int k) {                       // M(b_k), k + 1 < nmine
             matrix_half();
             __builtin_amdgcn_sched_barrier(0);
-            load_keys(b + 2);
-            load_values(b + 1);
+            load_keys(blk(k + 2));
+            load_values(blk(k + 1));
             __builtin_amdgcn_sched_barrier(0);
         };
-        auto interval = [&](int b, auto more) {
-            enter_interval(b, more);
-            if constexpr (VFIRST) {
-                vector_half_of(b);
-                __builtin_amdgcn_sched_barrier(0);
-                matrix_half_and_loads(b);
-            } else {
-                matrix_half_and_loads(b);
-                vector_half_of(b + 1);
-                __builtin_amdgcn_sched_barrier(0);
+        auto interval = [&](int k, auto more) {
+            enter_interval(k, more);
+            if (STRIDE == 1 || k + 1 < nmine) {                         // else: the other wave's last block only
+                if constexpr (VFIRST) {
+                    vector_half_of(blk(k));
+                    __builtin_amdgcn_sched_barrier(0);
+                    matrix_half_and_loads(k);
+                } else {
+                    matrix_half_and_loads(k);
+                    vector_half_of(blk(k + 1));
+                    __builtin_amdgcn_sched_barrier(0);
+                }
             }
         };
-        load_keys(0);
-        scores32();
-        __builtin_amdgcn_sched_barrier(0);
-        load_keys(1);
-        load_values(0);
-        __builtin_amdgcn_sched_barrier(0);
-        if constexpr (!VFIRST) {
-            vector_half_of(0);
+        if (STRIDE == 1 || nmine > 0) {
+            load_keys(blk(0));
+            scores32();
             __builtin_amdgcn_sched_barrier(0);
+            load_keys(blk(1));
+            load_values(blk(0));
+            __builtin_amdgcn_sched_barrier(0);
+            if constexpr (!VFIRST) {
+                vector_half_of(blk(0));
+                __builtin_amdgcn_sched_barrier(0);
+            }
         }
-        int b = 0;
+        int k = 0;
 #pragma unroll 1
-        for (; b + kRing < nblk; ++b) interval(b, yes{});
+        for (; k < nint && more_follow(k); ++k) interval(k, yes{});
 #pragma unroll 1
-        for (; b + 1 < nblk; ++b) interval(b, no{});
-        if constexpr (VFIRST) vector_half_of(nblk - 1);
-        if (short_block(nblk - 1) < 32) mask_values(short_block(nblk - 1));
-        accumulate32();
+        for (; k < nint; ++k) interval(k, no{});
+        if (STRIDE == 1 || nmine > 0) {
+            const int last = blk(nmine - 1);
+            if constexpr (VFIRST) vector_half_of(last);
+            if (short_block(last) < 32) mask_values(short_block(last));
+            accumulate32();
+        }
     } else {
-        int b = 0;
+        int k = 0;
 #pragma unroll 1
-        for (; b + kRing < nblk; ++b) enter_interval(b, yes{});
+        for (; k < nint && more_follow(k); ++k) enter_interval(k, yes{});
 #pragma unroll 1
-        for (; b + 1 < nblk; ++b) enter_interval(b, no{});
+        for (; k < nint; ++k) enter_interval(k, no{});
     }
 
-    if constexpr (LIVE) {
+    __syncthreads();                        // every block has been read: the ring is free
+    if constexpr (STRIDE == 2) {
+        // The odd-block wave hands its state to the even-block wave of its row group: 64 accumulator
+        // registers, reference and sum share per lane, register-major so that a wave's store or load
+        // covers consecutive words.
+        float *x = reinterpret_cast<float *>(lds) + (wave & 3) * (66 * 64) + lane;
+        if constexpr (ROLE == kVectorFirst) {
+#pragma unroll
+            for (int ct = 0; ct < 4; ++ct)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) x[(ct * 16 + r) * 64] = o[ct][r];
+            x[64 * 64] = m;
+            x[65 * 64] = l;
+        }
+        __syncthreads();
+        if constexpr (ROLE == kMatrixFirst) {
+            const float m2 = x[64 * 64], l2 = x[65 * 64];
+            const float m_new = fmaxf(m, m2);
+            const float a1 = weight(m, m_new), a2 = weight(m2, m_new);
+            l = l * a1 + l2 * a2;
+#pragma unroll
+            for (int ct = 0; ct < 4; ++ct)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) o[ct][r] = o[ct][r] * a1 + x[(ct * 16 + r) * 64] * a2;
+            m = m_new;
+        }
+    }
+
+    if constexpr (ROLE == kMatrixFirst || (STRIDE == 1 && LIVE)) {
         l += __shfl_xor(l, 32);
         const int row = row0 + l32;
         if (row < rows) {
@@ -837,8 +906,8 @@ __device__ __forceinline__ void dense32_wave(const PacParams &P, const DevTask &
             for (int ct = 0; ct < 4; ++ct)
 #pragma unroll
                 for (int q = 0; q < 4; ++q) {
-                    const f32x4 x = {o[ct][4 * q], o[ct][4 * q + 1], o[ct][4 * q + 2], o[ct][4 * q + 3]};
-                    *reinterpret_cast<f32x4 *>(po + ct * 32 + q * 8) = x;
+                    const f32x4 x4 = {o[ct][4 * q], o[ct][4 * q + 1], o[ct][4 * q + 2], o[ct][4 * q + 3]};
+                    *reinterpret_cast<f32x4 *>(po + ct * 32 + q * 8) = x4;
                 }
             if (kg == 0) {
                 float2 ml = {m, l};
@@ -846,20 +915,29 @@ __device__ __forceinline__ void dense32_wave(const PacParams &P, const DevTask &
             }
         }
     }
-    __syncthreads();                        // every block has been read: the ring is free for the next task
+    if constexpr (STRIDE == 2) __syncthreads();     // the hand-over area is free for the next task
 }
 
-// Dense task: wave w owns rows 32w .. 32w+31; waves 4 .. 7 share their SIMDs with waves 0 .. 3 and run
-// in the opposite phase.
+// Dense task.  More than 128 rows: wave w owns rows 32w .. 32w+31; waves 4 .. 7 share their SIMDs with
+// waves 0 .. 3 and run in the opposite phase.  Up to 128 rows: waves w and w+4 share rows 32w .. 32w+31
+// and take alternate blocks, again in opposite phases; short slices, for which the hand-over at the end
+// costs more than the overlap gains (about 1 us per task), keep one wave per row group.
 template <int DT>
 __device__ void run_dense32(const PacParams &P, const DevTask &t, int head, char *lds)
 {
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int rows = t.n_req * P.group;
-    const int row0 = wave * 32;
-    if (row0 >= rows)  dense32_wave<DT, kHelper>(P, t, head, lds, wave, 0, 0);
-    else if (wave & 4) dense32_wave<DT, kVectorFirst>(P, t, head, lds, wave, row0, rows);
-    else               dense32_wave<DT, kMatrixFirst>(P, t, head, lds, wave, row0, rows);
+    if (rows > kSplitBlocksMaxRows || t.kv_len < kSplitBlocksMinLen) {
+        const int row0 = wave * 32;
+        if (row0 >= rows)  dense32_wave<DT, kHelper, 1>(P, t, head, lds, wave, 0, 0);
+        else if (wave & 4) dense32_wave<DT, kVectorFirst, 1>(P, t, head, lds, wave, row0, rows);
+        else               dense32_wave<DT, kMatrixFirst, 1>(P, t, head, lds, wave, row0, rows);
+    } else {
+        const int row0 = (wave & 3) * 32;
+        if (row0 >= rows)  dense32_wave<DT, kHelper, 2>(P, t, head, lds, wave, 0, 0);
+        else if (wave & 4) dense32_wave<DT, kVectorFirst, 2>(P, t, head, lds, wave, row0, rows);
+        else               dense32_wave<DT, kMatrixFirst, 2>(P, t, head, lds, wave, row0, rows);
+    }
 }
 
 // WIDE: kRingBytes of dynamic LDS.  The dense path XORs the channel tile into operand addresses, so

@@ -180,17 +180,17 @@ const CostTable &builtin_cost_table(bool wide)
     static const CostTable narrow_table = {
         {1, 16},
         {32, 128, 512, 2048, 8192, 32768},
-        {1440, 5839, 22657, 89908, 359916, 1437084,
-         3059, 7420, 24877, 101148, 373734, 1448403}};
+        {1620, 5799, 22878, 90150, 362177, 1437170,
+         3140, 7659, 25137, 101308, 373456, 1447170}};
     static const CostTable wide_table = {
         {1, 16, 32, 64, 128, 256},
         {32, 128, 512, 2048, 8192, 32768},
-        {240, 2700, 10859, 45695, 180538, 721192,
-         621, 3820, 12039, 49194, 184597, 725231,
-         3240, 6960, 17237, 52573, 179478, 679017,
-         5200, 8419, 20217, 54893, 189277, 691436,
-         8459, 11159, 22217, 59512, 242370, 886711,
-         11678, 16278, 31816, 76451, 310641, 1201513}};
+        {20, 2499, 12659, 47075, 182699, 720715,
+         620, 3759, 13038, 50354, 186778, 726515,
+         3420, 7519, 17618, 49595, 178919, 677699,
+         5320, 8759, 18617, 52874, 184239, 693738,
+         8639, 11259, 22898, 57713, 177239, 775789,
+         10539, 16818, 30376, 80871, 326602, 1221677}};
     return wide ? wide_table : narrow_table;
 }
 

@@ -90,6 +90,21 @@ def test_row_tiles(max_rows):
     assert max(t["n_req"] * 4 for t in view["tasks"]) <= max_rows
 
 
+@pytest.mark.parametrize("requests", [5, 16, 17, 32, 33, 64])
+def test_dense_tasks_of_every_block_count(requests):
+    """One undivided task per root, 20 .. 256 rows: 1 .. 70 blocks of 32 tokens, odd and even counts,
+    counts around the depth of the block ring, ragged last blocks (the two waves of a row group take
+    alternate blocks in tasks of at most 128 rows, so the odd-block wave may have one block less, or none)."""
+    lens = [1, 33, 65, 96, 200, 256, 257, 289, 300, 330, 353, 511, 545, 577, 2210]
+    f = two_level_forest(lens[0], [43] * requests)
+    for n in lens[1:]:
+        f = concat_forests(f, two_level_forest(n, [40 + n % 4] * requests))      # private suffixes: stream path
+    w = make_workload(f"dense{requests}", f, HeadConfig(8, 2, 128, DTYPE_BF16), seed=31 + requests, poison=True)
+    _, view = check(w, num_slots=3, split_align=4096)
+    roots = [t for t in view["tasks"] if t["n_req"] == requests]
+    assert sorted(t["kv_len"] for t in roots) == lens
+
+
 @pytest.mark.parametrize("slots,align", [(1, 32), (7, 32), (64, 32), (64, 64), (256, 32)])
 def test_division_granularity(slots, align):
     """From everything on one slot to slices of a single block: merged result must not change."""

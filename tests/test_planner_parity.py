@@ -207,24 +207,36 @@ BEST_CASES = {
 }
 
 
+# A table under which tasks of more than 16 rows are dear (as on a device without a fast wide kernel):
+# cost = len * rows for up to 16 rows, forty times that above.  It makes the candidates with small row
+# tiles, or the flat plan, win where the built-in tables pick the 256-row plan.
+DEAR_WIDE = {"row_grid": [1, 16, 17, 256], "len_grid": [32, 65536],
+             "cost": [[32 * 1, 65536 * 1], [32 * 16, 65536 * 16], [32 * 17 * 40, 65536 * 17 * 40],
+                      [32 * 256 * 40, 65536 * 256 * 40]]}
+
+
+@pytest.mark.parametrize("table", ["builtin", "dear_wide"])
 @pytest.mark.parametrize("name", sorted(BEST_CASES))
-def test_best_of_three_plans_matches_oracle(name):
+def test_best_of_three_plans_matches_oracle(name, table):
     make, head = BEST_CASES[name]
     f = make()
     group = head.num_q_heads // head.num_kv_heads
     paged = build_paged_kv(f, head, seed=1)
+    custom = None if table == "builtin" else DEAR_WIDE
     st, plan = C.codec_plan_create(f.parent, f.node_len, f.req_node, paged.node_page_off, paged.page_ids,
                                    head.num_q_heads, head.num_kv_heads, head.head_dim, head.dtype,
-                                   head.page_size, head.scale, share=2)
+                                   head.page_size, head.scale, share=2,
+                                   cost_table=_tuple(custom) if custom else None)
     assert st == C.CODEC_OK
     st, view = C.codec_plan_export(plan)
     C.codec_plan_destroy(plan)
-    tables = {"narrow": _default_table(0), "wide": _default_table(1)}
+    tables = ({"narrow": _default_table(0), "wide": _default_table(1)} if custom is None
+              else {"narrow": custom, "wide": custom})
     ref = P.plan_best(f.parent, f.node_len, f.req_node, group, 256, 256, tables,
                       lambda wide: (256 if wide else 512) // head.num_kv_heads)
     assert (view["share"], view["max_rows"]) == (int(ref["share"]), ref["max_rows"])
     _compare(view, ref)
-    if name == "docqa":
+    if name == "docqa" and custom is None:
         assert (view["share"], view["max_rows"]) == (1, 256)
-    if name == "quarter":
+    if name in ("docqa", "quarter", "random") and custom is not None:
         assert (view["share"], view["max_rows"]) != (1, 256)
