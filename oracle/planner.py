@@ -19,10 +19,12 @@ quotient; every other node keeps the printed bound.
 The paper gives the solver in prose; where it is silent this file fixes:
 integer costs; round-half-up bilinear interpolation, clamped below the grid
 and linearly extrapolated above it; slice boundaries on multiples of
-``align`` tokens with equal-length slices except the last; one pass of the
-grid search in order of decreasing node cost with ties to the smaller slice
-count; ties in the schedule to the lower slot id.  Python integers are
-unbounded, so no intermediate can overflow.
+``align`` tokens with equal-length slices except the last; the grid search as
+one pass node by node, in order of decreasing node cost with ties to the
+smaller slice count, followed by nine points on the diagonal of the grid (every
+node at its Eq. 5 quotient for a common target cost_l * (1 + k/8), k = 0 .. 8),
+the best point seen being kept; ties in the schedule to the lower slot id.
+Python integers are unbounded, so no intermediate can overflow.
 """
 from __future__ import annotations
 
@@ -202,6 +204,22 @@ def plan(parent, node_len, req_node, group: int, num_slots: int, align: int,
             if best_ms is None or ms < best_ms:
                 best_b, best_ms = count, ms
         it["b"] = best_b
+
+    if fixed_slices == 0 and items:
+        # the pass above moves one node at a time; the search also looks along the diagonal of the grid:
+        # every node at its Eq. 5 quotient for one common target cost_l * (1 + k/8), k = 0 .. 8, capped by
+        # its bound; the best point seen is kept (ties: the earlier one)
+        best_ms = lpt(subtasks(), m)[0]
+        best_bs = [it["b"] for it in items]
+        for k in range(9):
+            target = max(1, cost_l + cost_l * k // 8)
+            for it in items:
+                it["b"] = slices(it["len"], min(it["ub"], b_of(it, target)), align)[0]
+            ms = lpt(subtasks(), m)[0]
+            if ms < best_ms:
+                best_ms, best_bs = ms, [it["b"] for it in items]
+        for it, b in zip(items, best_bs):
+            it["b"] = b
 
     sub = subtasks()
     makespan, slot_of, lists = lpt(sub, m) if sub else (0, [], [[] for _ in range(m)])

@@ -496,7 +496,7 @@ __device__ void run_stream(const PacParams &P, const DevTask &t, int head, char 
 // The compiler does not see these loads (inline asm), so the waits are explicit: loads complete in
 // issue order, block b is in LDS once at most 2 * (blocks issued after b) of the wave's loads are
 // outstanding, and the barrier that follows publishes all eight waves' parts.
-constexpr int kRing = 8;
+constexpr int kRing = 10;                    // slots allocated; a path may cycle through fewer
 constexpr int kBlockBytes = 16384;
 constexpr int kRingBytes = kRing * kBlockBytes;
 constexpr int kSplitBlocksMaxRows = 128;     // dense tasks up to this many rows, and at least
@@ -583,6 +583,8 @@ __device__ __forceinline__ void dense32_wave(const PacParams &P, const DevTask &
 {
     constexpr bool LIVE = ROLE != kHelper;
     static_assert(STRIDE == 1 || STRIDE == 2, "a row group is shared by one or two waves");
+    // slots in use: an interval of two blocks wants a deeper ring to keep as many bytes in flight
+    constexpr int RING = STRIDE == 2 ? kRing : 8;
     // the wave's blocks are first, first + STRIDE, ...
     const int first = (STRIDE == 2 && ROLE == kVectorFirst) ? 1 : 0;
     auto blk = [&](int k) { return first + k * STRIDE; };
@@ -632,7 +634,7 @@ __device__ __forceinline__ void dense32_wave(const PacParams &P, const DevTask &
     auto page_issue = [&](int bb) { return uniform_load(c.pages, first_token(bb) >> c.page_shift); };
     auto dma_block = [&](int bb, int pg) {                              // pg: page id from page_issue(bb)
         const int64_t off = page_offset(c, pg, first_token(bb) & c.page_mask);
-        const uint32_t slot = lds_base + uint32_t(bb % kRing) * kBlockBytes + uint32_t(wave) * 1024;
+        const uint32_t slot = lds_base + uint32_t(bb % RING) * kBlockBytes + uint32_t(wave) * 1024;
         dma16_pair(slot, voff_k, voff_v, c.k_head + off, c.v_head + off, c.read_once);
     };
 
@@ -652,7 +654,7 @@ __device__ __forceinline__ void dense32_wave(const PacParams &P, const DevTask &
     u32x4 kr[8];            // K operands of one block, by k-step
     u32x4 vr[4][2];         // V operands of one block, by channel tile and k-step
     auto load_keys = [&](int bb) {
-        const uint32_t base = lds_base + uint32_t(bb % kRing) * kBlockBytes + ka_lane;
+        const uint32_t base = lds_base + uint32_t(bb % RING) * kBlockBytes + ka_lane;
 #pragma unroll
         for (int ks = 0; ks < 8; ++ks)
             kr[ks] = *reinterpret_cast<const u32x4 __attribute__((address_space(3))) *>(uintptr_t(base ^ uint32_t(ks << 5)));
@@ -660,7 +662,7 @@ __device__ __forceinline__ void dense32_wave(const PacParams &P, const DevTask &
     typedef __attribute__((ext_vector_type(4))) short s16x4;
     typedef s16x4 __attribute__((address_space(3))) *lds_s16x4_ptr;
     auto load_values = [&](int bb) {
-        const uint32_t base = lds_base + uint32_t(bb % kRing) * kBlockBytes + va_lane;
+        const uint32_t base = lds_base + uint32_t(bb % RING) * kBlockBytes + va_lane;
 #pragma unroll
         for (int ct = 0; ct < 4; ++ct)
 #pragma unroll
@@ -767,38 +769,38 @@ __device__ __forceinline__ void dense32_wave(const PacParams &P, const DevTask &
     const int nblk = (t.kv_len + 31) >> 5;
     const int nint = (nblk + STRIDE - 1) / STRIDE - 1;                  // the same for every wave
     {
-        int pg[kRing];
+        int pg[RING];
 #pragma unroll
-        for (int d = 0; d < kRing; ++d) pg[d] = page_issue(d < nblk ? d : 0);
+        for (int d = 0; d < RING; ++d) pg[d] = page_issue(d < nblk ? d : 0);
 #pragma unroll
-        for (int d = 0; d < kRing; ++d)
+        for (int d = 0; d < RING; ++d)
             if (d < nblk) dma_block(d, pg[d]);
     }
     int pg_next[STRIDE];                                                // pages of the blocks interval 0 requests
 #pragma unroll
-    for (int u = 0; u < STRIDE; ++u) pg_next[u] = page_issue(kRing + u);
-    if (nblk >= kRing) __builtin_amdgcn_s_waitcnt(vmcnt_imm(2 * (kRing - 2 * STRIDE)));    // blocks 0 .. 2S-1 have landed
+    for (int u = 0; u < STRIDE; ++u) pg_next[u] = page_issue(RING + u);
+    if (nblk >= RING) __builtin_amdgcn_s_waitcnt(vmcnt_imm(2 * (RING - 2 * STRIDE)));    // blocks 0 .. 2S-1 have landed
     else               __builtin_amdgcn_s_waitcnt(0x0F70);
     __syncthreads();
 
     // more: blocks S*j+8 .. S*j+8+S-1 all exist
     auto enter_interval = [&](int j, auto more) {                       // j < nint
-        if constexpr (decltype(more)::value) __builtin_amdgcn_s_waitcnt(vmcnt_imm(2 * (kRing - 3 * STRIDE)));
+        if constexpr (decltype(more)::value) __builtin_amdgcn_s_waitcnt(vmcnt_imm(2 * (RING - 3 * STRIDE)));
         else                                 __builtin_amdgcn_s_waitcnt(0x0F70);
         __syncthreads();                    // blocks up to S*j+3S-1 are complete; everyone is done with block(s) S*j ..
         if constexpr (decltype(more)::value) {
 #pragma unroll
-            for (int u = 0; u < STRIDE; ++u) dma_block(STRIDE * j + kRing + u, pg_next[u]);
+            for (int u = 0; u < STRIDE; ++u) dma_block(STRIDE * j + RING + u, pg_next[u]);
 #pragma unroll
-            for (int u = 0; u < STRIDE; ++u) pg_next[u] = page_issue(STRIDE * (j + 1) + kRing + u);
+            for (int u = 0; u < STRIDE; ++u) pg_next[u] = page_issue(STRIDE * (j + 1) + RING + u);
         } else if constexpr (STRIDE == 2) {
-            if (2 * j + kRing < nblk) dma_block(2 * j + kRing, pg_next[0]);         // an odd block left over
+            if (2 * j + RING < nblk) dma_block(2 * j + RING, pg_next[0]);         // an odd block left over
         }
     };
     using yes = std::true_type;
     using no = std::false_type;
     auto short_block = [&](int b) { return c.kv_len - b * 32; };        // valid tokens if below 32
-    auto more_follow = [&](int j) { return STRIDE * j + kRing + STRIDE - 1 < nblk; };
+    auto more_follow = [&](int j) { return STRIDE * j + RING + STRIDE - 1 < nblk; };
 
     if constexpr (LIVE) {
         // The wave's k-th block is b_k = blk(k), nmine of them.  Per block a vector half V(b_k) (scores

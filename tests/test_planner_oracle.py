@@ -367,3 +367,24 @@ def test_slice_bound_slack_hand_worked():
                max_rows=64, share=True, table=LINEAR)
     assert q["cost_l"] == 1500 and [it["ub"] for it in q["items"]] == [2, 2, 2]
     assert q["makespan"] == 1500 and sorted(it["b"] for it in q["items"]) == [1, 1, 2]
+
+
+def test_diagonal_of_the_grid_hand_worked():
+    """Two 1200-token contexts on 8 slots, cost = tokens, slices on multiples of 20 tokens.
+
+    Total 2400 -> cost_l = 300; quotient 4, bound 5 with the slack.  Node by node from (5, 5): with the
+    other node in 5 slices of 240, the first node in 3 slices of 400 gives 8 tasks on 8 slots, makespan
+    400; 4 slices (4 x 300 + 5 x 240: nine tasks, one slot holds 240 + 240) or 5 slices give 480, so 3 is
+    kept; then the second node: 3, 4 or 5 slices all leave the makespan at 400, the first of them, 3, is
+    kept.  That point, (3, 3), is one no single move improves.  The diagonal point of target cost_l,
+    (4, 4), packs 8 slices of 300 onto the 8 slots: makespan 300, which is the lower bound.
+    """
+    f = unshared_forest([1200, 1200])
+    p = P.plan(f.parent, f.node_len, f.req_node, group=1, num_slots=8, align=20,
+               max_rows=64, share=True, table=LINEAR)
+    assert p["cost_l"] == 300
+    assert [it["ub"] for it in p["items"]] == [5, 5]
+    assert [it["b"] for it in p["items"]] == [4, 4]
+    assert p["makespan"] == 300 and len(p["tasks"]) == 8
+    assert sorted(t["kv_len"] for t in p["tasks"]) == [300] * 8
+
