@@ -26,9 +26,13 @@
 //    LDS at the end.  Runs of short tasks are handed out one wave each instead.
 //  * "dense" (tasks of 17..256 rows, wide variant): 32 x 32 x 16 tiles; eight waves
 //    split the rows (32 each) and walk the slice together; blocks are copied HBM ->
-//    LDS asynchronously into a ring of eight 16 KB slots (six blocks in flight, one
-//    barrier per block) and read by all waves, V through transposing LDS reads
-//    (ds_read_b64_tr_b16).
+//    LDS asynchronously into a ring of 16 KB slots (six or eight blocks in flight)
+//    and read by all waves, V through transposing LDS reads (ds_read_b64_tr_b16).
+//    Long slices under at most 128 rows put two waves on each row group, on
+//    alternate blocks.
+//
+// K and V slices that a single task reads, in plans that read little twice, are
+// loaded with the streaming (nontemporal) hint; the plan marks those tasks.
 #include <hip/hip_runtime.h>
 
 #include <type_traits>
@@ -488,9 +492,9 @@ __device__ void run_stream(const PacParams &P, const DevTask &t, int head, char 
 //
 // Blocks travel HBM -> LDS without passing through registers (global_load_lds_dwordx4: every lane
 // moves 16 bytes, a wave fills 1 KB of consecutive LDS).  A ring of kRing block slots (16 KB each:
-// 32 K rows then 32 V rows of 256 B) keeps up to kRing-2 blocks in flight per workgroup.  Rows are
-// stored unpadded; the 16-byte column index is XORed with a function of the row so that the operand
-// reads spread over all banks.  The swizzle is applied on the global side: the lane that fills LDS
+// 32 K rows then 32 V rows of 256 B) keeps six (eight with two-block intervals) blocks in flight per
+// workgroup.  Rows are stored unpadded; the 16-byte column index is XORed with a function of the row so
+// that the operand reads spread over all banks.  The swizzle is applied on the global side: the lane that fills LDS
 // column c of a row fetches column c ^ f(row).
 //
 // The compiler does not see these loads (inline asm), so the waits are explicit: loads complete in
