@@ -657,29 +657,34 @@ __device__ __forceinline__ void dense32_wave(const PacParams &P, const DevTask &
         uint32_t(8192 + vrow * 256 + ((((2 * vch + (vq >> 1)) ^ (2 * vrow)) & 15) << 4) + 8 * (vq & 1));
     u32x4 kr[8];            // K operands of one block, by k-step
     u32x4 vr[4][2];         // V operands of one block, by channel tile and k-step
-    auto load_keys = [&](int bb) {
-        const uint32_t base = lds_base + uint32_t(bb % RING) * kBlockBytes + ka_lane;
-#pragma unroll
-        for (int ks = 0; ks < 8; ++ks)
-            kr[ks] = *reinterpret_cast<const u32x4 __attribute__((address_space(3))) *>(uintptr_t(base ^ uint32_t(ks << 5)));
+    auto key_base = [&](int bb) { return lds_base + uint32_t(bb % RING) * kBlockBytes + ka_lane; };
+    auto value_base = [&](int bb) { return lds_base + uint32_t(bb % RING) * kBlockBytes + va_lane; };
+    auto load_key = [&](uint32_t base, int ks) {                        // K operand of k-step ks
+        kr[ks] = *reinterpret_cast<const u32x4 __attribute__((address_space(3))) *>(uintptr_t(base ^ uint32_t(ks << 5)));
     };
     typedef __attribute__((ext_vector_type(4))) short s16x4;
     typedef s16x4 __attribute__((address_space(3))) *lds_s16x4_ptr;
+    auto load_value = [&](uint32_t base, int ct, int tt) {              // V operand of channel tile ct, k-step tt
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            const uint32_t addr = (base ^ uint32_t(ct << 6)) + tt * 4096 + h * 2048;
+            const s16x4 x = __builtin_amdgcn_ds_read_tr16_b64_v4i16(reinterpret_cast<lds_s16x4_ptr>(uintptr_t(addr)));
+            const uint2 w = __builtin_bit_cast(uint2, x);
+            vr[ct][tt][2 * h] = w.x;
+            vr[ct][tt][2 * h + 1] = w.y;
+        }
+    };
+    auto load_keys = [&](int bb) {
+        const uint32_t base = key_base(bb);
+#pragma unroll
+        for (int ks = 0; ks < 8; ++ks) load_key(base, ks);
+    };
     auto load_values = [&](int bb) {
-        const uint32_t base = lds_base + uint32_t(bb % RING) * kBlockBytes + va_lane;
+        const uint32_t base = value_base(bb);
 #pragma unroll
         for (int ct = 0; ct < 4; ++ct)
 #pragma unroll
-            for (int tt = 0; tt < 2; ++tt)
-#pragma unroll
-                for (int h = 0; h < 2; ++h) {
-                    const uint32_t addr = (base ^ uint32_t(ct << 6)) + tt * 4096 + h * 2048;
-                    const s16x4 x =
-                        __builtin_amdgcn_ds_read_tr16_b64_v4i16(reinterpret_cast<lds_s16x4_ptr>(uintptr_t(addr)));
-                    const uint2 w = __builtin_bit_cast(uint2, x);
-                    vr[ct][tt][2 * h] = w.x;
-                    vr[ct][tt][2 * h + 1] = w.y;
-                }
+            for (int tt = 0; tt < 2; ++tt) load_value(base, ct, tt);
     };
     // tokens past `valid` count as zero in V (the slot may hold anything there, NaN patterns included)
     // and as -inf in the scores
@@ -717,8 +722,12 @@ __device__ __forceinline__ void dense32_wave(const PacParams &P, const DevTask &
         for (int i = 0; i < 8; ++i) o[i & 3] = mfma32<DT>(vr[i & 3][i >> 2], p[i >> 2], o[i & 3]);
     };
     // The matrix half of a FULL step: O^T += V^T P^T of the block in vr and the scores of the block in
-    // kr; the two alternate so that no instruction waits for the one before it.
-    auto matrix_half = [&]() {
+    // kr; the two alternate so that no instruction waits for the one before it.  With one wave per row
+    // group (compute-bound tasks) each pair is followed by the LDS reads that refill the operand
+    // registers it has just consumed (K of block kb, V of block vb): the reads are issued while the
+    // matrix unit works on the pair.
+    auto matrix_half = [&](int kb, int vb) {
+        const uint32_t kbase = key_base(kb), vbase = value_base(vb);
         f32x16 acc;
 #pragma unroll
         for (int r = 0; r < 16; ++r) acc[r] = 0.f;
@@ -726,6 +735,15 @@ __device__ __forceinline__ void dense32_wave(const PacParams &P, const DevTask &
         for (int i = 0; i < 8; ++i) {
             o[i & 3] = mfma32<DT>(vr[i & 3][i >> 2], p[i >> 2], o[i & 3]);
             acc = mfma32<DT>(kr[i], qb[i], acc);
+            if constexpr (STRIDE == 1) {
+                load_value(vbase, i & 3, i >> 2);
+                load_key(kbase, i);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        if constexpr (STRIDE == 2) {        // memory-bound tasks: measured faster with the reads in one go
+            load_keys(kb);
+            load_values(vb);
             __builtin_amdgcn_sched_barrier(0);
         }
         s = acc;
@@ -823,10 +841,7 @@ __device__ __forceinline__ void dense32_wave(const PacParams &P, const DevTask &
             probabilities32(1);
         };
         auto matrix_half_and_loads = [&](int k) {                       // M(b_k), k + 1 < nmine
-            matrix_half();
-            __builtin_amdgcn_sched_barrier(0);
-            load_keys(blk(k + 2));
-            load_values(blk(k + 1));
+            matrix_half(blk(k + 2), blk(k + 1));
             __builtin_amdgcn_sched_barrier(0);
         };
         auto interval = [&](int k, auto more) {
