@@ -726,7 +726,7 @@ __device__ __forceinline__ void dense32_wave(const PacParams &P, const DevTask &
     // group (compute-bound tasks) each pair is followed by the LDS reads that refill the operand
     // registers it has just consumed (K of block kb, V of block vb): the reads are issued while the
     // matrix unit works on the pair.
-    auto matrix_half = [&](int kb, int vb) {
+    auto matrix_half = [&](int kb, int vb, auto after_first_pair) {
         const uint32_t kbase = key_base(kb), vbase = value_base(vb);
         f32x16 acc;
 #pragma unroll
@@ -739,6 +739,7 @@ __device__ __forceinline__ void dense32_wave(const PacParams &P, const DevTask &
                 load_value(vbase, i & 3, i >> 2);
                 load_key(kbase, i);
             }
+            if (i == 0) after_first_pair();
             __builtin_amdgcn_sched_barrier(0);
         }
         if constexpr (STRIDE == 2) {        // memory-bound tasks: measured faster with the reads in one go
@@ -806,10 +807,12 @@ __device__ __forceinline__ void dense32_wave(const PacParams &P, const DevTask &
     __syncthreads();
 
     // more: blocks S*j+8 .. S*j+8+S-1 all exist
-    auto enter_interval = [&](int j, auto more) {                       // j < nint
+    auto wait_and_sync = [&](auto more) {
         if constexpr (decltype(more)::value) __builtin_amdgcn_s_waitcnt(vmcnt_imm(2 * (RING - 3 * STRIDE)));
         else                                 __builtin_amdgcn_s_waitcnt(0x0F70);
         __syncthreads();                    // blocks up to S*j+3S-1 are complete; everyone is done with block(s) S*j ..
+    };
+    auto request_blocks = [&](int j, auto more) {                       // any time inside interval j
         if constexpr (decltype(more)::value) {
 #pragma unroll
             for (int u = 0; u < STRIDE; ++u) dma_block(STRIDE * j + RING + u, pg_next[u]);
@@ -818,6 +821,10 @@ __device__ __forceinline__ void dense32_wave(const PacParams &P, const DevTask &
         } else if constexpr (STRIDE == 2) {
             if (2 * j + RING < nblk) dma_block(2 * j + RING, pg_next[0]);         // an odd block left over
         }
+    };
+    auto enter_interval = [&](int j, auto more) {                       // j < nint
+        wait_and_sync(more);
+        request_blocks(j, more);
     };
     using yes = std::true_type;
     using no = std::false_type;
@@ -840,19 +847,25 @@ __device__ __forceinline__ void dense32_wave(const PacParams &P, const DevTask &
             probabilities32(0);
             probabilities32(1);
         };
-        auto matrix_half_and_loads = [&](int k) {                       // M(b_k), k + 1 < nmine
-            matrix_half(blk(k + 2), blk(k + 1));
+        // With one wave per row group the copies of the interval are requested from inside the matrix
+        // half: their address arithmetic issues while the matrix unit works, instead of ahead of it.
+        constexpr bool REQUEST_INSIDE = STRIDE == 1;
+        auto matrix_half_and_loads = [&](int k, auto more) {            // M(b_k), k + 1 < nmine
+            matrix_half(blk(k + 2), blk(k + 1), [&]() {
+                if constexpr (REQUEST_INSIDE) request_blocks(k, more);
+            });
             __builtin_amdgcn_sched_barrier(0);
         };
         auto interval = [&](int k, auto more) {
-            enter_interval(k, more);
+            wait_and_sync(more);
+            if constexpr (!REQUEST_INSIDE) request_blocks(k, more);
             if (STRIDE == 1 || k + 1 < nmine) {                         // else: the other wave's last block only
                 if constexpr (VFIRST) {
                     vector_half_of(blk(k));
                     __builtin_amdgcn_sched_barrier(0);
-                    matrix_half_and_loads(k);
+                    matrix_half_and_loads(k, more);
                 } else {
-                    matrix_half_and_loads(k);
+                    matrix_half_and_loads(k, more);
                     vector_half_of(blk(k + 1));
                     __builtin_amdgcn_sched_barrier(0);
                 }
