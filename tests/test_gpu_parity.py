@@ -93,9 +93,11 @@ def test_row_tiles(max_rows):
 @pytest.mark.parametrize("requests", [5, 16, 17, 32, 33, 64])
 def test_dense_tasks_of_every_block_count(requests):
     """One undivided task per root, 20 .. 256 rows: 1 .. 70 blocks of 32 tokens, odd and even counts,
-    counts around the depth of the block ring, ragged last blocks (the two waves of a row group take
-    alternate blocks in tasks of at most 128 rows, so the odd-block wave may have one block less, or none)."""
-    lens = [1, 33, 65, 96, 200, 256, 257, 289, 300, 330, 353, 511, 545, 577, 2210]
+    counts around the depth of the block ring, ragged last blocks; from 1024 tokens on, the two waves of
+    a row group take alternate blocks in tasks of at most 128 rows, so the odd-block wave may have one
+    block less than the other."""
+    lens = [1, 33, 65, 96, 200, 256, 257, 289, 300, 330, 353, 511, 545, 577, 1023, 1024, 1025, 1090, 1290, 1312,
+            1345, 2210]
     f = two_level_forest(lens[0], [43] * requests)
     for n in lens[1:]:
         f = concat_forests(f, two_level_forest(n, [40 + n % 4] * requests))      # private suffixes: stream path
