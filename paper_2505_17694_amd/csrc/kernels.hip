@@ -623,12 +623,13 @@ __device__ __forceinline__ void dense32_wave(const PacParams &P, const DevTask &
 
     // Asynchronous copies.  Wave w moves tokens 4w .. 4w+3 of every block, 1 KB of K and 1 KB of V;
     // lane (grp, l16) writes the 16-byte slot l16 of LDS row 4w + grp.  A K row keeps its 16-byte
-    // column g in slot g ^ (token & 15), a V row in slot g ^ (2*token & 15): the swizzles that make
-    // the operand reads below free of bank conflicts.
+    // column g in slot g ^ (token & 15), a V row in slot g ^ 4*(token & 3): the swizzles that make
+    // the operand reads below free of bank conflicts (a transposing V read takes, per 32 lanes, 4 rows
+    // x 64 bytes: the four rows must land in four different quarters of the 256 bytes of banks).
     const uint32_t lds_base = uint32_t(uintptr_t(lds));
     const int tok_w = wave * 4 + grp;
     const uint32_t voff_k = uint32_t(grp) * c.token_bytes + uint32_t((l16 ^ (tok_w & 15)) << 4);
-    const uint32_t voff_v = uint32_t(grp) * c.token_bytes + uint32_t((l16 ^ ((2 * tok_w) & 15)) << 4);
+    const uint32_t voff_v = uint32_t(grp) * c.token_bytes + uint32_t((l16 ^ ((tok_w & 3) << 2)) << 4);
     // a group of four tokens past the end of the slice is redirected to token 0 (its rows are masked
     // later) so that no address leaves the slice's pages
     auto first_token = [&](int bb) {
@@ -654,7 +655,7 @@ __device__ __forceinline__ void dense32_wave(const PacParams &P, const DevTask &
     const int vk = l16 >> 2, vq = l16 & 3, vch = grp & 1;
     const int vrow = 4 * kg + vk;
     const uint32_t va_lane =
-        uint32_t(8192 + vrow * 256 + ((((2 * vch + (vq >> 1)) ^ (2 * vrow)) & 15) << 4) + 8 * (vq & 1));
+        uint32_t(8192 + vrow * 256 + ((((2 * vch + (vq >> 1)) ^ ((vrow & 3) << 2)) & 15) << 4) + 8 * (vq & 1));
     u32x4 kr[8];            // K operands of one block, by k-step
     u32x4 vr[4][2];         // V operands of one block, by channel tile and k-step
     auto key_base = [&](int bb) { return lds_base + uint32_t(bb % RING) * kBlockBytes + ka_lane; };
