@@ -166,6 +166,14 @@ def run_config(name, args, steps, warmup, want_flat):
             res[key]["refresh_ms"] = round((time.perf_counter() - t0) * 1e3, 3)
         pa.close()
     if want_flat:
+        # the same prefix-shared tasks taken from a run-time queue instead of the static slot lists
+        pa = C.PlannedAttention(w.forest, w.paged, w.head, device="cuda:0", share=1, schedule=1,
+                                num_slots=args.num_slots, split_align=args.split_align, max_rows=args.max_rows)
+        view = pa.export()
+        t, _ = time_plan(pa, w, rot, steps, warmup)
+        res["tree_queued"] = {"us_per_step": round(t["step_ms"] * 1e3, 2), "pac_us": round(t["pac_ms_avg"] * 1e3, 2),
+                              "entries": len(view["queue_off"]) - 1, "slots": view["num_slots"]}
+        pa.close()
         res["speedup_vs_flat"] = round(res["flat"]["us_per_step"] / res["tree"]["us_per_step"], 3)
         res["tree_vs_flat_max_abs_diff"] = float((outs[1].float() - outs[0].float()).abs().max())
     return res, w, outs[1]

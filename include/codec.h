@@ -112,6 +112,14 @@ typedef struct {
                                n > 0 = the naive strategy it is compared with (Sec. 7, impact of
                                division granularity): every node is cut evenly into n slices (fewer
                                when the node is too short), then scheduled the same way            */
+    int32_t schedule;       /* 0 = static: slot s runs the task list the greedy schedule gave it (Eq. 3's
+                               assignment, as the paper executes it); 1 = run-time queue: the same tasks
+                               in the same longest-first order, but a workgroup takes the next entry of
+                               the queue when it has finished one, so that errors of the cost estimate
+                               do not leave workgroups idle.  The first num_slots entries go to the
+                               workgroups they would go to anyway; runs of short tasks form one entry.
+                               The queue keeps two counters per KV head in the plan's device metadata:
+                               one launch of a plan at a time                                        */
 } codec_plan_options;
 
 /* One work item of the division problem: a node (or a row tile of it) with its queries. */
@@ -167,6 +175,10 @@ typedef struct {
     int32_t           split_align;
     int32_t           max_rows;
     int32_t           share;
+    int32_t           schedule;
+    int32_t           num_entries;  /* run-time queue (also built for static plans): entry e holds tasks */
+    const int32_t    *queue_off;    /* queue_tasks[queue_off[e] .. queue_off[e+1]); entries in order of  */
+    const int32_t    *queue_tasks;  /* decreasing cost of their first task                               */
 } codec_plan_view;
 
 /*

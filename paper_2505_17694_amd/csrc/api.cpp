@@ -105,6 +105,10 @@ int codec_plan_export(const codec_plan_t *plan, codec_plan_view *v)
     v->split_align = d.split_align;
     v->max_rows = d.max_rows;
     v->share = d.share;
+    v->schedule = d.schedule;
+    v->num_entries = int32_t(d.queue_off.size()) - 1;
+    v->queue_off = d.queue_off.data();
+    v->queue_tasks = d.queue_tasks.data();
     return CODEC_OK;
 }
 
@@ -227,6 +231,13 @@ int codec_partial_attention(const codec_plan_t *plan, const void *q, const void 
     while ((1 << pp.page_shift) < d.head.page_size) ++pp.page_shift;
     pp.part_rows = d.part_rows;
     pp.scale_log2e = d.head.scale * 1.4426950408889634f;
+    pp.num_slots = d.num_slots;
+    if (d.schedule == 1) {
+        pp.queue_off = reinterpret_cast<const int32_t *>(meta + L.queue_off);
+        pp.queue_tasks = reinterpret_cast<const int32_t *>(meta + L.queue_tasks);
+        pp.counters = reinterpret_cast<int32_t *>(const_cast<char *>(meta) + L.counters);
+        pp.num_entries = int32_t(d.queue_off.size()) - 1;
+    }
     if (int e = codec::launch_pac(pp, d.head.dtype, d.num_slots, plan->max_task_rows, stream))
         return hip_failure("partial attention launch", e);
     return CODEC_OK;

@@ -992,43 +992,75 @@ __global__ void __launch_bounds__(WIDE ? kWideWaves * 64 : kNarrowWaves * 64, 2)
     }
     const int head = blockIdx.x % P.h_kv;
     const int slot = blockIdx.x / P.h_kv;
-    const int t0 = P.slot_off[slot], t1 = P.slot_off[slot + 1];
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    // Tasks of more than 16 rows take the dense path (wide variant only).  Tasks of at most 16 rows take
-    // the stream path, as a rule with all waves of the workgroup as one team.  Runs of two or more short
-    // ones (the plan marks them; they are neighbours in a slot's list, which is sorted by cost) are
-    // handed out one wave each through a counter in LDS: the latencies of a short task (descriptor,
-    // query rows, page ids, first blocks, merge of a team) then overlap with the other tasks' instead of
-    // adding up.
-    int i = t0;
+    // Runs the tasks list[t0 .. t1).  Tasks of more than 16 rows take the dense path (wide variant
+    // only).  Tasks of at most 16 rows take the stream path, as a rule with all waves of the workgroup
+    // as one team.  Runs of two or more short ones are handed out one wave each through a counter in
+    // LDS: the latencies of a short task (descriptor, query rows, page ids, first blocks, merge of a
+    // team) then overlap with the other tasks' instead of adding up.  In a slot's list the plan marks
+    // such runs (they are neighbours there, the list being sorted by cost); an entry of the run-time
+    // queue with several tasks is one such run.
+    auto run_tasks = [&](const int32_t *list, int t0, int t1, bool marked) __attribute__((always_inline)) {
+        int i = t0;
 #pragma unroll 1
-    while (i < t1) {
-        const DevTask t = P.tasks[P.slot_tasks[i]];
-        const int n = t.solo_run;
-        if (n >= 2) {
-            int *next = reinterpret_cast<int *>(lds);
-            if (threadIdx.x == 0) *next = 0;
-            __syncthreads();
+        while (i < t1) {
+            const DevTask t = P.tasks[list[i]];
+            const int n = marked ? t.solo_run : t1 - i;
+            if (n >= 2) {
+                int *next = reinterpret_cast<int *>(lds);
+                if (threadIdx.x == 0) *next = 0;
+                __syncthreads();
 #pragma unroll 1
-            for (;;) {
-                int k = 0;
-                if ((threadIdx.x & 63) == 0) k = atomicAdd(next, 1);
-                k = __builtin_amdgcn_readfirstlane(k);
-                if (k >= n) break;
-                const DevTask mine = P.tasks[P.slot_tasks[i + k]];
-                if (mine.read_once) run_stream<DT, true, 1, 1>(P, mine, head, lds, 0);
-                else                run_stream<DT, false, 1, 1>(P, mine, head, lds, 0);
+                for (;;) {
+                    int k = 0;
+                    if ((threadIdx.x & 63) == 0) k = atomicAdd(next, 1);
+                    k = __builtin_amdgcn_readfirstlane(k);
+                    if (k >= n) break;
+                    const DevTask mine = P.tasks[list[i + k]];
+                    if (mine.read_once) run_stream<DT, true, 1, 1>(P, mine, head, lds, 0);
+                    else                run_stream<DT, false, 1, 1>(P, mine, head, lds, 0);
+                }
+                __syncthreads();                // the counter is done with before LDS is used again
+                i += n;
+            } else {
+                if (t.n_req * P.group <= 16) {
+                    if (t.read_once) run_stream<DT, true, 1, W>(P, t, head, lds, wave);
+                    else             run_stream<DT, false, 1, W>(P, t, head, lds, wave);
+                }
+                else if constexpr (WIDE != 0) run_dense32<DT>(P, t, head, lds);
+                ++i;
             }
-            __syncthreads();                // the counter is done with before LDS is used again
-            i += n;
-        } else {
-            if (t.n_req * P.group <= 16) {
-                if (t.read_once) run_stream<DT, true, 1, W>(P, t, head, lds, wave);
-                else             run_stream<DT, false, 1, W>(P, t, head, lds, wave);
-            }
-            else if constexpr (WIDE != 0) run_dense32<DT>(P, t, head, lds);
-            ++i;
         }
+    };
+
+    // Static schedule: the slot's own list, once.  Run-time queue: entry `slot` is this workgroup's
+    // first; every further one is the next entry nobody has taken, fetched by one thread (one atomic)
+    // and spread to the waves through LDS.  Every path through run_tasks ends with a barrier behind
+    // its last LDS access, so the word can be written right away; the second barrier keeps the next
+    // task's block copies from overwriting it before everyone has read it.
+    const bool queued = P.queue_off != nullptr;
+    const bool fetching = queued && P.num_entries > P.num_slots;        // else: an entry per workgroup at most
+    const int32_t *list = queued ? P.queue_tasks : P.slot_tasks;
+    const int32_t *off = queued ? P.queue_off : P.slot_off;
+    const int limit = queued ? P.num_entries : slot + 1;
+    int32_t *taken = P.counters + 2 * head, *finished = taken + 1;
+    int *word = reinterpret_cast<int *>(lds);
+    int e = slot;
+#pragma unroll 1
+    while (e < limit) {
+        run_tasks(list, off[e], off[e + 1], !queued);
+        if (!fetching) break;
+        // taken when the workgroup is free, not ahead of time: an entry reserved early would wait for
+        // the end of a long task while other workgroups idle
+        if (threadIdx.x == 0) *word = P.num_slots + atomicAdd(taken, 1);
+        __syncthreads();
+        e = __builtin_amdgcn_readfirstlane(*word);
+        __syncthreads();
+    }
+    // the last workgroup of this KV head to get here leaves the counters at zero for the next launch
+    if (fetching && threadIdx.x == 0 && atomicAdd(finished, 1) == P.num_slots - 1) {
+        atomicExch(taken, 0);
+        atomicExch(finished, 0);
     }
 }
 

@@ -21,6 +21,14 @@ struct PacParams {
     float *part_ml;                 // [h_kv][part_rows][2]   (max in log2 units, sum of exponentials)
     int32_t h_q, h_kv, group, page_shift, part_rows;    // page_shift = log2(tokens per page)
     float scale_log2e;              // scale * log2(e): scores are kept in log2 units
+    // Run-time queue (queue_off == nullptr: static slot lists).  Entry e holds the tasks
+    // queue_tasks[queue_off[e] .. queue_off[e+1]); counters[2*head] counts the entries taken beyond the
+    // first num_slots, counters[2*head + 1] the workgroups of the head that have finished.  The last
+    // workgroup to finish puts both back to zero.
+    const int32_t *queue_off;
+    const int32_t *queue_tasks;
+    int32_t *counters;
+    int32_t num_entries, num_slots;
 };
 
 struct MergeParams {

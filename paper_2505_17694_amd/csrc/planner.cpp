@@ -108,6 +108,50 @@ void build_device_image(PlanData &p)
     L.page_ids = place(p.page_ids.size() * 4);
     L.req_part_off = place(p.req_part_off.size() * 4);
     L.req_part = place(p.req_part.size() * 4);
+    // Run-time queue.  Short tasks (the ones a single wave runs) are bundled, in order of decreasing
+    // cost, into entries that a workgroup hands out one wave each, like a run of short tasks in a
+    // slot's list; every other task is an entry of its own.  The bundle size is the smallest that lets
+    // every entry have a workgroup of its own (then no entry is ever fetched at run time and the queue
+    // costs nothing), at most kQueueBundle.  Entries are ordered by decreasing cost, a bundle counting
+    // as the sum of its tasks, ties to the entry with the lower first task: the order in which the
+    // greedy schedule would deal them.
+    {
+        std::vector<int32_t> order(p.tasks.size());
+        for (size_t i = 0; i < order.size(); ++i) order[i] = int32_t(i);
+        std::stable_sort(order.begin(), order.end(),
+                         [&](int32_t a, int32_t b) { return p.tasks[a].cost > p.tasks[b].cost; });
+        auto is_short = [&](int32_t i) {
+            return p.tasks[i].n_req * p.group <= kSoloMaxRows && p.tasks[i].kv_len <= kSoloMaxLen;
+        };
+        int64_t n_short = 0;
+        for (int32_t i : order) n_short += is_short(i);
+        const int64_t n_long = int64_t(order.size()) - n_short;
+        int64_t bundle = kQueueBundle;
+        if (n_long < p.num_slots) bundle = std::min<int64_t>(kQueueBundle, std::max<int64_t>(1, ceil_div(n_short, p.num_slots - n_long)));
+        struct Entry { int64_t cost; std::vector<int32_t> tasks; };
+        std::vector<Entry> entries;
+        int64_t open_bundle = -1;
+        for (int32_t i : order) {
+            if (is_short(i) && open_bundle >= 0 && int64_t(entries[open_bundle].tasks.size()) < bundle) {
+                entries[open_bundle].tasks.push_back(i);
+                entries[open_bundle].cost += p.tasks[i].cost;
+                continue;
+            }
+            entries.push_back({p.tasks[i].cost, {i}});
+            open_bundle = is_short(i) ? int64_t(entries.size()) - 1 : open_bundle;
+            if (is_short(i) && bundle == 1) open_bundle = -1;
+        }
+        std::stable_sort(entries.begin(), entries.end(), [](const Entry &a, const Entry &b) { return a.cost > b.cost; });
+        p.queue_off.assign(1, 0);
+        p.queue_tasks.clear();
+        for (const Entry &e : entries) {
+            p.queue_tasks.insert(p.queue_tasks.end(), e.tasks.begin(), e.tasks.end());
+            p.queue_off.push_back(int32_t(p.queue_tasks.size()));
+        }
+    }
+    L.queue_off = place(p.queue_off.size() * 4);
+    L.queue_tasks = place(p.queue_tasks.size() * 4);
+    L.counters = place(size_t(p.head.num_kv_heads) * 2 * 4);               // zero: nothing taken, nobody done
     L.total = std::max<size_t>(off, 256);
     p.blob.assign(L.total, 0);
     DevTask *dt = reinterpret_cast<DevTask *>(p.blob.data() + L.tasks);
@@ -148,6 +192,8 @@ void build_device_image(PlanData &p)
     put(L.page_ids, p.page_ids);
     put(L.req_part_off, p.req_part_off);
     put(L.req_part, p.req_part);
+    put(L.queue_off, p.queue_off);
+    put(L.queue_tasks, p.queue_tasks);
 }
 
 }  // namespace
@@ -230,6 +276,7 @@ int build_plan(const codec_tree &tree, const codec_head_config &head,
     if (max_rows > 256 || max_rows < group) return CODEC_ERR_INVALID_ARGUMENT;
     if (opt.share != 0 && opt.share != 1) return CODEC_ERR_INVALID_ARGUMENT;
     if (opt.fixed_slices < 0) return CODEC_ERR_INVALID_ARGUMENT;
+    if (opt.schedule != 0 && opt.schedule != 1) return CODEC_ERR_INVALID_ARGUMENT;
 
     CostTable user;
     const CostTable *table = nullptr;           // nullptr: the built-in table of the kernel variant
@@ -284,6 +331,7 @@ int build_plan(const codec_tree &tree, const codec_head_config &head,
     p.split_align = align;
     p.max_rows = max_rows;
     p.share = opt.share;
+    p.schedule = opt.schedule;
     p.num_nodes = N;
     p.num_requests = B;
     p.node_len.assign(tree.node_len, tree.node_len + N);

@@ -23,6 +23,9 @@ struct CostTable {
 // take runs of such tasks in a slot's list one wave each (see solo_run below).
 constexpr int32_t kSoloMaxRows = 16;
 constexpr int32_t kSoloMaxLen = 1024;
+// Most short tasks in one entry of the run-time queue (measured on cfg3/cfg4: 2 costs fetches, 8 and
+// more make the last entries long).
+constexpr int32_t kQueueBundle = 4;
 
 // Task record as the kernels read it (32 bytes).
 struct DevTask {
@@ -39,13 +42,13 @@ struct DevTask {
 // Byte offsets of the arrays inside the device metadata blob.
 struct DevLayout {
     size_t tasks = 0, slot_off = 0, slot_tasks = 0, node_q = 0, page_ids = 0,
-           req_part_off = 0, req_part = 0, total = 0;
+           req_part_off = 0, req_part = 0, queue_off = 0, queue_tasks = 0, counters = 0, total = 0;
 };
 
 struct PlanData {
     codec_head_config head{};
     int32_t group = 1;
-    int32_t num_slots = 0, split_align = 0, max_rows = 0, share = 1;
+    int32_t num_slots = 0, split_align = 0, max_rows = 0, share = 1, schedule = 0;
     int32_t num_nodes = 0, num_requests = 0;
 
     std::vector<int32_t> node_len, node_page_off, page_ids;
@@ -53,6 +56,7 @@ struct PlanData {
     std::vector<codec_item> items;
     std::vector<codec_task> tasks;
     std::vector<int32_t> slot_off, slot_tasks;
+    std::vector<int32_t> queue_off, queue_tasks;    // run-time queue: entries in longest-first order
     std::vector<int32_t> req_part_off, req_part;
     int64_t cost_l = 0, makespan = 0;
     int32_t part_rows = 0;

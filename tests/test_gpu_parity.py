@@ -269,13 +269,15 @@ def test_limits_of_the_interface():
     assert np.abs(got - ref).max() <= TOL
 
 
-def test_decode_replayed_from_a_hip_graph():
+@pytest.mark.parametrize("schedule", [0, 1])
+def test_decode_replayed_from_a_hip_graph(schedule):
     """The decode call is two kernel launches on the caller's stream and nothing else, so it can be
-    captured; every replay (with eager work and new queries in between) must equal the eager result."""
+    captured; every replay (with eager work and new queries in between) must equal the eager result.
+    With the run-time queue the kernel itself puts the queue's counters back (no memset node)."""
     C = _C()
     w = make_small_config("cfg3", 16, 2, poison=True)
     wd = w.to("cuda:0")
-    pa = C.PlannedAttention(w.forest, w.paged, w.head, device="cuda:0")
+    pa = C.PlannedAttention(w.forest, w.paged, w.head, device="cuda:0", schedule=schedule)
     q = wd.q.clone()
     out = torch.empty_like(q)
     pa.decode(q, wd.k_pool, wd.v_pool, out)                         # warm-up outside the capture
@@ -296,6 +298,76 @@ def test_decode_replayed_from_a_hip_graph():
     ref, _ = A.decode_attention_workload(w)
     assert np.abs(out.double().cpu().numpy() - ref).max() <= TOL
     pa.close()
+
+
+def _queue_cases():
+    short = [7, 40, 1024, 33, 1025, 64, 300, 5, 2000, 96, 17, 1000, 31, 640, 1, 129] * 3
+    dense = two_level_forest(1, [43] * 17)
+    for n in [33, 300, 545, 1024, 1090, 2210]:
+        dense = concat_forests(dense, two_level_forest(n, [40 + n % 4] * 17))
+    return {
+        "cfg2": (lambda: make_small_config("cfg2", 8, 2, poison=True), {}),
+        "cfg3": (lambda: make_small_config("cfg3", 16, 2, poison=True), {}),
+        "cfg4": (lambda: make_small_config("cfg4", 8, 8, poison=True), {}),
+        "cfg5c": (lambda: make_small_config("cfg5c", 64, 8, poison=True), {}),
+        "cfg3-flat": (lambda: make_small_config("cfg3", 16, 2, poison=True), {"share": 0}),
+        "short-1-slot": (lambda: make_workload("q-short", concat_forests(two_level_forest(1500, short),
+                                                                         two_level_forest(200, [50, 60, 70, 80, 90])),
+                                               HeadConfig(8, 2, 128, DTYPE_BF16), seed=23, poison=True),
+                         {"num_slots": 1, "split_align": 32}),
+        "short-3-slots": (lambda: make_workload("q-short3", two_level_forest(1500, short),
+                                                HeadConfig(8, 2, 128, DTYPE_BF16), seed=24, poison=True),
+                          {"num_slots": 3, "split_align": 32}),
+        "dense-2-slots": (lambda: make_workload("q-dense", dense, HeadConfig(8, 2, 128, DTYPE_BF16), seed=25,
+                                                poison=True), {"num_slots": 2, "split_align": 4096}),
+        "more-slots-than-entries": (lambda: make_workload("q-few", two_level_forest(100, [5, 9]),
+                                                          HeadConfig(8, 8, 128, DTYPE_FP16), seed=26, poison=True),
+                                    {"num_slots": 64}),
+        "mqa-one-head": (lambda: make_workload("q-mqa", three_level_forest(70, [130, 45], 3, [5, 33, 64, 1, 17, 48]),
+                                               HeadConfig(4, 1, 128, DTYPE_BF16), seed=27, poison=True), {}),
+    }
+
+
+@pytest.mark.parametrize("name", sorted(_queue_cases()))
+def test_run_time_queue_equals_the_static_schedule(name):
+    """schedule = 1 runs the same tasks, writes the same partial rows and merges them in the same order as
+    the static schedule; what differs is the workgroup that runs a task and whether a short task is
+    run by one wave or by a team (which changes the order of its fp32 sums).  Every launch is held
+    against the oracle with both bars of this file, and the launches of the queue against each other bit
+    for bit (the kernel leaves the queue's counters at zero behind it; which workgroup takes which entry
+    changes no task's own arithmetic)."""
+    C = _C()
+    make, opts = _queue_cases()[name]
+    w = make()
+    wd = w.to("cuda:0")
+    static = C.PlannedAttention(w.forest, w.paged, w.head, device="cuda:0", **opts)
+    queued = C.PlannedAttention(w.forest, w.paged, w.head, device="cuda:0", schedule=1, **opts)
+    view = queued.export()
+    assert view["schedule"] == 1
+    want = static.decode(wd.q, wd.k_pool, wd.v_pool).double().cpu().numpy()
+    ref, _ = A.decode_attention_workload(w)
+    assert np.all(np.abs(want - ref) <= 2e-3 + 2.0 ** -7 * np.abs(ref))
+    outs = []
+    for launch in range(3):
+        got = queued.decode(wd.q, wd.k_pool, wd.v_pool)
+        torch.cuda.synchronize()
+        outs.append(got.clone())
+        g = got.double().cpu().numpy()
+        assert not np.any(np.isnan(g)), f"launch {launch}"
+        assert np.abs(g - ref).max() <= TOL, f"launch {launch}: {np.abs(g - ref).max():.3e}"
+        assert np.all(np.abs(g - ref) <= 2e-3 + 2.0 ** -7 * np.abs(ref)), f"launch {launch}: mixed bar"
+    # partial attention alone, twice in a row, then the reduction: the counters do not depend on the
+    # reduction kernel
+    queued.partial_attention(wd.q, wd.k_pool, wd.v_pool)
+    queued.partial_attention(wd.q, wd.k_pool, wd.v_pool)
+    out = torch.empty_like(wd.q)
+    queued.partial_reduction(out)
+    torch.cuda.synchronize()
+    outs.append(out)
+    for i, o in enumerate(outs[1:]):
+        assert torch.equal(o.view(torch.int16), outs[0].view(torch.int16)), f"launch {i + 1} differs from launch 0"
+    static.close()
+    queued.close()
 
 
 def test_tree_equals_flat_on_the_gpu():

@@ -240,3 +240,52 @@ def test_best_of_three_plans_matches_oracle(name, table):
         assert (view["share"], view["max_rows"]) == (1, 256)
     if name in ("docqa", "quarter", "random") and custom is not None:
         assert (view["share"], view["max_rows"]) != (1, 256)
+
+
+# ---- run-time queue (schedule = 1): structure of the entries ---------------------------------------
+
+@pytest.mark.parametrize("name", sorted(BEST_CASES))
+@pytest.mark.parametrize("slots", [0, 4])
+def test_run_time_queue_entries(name, slots):
+    """The queue holds every task once; an entry of several tasks holds short ones only (at most 16 rows
+    and 1024 tokens, at most 4 of them); entries come in order of decreasing cost (a bundle counts as the
+    sum of its tasks); when the tasks that are not short leave workgroups free, the bundles are just
+    large enough for every entry to have a workgroup of its own."""
+    make, head = BEST_CASES[name]
+    f = make()
+    group = head.num_q_heads // head.num_kv_heads
+    paged = build_paged_kv(f, head, seed=1)
+    st, plan = C.codec_plan_create(f.parent, f.node_len, f.req_node, paged.node_page_off, paged.page_ids,
+                                   head.num_q_heads, head.num_kv_heads, head.head_dim, head.dtype,
+                                   head.page_size, head.scale, num_slots=slots, schedule=1)
+    assert st == C.CODEC_OK
+    st, v = C.codec_plan_export(plan)
+    C.codec_plan_destroy(plan)
+    assert v["schedule"] == 1
+    off, q, tasks = list(v["queue_off"]), list(v["queue_tasks"]), v["tasks"]
+    assert sorted(q) == list(range(len(tasks))) and off[0] == 0 and off[-1] == len(tasks)
+    short = [t["n_req"] * group <= 16 and t["kv_len"] <= 1024 for t in tasks]
+    costs = []
+    for e in range(len(off) - 1):
+        members = q[off[e]:off[e + 1]]
+        assert 1 <= len(members) <= 4
+        if len(members) > 1:
+            assert all(short[i] for i in members)
+        costs.append(sum(tasks[i]["cost"] for i in members))
+    assert costs == sorted(costs, reverse=True)
+    n_long = short.count(False)
+    m = v["num_slots"]
+    if n_long < m and -(-short.count(True) // (m - n_long)) <= 4:
+        assert len(off) - 1 <= m
+
+
+def test_schedule_option_is_checked():
+    f = two_level_forest(100, [5, 9])
+    head = HeadConfig(8, 8, 128, 0)
+    paged = build_paged_kv(f, head, seed=1)
+    for bad in (2, -1):
+        st, plan = C.codec_plan_create(f.parent, f.node_len, f.req_node, paged.node_page_off, paged.page_ids,
+                                       head.num_q_heads, head.num_kv_heads, head.head_dim, head.dtype,
+                                       head.page_size, head.scale, schedule=bad)
+        assert st == C.CODEC_ERR_INVALID_ARGUMENT and plan is None
+
