@@ -414,17 +414,18 @@ def test_full_size_configurations_on_sampled_outputs(name, n_pairs):
     C = _C()
     print(f"[case] full {name} unique_kv_bytes={w.unique_kv_bytes}", flush=True)
     sel = _sample_pairs(w, n_pairs, seed=77)
-    for share in (1, 0):
-        pa = C.PlannedAttention(w.forest, w.paged, w.head, device="cuda:0", share=share)
+    ref = None
+    for share, schedule in ((1, 0), (0, 0), (1, 1)):        # shared plan, flat plan, shared plan from the queue
+        pa = C.PlannedAttention(w.forest, w.paged, w.head, device="cuda:0", share=share, schedule=schedule)
         out = pa.decode(w.q, w.k_pool, w.v_pool)
         torch.cuda.synchronize()
         got = out.to(torch.float64).cpu().numpy()
         pa.close()
-        if share == 1:
+        if ref is None:
             ref, _ = A.decode_attention_workload(w, sel=sel)
         g = np.stack([got[r, h] for r, h in sel])
         err = np.abs(g - ref)
-        print(f"[case] full {name} share={share} max_err={err.max():.3e}", flush=True)
+        print(f"[case] full {name} share={share} schedule={schedule} max_err={err.max():.3e}", flush=True)
         assert not np.any(np.isnan(got))
         assert err.max() <= TOL
         assert np.all(err <= 2e-3 + 2.0 ** -7 * np.abs(ref))
