@@ -300,6 +300,33 @@ def test_decode_replayed_from_a_hip_graph(schedule):
     pa.close()
 
 
+@pytest.mark.parametrize("seed", range(24))
+def test_random_forests_heads_and_plan_options(seed):
+    """Seeded draws over tree shape, head layout, dtype, page size and layout, and every plan option
+    (slot count, slice alignment, row tile, plan kind, schedule): each against the oracle."""
+    rng = np.random.Generator(np.random.PCG64(4000 + seed))
+    leaves = int(rng.integers(1, 40))
+    f = random_forest(leaves, int(rng.integers(1, 6)), float(rng.uniform(0.3, 3.0)),
+                      int(rng.choice([20, 120, 600])), float(rng.uniform(0.3, 1.4)), 1,
+                      int(rng.choice([200, 1500, 5000])), seed=500 + seed)
+    if rng.random() < 0.3:                                    # some requests end at inner nodes
+        inner = [int(f.parent[n]) for n in f.req_node[:4] if f.parent[n] >= 0]
+        f = Forest(f.parent, f.node_len, np.concatenate([f.req_node, np.array(inner, dtype=np.int32)]))
+    hq, hkv = [(8, 8), (8, 2), (32, 8), (12, 4), (16, 1), (64, 8), (6, 3)][int(rng.integers(0, 7))]
+    dtype = DTYPE_BF16 if rng.random() < 0.6 else DTYPE_FP16
+    page_size = int(rng.choice([16, 32, 64]))
+    layout = "htd" if rng.random() < 0.5 else "thd"
+    head = HeadConfig(hq, hkv, 128, dtype, page_size=page_size)
+    w = make_workload(f"random{seed}", f, head, seed=900 + seed, poison=True, layout=layout)
+    opts = {"num_slots": int(rng.choice([0, 1, 5, 17])),
+            "split_align": int(rng.choice([1, 2, 8])) * max(32, page_size),
+            "max_rows": int(rng.choice([0, 0, 16, 64, 128, 200])),
+            "schedule": int(rng.integers(0, 2))}
+    if opts["max_rows"] and opts["max_rows"] < hq // hkv:
+        opts["max_rows"] = 0
+    check(w, share=int(rng.choice([1, 1, 0, 2])), **opts)
+
+
 def _queue_cases():
     short = [7, 40, 1024, 33, 1025, 64, 300, 5, 2000, 96, 17, 1000, 31, 640, 1, 129] * 3
     dense = two_level_forest(1, [43] * 17)
