@@ -179,9 +179,10 @@ def test_same_plan_decodes_repeatedly_and_with_new_queries():
     pa.close()
 
 
-@pytest.mark.parametrize("share", [1, 0])
-def test_plan_carried_over_to_grown_lengths(share):
-    """codec_plan_refresh_lengths: same division and schedule, longer last slices, new page lists."""
+@pytest.mark.parametrize("share,schedule", [(1, 0), (0, 0), (1, 1)])
+def test_plan_carried_over_to_grown_lengths(share, schedule):
+    """codec_plan_refresh_lengths: same division and schedule, longer last slices, new page lists (and, for
+    the run-time queue, entries ordered by the new costs and counters back at zero)."""
     C = _C()
     f_old = three_level_forest(700, [1300, 450], 3, [5, 33, 64, 1, 17, 48])
     head = HeadConfig(16, 4, 128, DTYPE_BF16)
@@ -195,7 +196,8 @@ def test_plan_carried_over_to_grown_lengths(share):
     w_old.k_pool[:] = w_new.k_pool
     w_old.v_pool[:] = w_new.v_pool
     wd = w_new.to("cuda:0")
-    pa = C.PlannedAttention(f_old, w_new.paged, head, device="cuda:0", share=share, num_slots=16, split_align=32)
+    pa = C.PlannedAttention(f_old, w_new.paged, head, device="cuda:0", share=share, num_slots=4 if schedule else 16,
+                            split_align=32, schedule=schedule)
     tasks_before = pa.export()["tasks"]
     for w, lens in ((w_old, None), (w_new, f_new.node_len)):
         if lens is not None:
