@@ -256,7 +256,11 @@ size_t codec_plan_device_bytes(const codec_plan_t *plan);
  * Copies the plan's device-side metadata into `device_meta` (device memory,
  * >= codec_plan_device_bytes, 256-byte aligned, caller-owned, must outlive all
  * decode calls on this plan) on `stream` (a hipStream_t, may be NULL) and
- * remembers the pointer.  Call once per plan before decoding.
+ * remembers the pointer.  Call once per plan before decoding.  With
+ * schedule = 1 the kernels keep the queue's counters in this memory (zero after
+ * the upload, zero again after every completed launch): launches of one plan
+ * must not overlap, and a launch that was aborted leaves them undefined (upload
+ * again).
  */
 int codec_plan_upload(codec_plan_t *plan, void *device_meta, size_t device_meta_bytes, void *stream);
 
