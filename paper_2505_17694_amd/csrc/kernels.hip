@@ -573,11 +573,12 @@ __device__ __forceinline__ void pin(float &x) { asm volatile("" : "+v"(x)); }
 // of a step come in opposite orders, for the two waves of a SIMD.  Waves without rows only help moving
 // blocks.  All eight waves run the same barriers.
 //
-// STRIDE = 1: a live wave takes every block (tasks of more than 128 rows: eight row groups).
+// STRIDE = 1: a live wave takes every block (tasks of more than 128 rows, up to eight row groups; and
+// short slices of any task, see run_dense32).
 // STRIDE = 2: tasks of at most 128 rows have at most four row groups; waves w and w+4 (one SIMD) share
 // group w, the first takes the even blocks, the second the odd ones, and their two states are merged
 // through LDS when the slice is done.  An interval then covers two blocks.  Without the split a SIMD
-// would hold a single computing wave, whose matrix and vector work cannot overlap.
+// would hold a single computing wave and the other one would idle.
 enum { kHelper = 0, kMatrixFirst = 1, kVectorFirst = 2 };
 
 // One wave's share of a dense task: task rows row0 .. row0+31 (none for a helper).
