@@ -422,13 +422,21 @@ int build_plan(const codec_tree &tree, const codec_head_config &head,
 
     // ---- grid search over slice counts, evaluated by the greedy schedule ---------------------
     std::vector<Sub> sub;
+    struct Sliced { int32_t b = -1; Slicing s{}; int64_t c_full = 0, c_last = 0; };
+    std::vector<Sliced> sliced(J);          // the search changes one node at a time: keep the others' costs
     auto expand = [&]() {
         sub.clear();
         for (size_t j = 0; j < J; ++j) {
             const codec_item &it = p.items[j];
-            const Slicing s = slice_node(it.len, it.b, align);
-            const int64_t c_full = s.count > 1 ? table->estimate(it.rows, s.length) : 0;
-            const int64_t c_last = table->estimate(it.rows, s.last);
+            Sliced &k = sliced[j];
+            if (k.b != it.b) {
+                k.b = it.b;
+                k.s = slice_node(it.len, it.b, align);
+                k.c_full = k.s.count > 1 ? table->estimate(it.rows, k.s.length) : 0;
+                k.c_last = table->estimate(it.rows, k.s.last);
+            }
+            const Slicing &s = k.s;
+            const int64_t c_full = k.c_full, c_last = k.c_last;
             for (int32_t c = 0; c < s.count; ++c) {
                 const bool last = c == s.count - 1;
                 sub.push_back({last ? c_last : c_full, int32_t(j), c, c * s.length, last ? s.last : s.length});
