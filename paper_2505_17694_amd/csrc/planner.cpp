@@ -235,17 +235,17 @@ const CostTable &builtin_cost_table(bool wide)
     static const CostTable narrow_table = {
         {1, 16},
         {32, 128, 512, 2048, 8192, 32768},
-        {1220, 5779, 22137, 90108, 365032, 1454270,
-         2740, 7719, 25177, 101027, 375971, 1466928}};
+        {1400, 5919, 22457, 90230, 363960, 1449535,
+         2939, 7539, 24677, 100789, 376977, 1461894}};
     static const CostTable wide_table = {
         {1, 16, 32, 64, 128, 256},
         {32, 128, 512, 2048, 8192, 32768},
-        {180, 2540, 11139, 46154, 181596, 728385,
-         460, 3500, 10918, 48234, 185816, 733524,
-         3540, 6919, 17177, 49093, 180657, 682750,
-         5199, 8479, 19997, 52593, 188355, 696069,
-         8339, 11338, 23177, 55793, 207393, 803094,
-         10978, 16138, 29736, 75170, 325797, 1196182}};
+        {220, 2559, 11159, 46395, 181640, 727736,
+         559, 3140, 11679, 48754, 185579, 732795,
+         3660, 6959, 16439, 48714, 177419, 684020,
+         5119, 8299, 18618, 52654, 189138, 695999,
+         8339, 10858, 22178, 53614, 201436, 821064,
+         11439, 16439, 28236, 71011, 315323, 1105291}};
     return wide ? wide_table : narrow_table;
 }
 
