@@ -101,12 +101,12 @@ typedef struct {
                                >= group; 0 = 256.  Larger query sets are cut into row tiles.       */
     int32_t share;          /* 1 = prefix-shared plan; 0 = flat baseline: every request gets its
                                own tasks for every node on its path, nothing shared across requests;
-                               2 = whichever of three plans has the lowest estimated makespan: the
-                               prefix-shared plan with row tiles of max_rows, the prefix-shared plan
-                               with row tiles of at most 16 rows (a query-dimension split, b_q > 1
-                               in the terms of Sec. 5.1, that fits the narrow kernel variant) and
-                               the flat plan; ties go to the earlier of the three.  The plan view
-                               reports the share and max_rows that won.                              */
+                               2 = whichever of up to four plans has the lowest estimated makespan:
+                               the prefix-shared plan with row tiles of max_rows, with row tiles of
+                               half that (if more than 16 rows), with row tiles of at most 16 rows
+                               (query-dimension splits, b_q > 1 in the terms of Sec. 5.1; the last
+                               one fits the narrow kernel variant) and the flat plan; ties go to the
+                               earlier one.  The plan view reports the share and max_rows that won. */
     const codec_cost_table *cost;   /* NULL = built-in table of the kernel variant the plan needs     */
     int32_t fixed_slices;   /* 0 = the paper's adaptive division (Eq. 4-5 and the grid search);
                                n > 0 = the naive strategy it is compared with (Sec. 7, impact of

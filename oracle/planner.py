@@ -299,12 +299,16 @@ def plan_best(parent, node_len, req_node, group: int, align: int, max_rows: int,
               num_slots_of) -> Dict:
     """share = 2 of the library: the candidate with the lowest estimated makespan, ties to the earlier.
 
-    Candidates: the prefix-shared plan with row tiles of ``max_rows``; the prefix-shared plan with row
-    tiles of at most 16 rows (a query-dimension split, b_q > 1 in the terms of Sec. 5.1); the flat plan.
+    Candidates: the prefix-shared plan with row tiles of ``max_rows``; with row tiles of half that (if
+    more than 16 rows); with row tiles of at most 16 rows (query-dimension splits, b_q > 1 in the terms
+    of Sec. 5.1); the flat plan.
     ``tables`` = {"narrow": .., "wide": ..} and ``num_slots_of(wide)`` give each candidate the table and
     slot count of the kernel variant its widest task selects, as the library does.
     """
     cands = [(True, max_rows)]
+    half = max_rows // 2 // group * group
+    if half > 16 and half >= group:
+        cands.append((True, half))
     small = 16 // group * group if group <= 16 else 0
     if small >= group and small < max_rows:
         cands.append((True, small))

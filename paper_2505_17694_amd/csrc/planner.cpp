@@ -559,10 +559,17 @@ int build_best_plan(const codec_tree &tree, const codec_head_config &head,
     if (head.num_kv_heads < 1 || head.num_q_heads < 1 || head.num_q_heads % head.num_kv_heads != 0)
         return CODEC_ERR_INVALID_ARGUMENT;
     const int32_t group = head.num_q_heads / head.num_kv_heads;
-    codec_plan_options cand[3] = {opt, opt, opt};
+    codec_plan_options cand[4] = {opt, opt, opt, opt};
     int n = 0;
     cand[n].share = 1;                                          // row tiles of max_rows (default 256)
     ++n;
+    const int32_t widest = opt.max_rows > 0 ? opt.max_rows : 256;
+    const int32_t half = widest / 2 / group * group;            // row tiles of half that (still dense tasks)
+    if (half > 16 && half >= group) {
+        cand[n].share = 1;
+        cand[n].max_rows = half;
+        ++n;
+    }
     const int32_t small = group <= 16 ? 16 / group * group : 0; // row tiles of at most 16 rows
     if (small >= group && (opt.max_rows == 0 || small < opt.max_rows)) {
         cand[n].share = 1;

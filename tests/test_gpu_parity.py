@@ -214,7 +214,7 @@ def test_plan_carried_over_to_grown_lengths(share, schedule):
     pa.close()
 
 
-def test_best_of_three_plans_on_the_gpu():
+def test_best_candidate_plan_on_the_gpu():
     """share = 2 on a forest where private leaves dominate and on one where the shared root does."""
     low = two_level_forest(960, [2900, 3100, 2800, 3000])
     high = two_level_forest(6000, [40] * 24)

@@ -329,7 +329,7 @@ def _check_invariants_of_division(f, p, group, m, align):
     assert max(loads) == p["makespan"]
 
 
-def test_best_of_three_plans_hand_worked():
+def test_best_candidate_plan_hand_worked():
     """Two requests under a 100-token root, 100-token leaves, group 8, 2 slots, cost = rows * tokens.
 
     Shared plan (16-row tiles cover both requests): root 16 * 100 = 1600, leaves 800 each -> loads
@@ -344,6 +344,23 @@ def test_best_of_three_plans_hand_worked():
         p = P.plan_best(f.parent, f.node_len, f.req_node, 8, 100, 16, {"narrow": table, "wide": table},
                         lambda wide: 2)
         assert (p["share"], p["makespan"]) == (want_share, want_ms)
+
+
+def test_half_width_row_tiles_hand_worked():
+    """64 requests end at one 100-token node, group 1, row tiles of at most 64, cost = rows * tokens.
+
+    On 2 slots: one 64-row task costs 6400 and leaves a slot idle; two 32-row tiles cost 3200 each, one
+    per slot -> 3200; four 16-row tiles -> two per slot, 3200; the flat plan, 64 tasks of 100 -> 3200.
+    The three ties go to the earliest candidate, the 32-row tiles.  On 1 slot all four come to 6400
+    and the tie goes to the 64-row plan.
+    """
+    f = Forest(np.array([-1]), np.array([100]), np.zeros(64, dtype=np.int32))
+    prop = {"row_grid": [1, 65], "len_grid": [1, 101], "cost": [[1, 101], [65, 6565]]}          # rows * tokens
+    for slots, want_rows, want_ms in ((2, 32, 3200), (1, 64, 6400)):
+        p = P.plan_best(f.parent, f.node_len, f.req_node, 1, 100, 64, {"narrow": prop, "wide": prop},
+                        lambda wide: slots)
+        assert (p["share"], p["max_rows"], p["makespan"]) == (True, want_rows, want_ms)
+        assert len(p["tasks"]) == 64 // want_rows
 
 
 def test_slice_bound_slack_hand_worked():

@@ -194,7 +194,7 @@ def test_fixed_slice_count_matches_oracle(name, fixed):
     _compare(view, P.plan(f.parent, f.node_len, f.req_node, 4, m, align, max_rows, True, table, fixed_slices=fixed))
 
 
-# ---- share = 2: best of three candidate plans ------------------------------------------------------
+# ---- share = 2: best of the candidate plans ------------------------------------------------------
 
 BEST_CASES = {
     # heavy sharing: the 256-row plan wins
@@ -217,7 +217,7 @@ DEAR_WIDE = {"row_grid": [1, 16, 17, 256], "len_grid": [32, 65536],
 
 @pytest.mark.parametrize("table", ["builtin", "dear_wide"])
 @pytest.mark.parametrize("name", sorted(BEST_CASES))
-def test_best_of_three_plans_matches_oracle(name, table):
+def test_best_candidate_plan_matches_oracle(name, table):
     make, head = BEST_CASES[name]
     f = make()
     group = head.num_q_heads // head.num_kv_heads
@@ -277,6 +277,27 @@ def test_run_time_queue_entries(name, slots):
     m = v["num_slots"]
     if n_long < m and -(-short.count(True) // (m - n_long)) <= 4:
         assert len(off) - 1 <= m
+
+
+def test_half_width_row_tiles_match_oracle():
+    """share = 2 with an explicit max_rows: the candidate with row tiles of half that width exists and wins
+    where the oracle says so (the hand-worked case of the oracle's pins, through the library)."""
+    f = Forest(np.array([-1]), np.array([100]), np.zeros(64, dtype=np.int32))
+    head = HeadConfig(2, 2, 128, 0)
+    paged = build_paged_kv(f, head, seed=1)
+    prop = {"row_grid": [1, 65], "len_grid": [1, 101], "cost": [[1, 101], [65, 6565]]}
+    for slots, want_rows in ((2, 32), (1, 64)):
+        st, plan = C.codec_plan_create(f.parent, f.node_len, f.req_node, paged.node_page_off, paged.page_ids,
+                                       head.num_q_heads, head.num_kv_heads, head.head_dim, head.dtype,
+                                       head.page_size, head.scale, num_slots=slots, split_align=256,
+                                       max_rows=64, share=2, cost_table=_tuple(prop))
+        assert st == C.CODEC_OK
+        st, view = C.codec_plan_export(plan)
+        C.codec_plan_destroy(plan)
+        ref = P.plan_best(f.parent, f.node_len, f.req_node, 1, 256, 64, {"narrow": prop, "wide": prop},
+                          lambda wide: slots)
+        assert (view["share"], view["max_rows"]) == (1, want_rows) == (int(ref["share"]), ref["max_rows"])
+        _compare(view, ref)
 
 
 def test_schedule_option_is_checked():
