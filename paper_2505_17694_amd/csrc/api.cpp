@@ -217,9 +217,8 @@ int codec_partial_attention(const codec_plan_t *plan, const void *q, const void 
     pp.page_stride = layout->page_stride;
     pp.token_stride = layout->token_stride;
     pp.head_stride = layout->head_stride;
-    pp.tasks = reinterpret_cast<const codec::DevTask *>(meta + L.tasks);
+    pp.slot_recs = reinterpret_cast<const codec::DevTask *>(meta + L.slot_recs);
     pp.slot_off = reinterpret_cast<const int32_t *>(meta + L.slot_off);
-    pp.slot_tasks = reinterpret_cast<const int32_t *>(meta + L.slot_tasks);
     pp.node_q = reinterpret_cast<const int32_t *>(meta + L.node_q);
     pp.page_ids = reinterpret_cast<const int32_t *>(meta + L.page_ids);
     pp.part_o = reinterpret_cast<float *>(ws);
@@ -234,7 +233,7 @@ int codec_partial_attention(const codec_plan_t *plan, const void *q, const void 
     pp.num_slots = d.num_slots;
     if (d.schedule == 1) {
         pp.queue_off = reinterpret_cast<const int32_t *>(meta + L.queue_off);
-        pp.queue_tasks = reinterpret_cast<const int32_t *>(meta + L.queue_tasks);
+        pp.queue_recs = reinterpret_cast<const codec::DevTask *>(meta + L.queue_recs);
         pp.counters = reinterpret_cast<int32_t *>(const_cast<char *>(meta) + L.counters);
         pp.num_entries = int32_t(d.queue_off.size()) - 1;
     }

@@ -335,7 +335,7 @@ __device__ __forceinline__ void gather_q(const PacParams &P, const DevTask &t, i
         const bool live = row < rows;
         const int qi = live ? row / P.group : 0;
         const int hj = live ? row - qi * P.group : 0;
-        const int req = P.node_q[t.q_off + qi];
+        const int req = t.single_req >= 0 ? t.single_req : P.node_q[t.q_off + qi];
         const char *qp = static_cast<const char *>(P.q)
                          + (int64_t(req) * P.h_q + int64_t(head) * P.group + hj) * (kHeadDim * 2) + grp * 16;
 #pragma unroll
@@ -606,7 +606,7 @@ __device__ __forceinline__ void dense32_wave(const PacParams &P, const DevTask &
         const bool live = row < rows;
         const int qi = live ? row / P.group : 0;
         const int hj = live ? row - qi * P.group : 0;
-        const int req = P.node_q[t.q_off + qi];
+        const int req = t.single_req >= 0 ? t.single_req : P.node_q[t.q_off + qi];
         const char *qp = static_cast<const char *>(P.q)
                          + (int64_t(req) * P.h_q + int64_t(head) * P.group + hj) * (kHeadDim * 2) + kg * 16;
 #pragma unroll
@@ -998,18 +998,18 @@ __global__ void __launch_bounds__(WIDE ? kWideWaves * 64 : kNarrowWaves * 64, 2)
     const int head = blockIdx.x % P.h_kv;
     const int slot = blockIdx.x / P.h_kv;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    // Runs the tasks list[t0 .. t1).  Tasks of more than 16 rows take the dense path (wide variant
+    // Runs the task records recs[t0 .. t1).  Tasks of more than 16 rows take the dense path (wide variant
     // only).  Tasks of at most 16 rows take the stream path, as a rule with all waves of the workgroup
     // as one team.  Runs of two or more short ones are handed out one wave each through a counter in
     // LDS: the latencies of a short task (descriptor, query rows, page ids, first blocks, merge of a
     // team) then overlap with the other tasks' instead of adding up.  In a slot's list the plan marks
     // such runs (they are neighbours there, the list being sorted by cost); an entry of the run-time
     // queue with several tasks is one such run.
-    auto run_tasks = [&](const int32_t *list, int t0, int t1, bool marked) __attribute__((always_inline)) {
+    auto run_tasks = [&](const DevTask *recs, int t0, int t1, bool marked) __attribute__((always_inline)) {
         int i = t0;
 #pragma unroll 1
         while (i < t1) {
-            const DevTask t = P.tasks[list[i]];
+            const DevTask t = recs[i];
             const int n = marked ? t.solo_run : t1 - i;
             if (n >= 2) {
                 int *next = reinterpret_cast<int *>(lds);
@@ -1021,7 +1021,7 @@ __global__ void __launch_bounds__(WIDE ? kWideWaves * 64 : kNarrowWaves * 64, 2)
                     if ((threadIdx.x & 63) == 0) k = atomicAdd(next, 1);
                     k = __builtin_amdgcn_readfirstlane(k);
                     if (k >= n) break;
-                    const DevTask mine = P.tasks[list[i + k]];
+                    const DevTask mine = recs[i + k];
                     if (mine.read_once) run_stream<DT, true, 1, 1>(P, mine, head, lds, 0);
                     else                run_stream<DT, false, 1, 1>(P, mine, head, lds, 0);
                 }
@@ -1045,7 +1045,7 @@ __global__ void __launch_bounds__(WIDE ? kWideWaves * 64 : kNarrowWaves * 64, 2)
     // task's block copies from overwriting it before everyone has read it.
     const bool queued = P.queue_off != nullptr;
     const bool fetching = queued && P.num_entries > P.num_slots;        // else: an entry per workgroup at most
-    const int32_t *list = queued ? P.queue_tasks : P.slot_tasks;
+    const DevTask *recs = queued ? P.queue_recs : P.slot_recs;
     const int32_t *off = queued ? P.queue_off : P.slot_off;
     const int limit = queued ? P.num_entries : slot + 1;
     int32_t *taken = P.counters + 2 * head, *finished = taken + 1;
@@ -1053,7 +1053,7 @@ __global__ void __launch_bounds__(WIDE ? kWideWaves * 64 : kNarrowWaves * 64, 2)
     int e = slot;
 #pragma unroll 1
     while (e < limit) {
-        run_tasks(list, off[e], off[e + 1], !queued);
+        run_tasks(recs, off[e], off[e + 1], !queued);
         if (!fetching) break;
         // taken when the workgroup is free, not ahead of time: an entry reserved early would wait for
         // the end of a long task while other workgroups idle

@@ -101,9 +101,8 @@ void build_device_image(PlanData &p)
     DevLayout &L = p.layout;
     size_t off = 0;
     auto place = [&](size_t bytes) { size_t at = off; off = align_up(off + bytes, 256); return at; };
-    L.tasks = place(p.tasks.size() * sizeof(DevTask));
+    L.slot_recs = place(p.slot_tasks.size() * sizeof(DevTask));
     L.slot_off = place(p.slot_off.size() * 4);
-    L.slot_tasks = place(p.slot_tasks.size() * 4);
     L.node_q = place(p.node_q.size() * 4);
     L.page_ids = place(p.page_ids.size() * 4);
     L.req_part_off = place(p.req_part_off.size() * 4);
@@ -150,11 +149,10 @@ void build_device_image(PlanData &p)
         }
     }
     L.queue_off = place(p.queue_off.size() * 4);
-    L.queue_tasks = place(p.queue_tasks.size() * 4);
+    L.queue_recs = place(p.queue_tasks.size() * sizeof(DevTask));
     L.counters = place(size_t(p.head.num_kv_heads) * 2 * 4);               // zero: nothing taken, nobody done
     L.total = std::max<size_t>(off, 256);
     p.blob.assign(L.total, 0);
-    DevTask *dt = reinterpret_cast<DevTask *>(p.blob.data() + L.tasks);
     // Streaming hint (kernels.hip): a task reads its slice with it when no other task reads that slice
     // (its node has one item: one row tile, or one request of a flat plan) and the plan as a whole reads
     // little twice (tokens read <= 1.25 x tokens held).  Measured on MI355X: plans that re-read a lot,
@@ -166,34 +164,40 @@ void build_device_image(PlanData &p)
     for (const codec_task &t : p.tasks) tokens_read += t.kv_len;
     for (int32_t len : p.node_len) tokens_held += len;
     const bool streaming_plan = 4 * tokens_read <= 5 * tokens_held;
-    for (size_t i = 0; i < p.tasks.size(); ++i) {
+    auto record = [&](int32_t i) {
         const codec_task &t = p.tasks[i];
-        dt[i].read_once = streaming_plan && readers[t.node] == 1;
-        dt[i].page_off = p.node_page_off[t.node] + t.kv_begin / ps;
-        dt[i].kv_len = t.kv_len;
-        dt[i].q_off = t.q_off;
-        dt[i].n_req = t.n_req;
-        dt[i].part_row_base = t.part_row_base;
-    }
+        DevTask r{};
+        r.page_off = p.node_page_off[t.node] + t.kv_begin / ps;
+        r.kv_len = t.kv_len;
+        r.q_off = t.q_off;
+        r.n_req = t.n_req;
+        r.part_row_base = t.part_row_base;
+        r.solo_run = 0;
+        r.read_once = streaming_plan && readers[t.node] == 1;
+        r.single_req = t.n_req == 1 ? p.node_q[t.q_off] : -1;
+        return r;
+    };
+    DevTask *by_slot = reinterpret_cast<DevTask *>(p.blob.data() + L.slot_recs);
     for (int32_t sl = 0; sl < p.num_slots; ++sl) {                      // runs of single-wave tasks, back to front
         int32_t run = 0;
         for (int32_t i = p.slot_off[sl + 1] - 1; i >= p.slot_off[sl]; --i) {
-            const codec_task &t = p.tasks[p.slot_tasks[i]];
-            run = (t.n_req * p.group <= kSoloMaxRows && t.kv_len <= kSoloMaxLen) ? run + 1 : 0;
-            dt[p.slot_tasks[i]].solo_run = run;
+            by_slot[i] = record(p.slot_tasks[i]);
+            const bool is_short = by_slot[i].n_req * p.group <= kSoloMaxRows && by_slot[i].kv_len <= kSoloMaxLen;
+            run = is_short ? run + 1 : 0;
+            by_slot[i].solo_run = run;
         }
     }
+    DevTask *by_entry = reinterpret_cast<DevTask *>(p.blob.data() + L.queue_recs);
+    for (size_t i = 0; i < p.queue_tasks.size(); ++i) by_entry[i] = record(p.queue_tasks[i]);
     auto put = [&](size_t at, const std::vector<int32_t> &v) {
         if (!v.empty()) std::memcpy(p.blob.data() + at, v.data(), v.size() * 4);
     };
     put(L.slot_off, p.slot_off);
-    put(L.slot_tasks, p.slot_tasks);
     put(L.node_q, p.node_q);
     put(L.page_ids, p.page_ids);
     put(L.req_part_off, p.req_part_off);
     put(L.req_part, p.req_part);
     put(L.queue_off, p.queue_off);
-    put(L.queue_tasks, p.queue_tasks);
 }
 
 }  // namespace

@@ -27,7 +27,10 @@ constexpr int32_t kSoloMaxLen = 1024;
 // more make the last entries long).
 constexpr int32_t kQueueBundle = 4;
 
-// Task record as the kernels read it (32 bytes).
+// Task record as the kernels read it (32 bytes).  The device image holds the records twice: in the
+// order of the slots' lists and in the order of the run-time queue, so that a workgroup reads record
+// i of its list directly instead of through an index (a task's start is a chain of dependent reads,
+// each of which costs microseconds when the memory system is busy).
 struct DevTask {
     int32_t page_off;       // index into the device copy of page_ids of the slice's first page
     int32_t kv_len;         // tokens in the slice
@@ -36,13 +39,13 @@ struct DevTask {
     int32_t part_row_base;  // first partial row
     int32_t solo_run;       // number of consecutive single-wave tasks in the slot's list from this one on
     int32_t read_once;      // 1 = no other task reads this KV slice (its node has a single row tile)
-    int32_t reserved;
+    int32_t single_req;     // n_req == 1: the request itself (saves the read of node_q); else -1
 };
 
 // Byte offsets of the arrays inside the device metadata blob.
 struct DevLayout {
-    size_t tasks = 0, slot_off = 0, slot_tasks = 0, node_q = 0, page_ids = 0,
-           req_part_off = 0, req_part = 0, queue_off = 0, queue_tasks = 0, counters = 0, total = 0;
+    size_t slot_recs = 0, slot_off = 0, node_q = 0, page_ids = 0,
+           req_part_off = 0, req_part = 0, queue_off = 0, queue_recs = 0, counters = 0, total = 0;
 };
 
 struct PlanData {
