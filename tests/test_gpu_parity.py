@@ -14,7 +14,7 @@ import torch
 from oracle import attention as A
 from workloads import (HeadConfig, Forest, make_workload, make_small_config, make_config,
                        two_level_forest, three_level_forest, unshared_forest, random_forest,
-                       concat_forests, degenerate_forest, DTYPE_FP16, DTYPE_BF16)
+                       concat_forests, degenerate_forest, draft_tree_forest, DTYPE_FP16, DTYPE_BF16)
 
 pytestmark = pytest.mark.gpu
 
@@ -327,6 +327,20 @@ def test_random_forests_heads_and_plan_options(seed):
     if opts["max_rows"] and opts["max_rows"] < hq // hkv:
         opts["max_rows"] = 0
     check(w, share=int(rng.choice([1, 1, 0, 2])), **opts)
+
+
+@pytest.mark.parametrize("drafted,hq,hkv,share,schedule", [
+    (1, 8, 2, 1, 0), (7, 32, 8, 1, 0), (24, 32, 8, 1, 1), (24, 8, 8, 2, 0), (40, 16, 1, 1, 0), (12, 32, 8, 0, 0)])
+def test_drafted_token_trees(drafted, hq, hkv, share, schedule):
+    """Multi-token decoding: verification of tree-structured drafts.  Every drafted token is a node
+    of one token, a request ends at every one of them and at the context they hang from, so what a
+    query may see is its path (the visibility of the streaming softmax of Sec. 4.2 reduces to the
+    tree).  Inner nodes carry requests, nodes are as short as they get, and many requests share
+    the one-token nodes near the context."""
+    f = draft_tree_forest(300, [900, 33, 2100, 260], drafted, seed=70 + drafted)
+    assert f.num_requests == 4 * (drafted + 1)
+    w = make_workload(f"drafted{drafted}", f, HeadConfig(hq, hkv, 128, DTYPE_BF16), seed=71 + drafted, poison=True)
+    check(w, share=share, schedule=schedule)
 
 
 def _queue_cases():

@@ -13,8 +13,8 @@ import paper_2505_17694_amd as C
 from oracle import planner as P
 from golden_tables import load_table2
 from workloads import (two_level_forest, three_level_forest, random_forest, unshared_forest,
-                       concat_forests, degenerate_forest, full_kary_forest, Forest, HeadConfig,
-                       build_paged_kv)
+                       concat_forests, degenerate_forest, full_kary_forest, draft_tree_forest, Forest,
+                       HeadConfig, build_paged_kv)
 from workloads.configs import config_forest, config_head, CONFIG_NAMES
 
 TABLE2 = load_table2()
@@ -80,6 +80,7 @@ FORESTS = {
     "mixed": lambda: concat_forests(two_level_forest(30000, [100] * 9), unshared_forest([7000, 8000, 50])),
     "degenerate": lambda: degenerate_forest(6, 3000, 200),
     "binary": lambda: full_kary_forest(2, 5, lambda lvl: 4000 // lvl),
+    "drafted": lambda: draft_tree_forest(700, [3000, 45, 1200], 9, seed=4),
     "inner_request": lambda: Forest(np.array([-1, 0, 0, -1]), np.array([300, 40, 50, 77]), np.array([1, 0, 1])),
 }
 

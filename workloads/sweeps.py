@@ -12,15 +12,20 @@ Forests only; tensors come from ``make_workload`` like every other input.  Each 
                tokens each ("the same workload" over different shapes)
 * ``ablation`` a full binary tree (6 levels) and a degenerate tree (8 levels) with 204800-token (200k)
                contexts, for the tree on/off x division on/off grid
+* ``draft``    verification of drafted token trees (multi-token decoding): 16 sequences of 8192 tokens
+               under a shared 2048-token prompt, each with a random tree of 0 .. 64 one-token draft nodes
+               and one request per draft token; not one of the paper's sweeps, its motivation names the
+               use case
 """
 from __future__ import annotations
 
 from typing import List, Tuple
 
-from .trees import Forest, two_level_forest, full_kary_forest, degenerate_forest, unshared_forest
+from .trees import (Forest, two_level_forest, full_kary_forest, degenerate_forest, unshared_forest,
+                    draft_tree_forest)
 from .tensors import HeadConfig, DTYPE_BF16
 
-SWEEP_NAMES = ["seqlen", "batch", "depth", "ratio", "shape", "ablation"]
+SWEEP_NAMES = ["seqlen", "batch", "depth", "ratio", "shape", "ablation", "draft"]
 SWEEP_SEED = 2000
 
 
@@ -57,4 +62,8 @@ def sweep_points(name: str) -> List[Tuple[str, Forest]]:
     if name == "ablation":
         return [("balanced", full_kary_forest(2, 6, lambda lvl: _r16(204800 / 6))),
                 ("degenerate", degenerate_forest(8, _r16(204800 / 8), _r16(204800 / 8)))]
+    if name == "draft":
+        # verification of drafted token trees (the speculative-decoding use of prefix sharing named
+        # in the motivation): 16 sequences of 8192 tokens under a prompt of 2048
+        return [(f"drafted={t}", draft_tree_forest(2048, [8192] * 16, t, SWEEP_SEED + t)) for t in (0, 4, 16, 64)]
     raise KeyError(name)

@@ -154,6 +154,39 @@ def random_forest(num_leaves: int, max_depth: int, poisson_mean: float,
     return Forest(np.array(parent), lens.astype(np.int32), np.array(req_node))
 
 
+def draft_tree_forest(prompt_len: int, context_lens: Sequence[int], draft_tokens: int, seed: int) -> Forest:
+    """Verification step of tree-structured speculative decoding (multi-token decoding).
+
+    A prompt of ``prompt_len`` tokens is shared by all sequences (0: none); sequence i has
+    ``context_lens[i]`` tokens of its own; on top of each sits a seeded random tree of
+    ``draft_tokens`` drafted tokens, every one a node of length 1 whose parent is the token it was
+    drafted after (an earlier draft token of the sequence, or the sequence's context).  A query
+    sees exactly the tokens on its path, so which drafted tokens a query may attend to is given by
+    the tree itself.  There is one request per context node (the last accepted token) and one per
+    draft token: requests end at internal nodes as well as at leaves.
+    """
+    rng = np.random.Generator(np.random.PCG64(seed))
+    parent: List[int] = []
+    node_len: List[int] = []
+    req_node: List[int] = []
+    top = -1
+    if prompt_len > 0:
+        parent.append(-1); node_len.append(prompt_len); top = 0
+    for ctx_len in context_lens:
+        parent.append(top); node_len.append(int(ctx_len))
+        ctx = len(parent) - 1
+        req_node.append(ctx)
+        drafted = [ctx]
+        for _ in range(draft_tokens):
+            # half of the tokens extend the newest branch, the others start a sibling branch
+            # somewhere in the tree drafted so far
+            after = drafted[-1] if rng.random() < 0.5 else drafted[int(rng.integers(len(drafted)))]
+            parent.append(after); node_len.append(1)
+            drafted.append(len(parent) - 1)
+            req_node.append(len(parent) - 1)
+    return Forest(np.array(parent), np.array(node_len), np.array(req_node))
+
+
 def concat_forests(a: Forest, b: Forest) -> Forest:
     """Both forests under one virtual root; b's node ids are shifted by a.num_nodes."""
     shift = a.num_nodes
