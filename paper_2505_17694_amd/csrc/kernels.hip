@@ -92,6 +92,14 @@ __device__ __forceinline__ u32x4 ld16_once(const char *p)
     return __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(p));
 }
 
+// A 16-byte load the compiler does not know is pending: the caller waits for it itself (a vector-memory
+// wait that names dst, see wait_pending) and must not touch dst before.  Used where loads are queued
+// between asynchronous copies: a wait placed by the compiler would count those copies as its own.
+__device__ __forceinline__ void ld16_pending(u32x4 &dst, const char *p)
+{
+    asm volatile("global_load_dwordx4 %0, %1, off" : "=v"(dst) : "v"(p) : "memory");
+}
+
 // The lane index as a value the optimiser cannot trace back to the thread id.  Each task path derives
 // its lane constants (operand addresses, row and channel positions) from it, which keeps them inside
 // the path: hoisted out of the task loop they would stay live across all paths and cost the dense
@@ -568,6 +576,7 @@ __device__ __forceinline__ f32x16 mfma32(u32x4 a, u32x4 b, f32x16 c)
 // is only used after the next barrier below that barrier).
 __device__ __forceinline__ void pin(u32x4 &x) { asm volatile("" : "+v"(x)); }
 __device__ __forceinline__ void pin(float &x) { asm volatile("" : "+v"(x)); }
+__device__ __forceinline__ void pin(int &x) { asm volatile("" : "+v"(x)); }
 
 // Roles of a wave in a dense task.  A wave with rows owns 32 of them; in the two live roles the halves
 // of a step come in opposite orders, for the two waves of a SIMD.  Waves without rows only help moving
@@ -602,24 +611,11 @@ __device__ __forceinline__ void dense32_wave(const PacParams &P, const DevTask &
     float m = -INFINITY;    // reference, log2 units, integer-valued (same in the two lanes of a row)
     float l = 0.f;          // this lane's share of the row sum
     if constexpr (LIVE) {
-        const int row = row0 + l32;
-        const bool live = row < rows;
-        const int qi = live ? row / P.group : 0;
-        const int hj = live ? row - qi * P.group : 0;
-        const int req = t.single_req >= 0 ? t.single_req : P.node_q[t.q_off + qi];
-        const char *qp = static_cast<const char *>(P.q)
-                         + (int64_t(req) * P.h_q + int64_t(head) * P.group + hj) * (kHeadDim * 2) + kg * 16;
-#pragma unroll
-        for (int ks = 0; ks < 8; ++ks) qb[ks] = live ? ld16(qp + ks * 32) : u32x4{0u, 0u, 0u, 0u};
 #pragma unroll
         for (int ct = 0; ct < 4; ++ct)
 #pragma unroll
             for (int r = 0; r < 16; ++r) o[ct][r] = 0.f;
     }
-    // every load the compiler knows about is complete before the first asynchronous copy is issued, so
-    // that it places no vector-memory wait of its own inside the loop (such a wait would also drain
-    // the copies in flight)
-    __builtin_amdgcn_s_waitcnt(0x0F70);
     const SliceCtx c = make_ctx(P, t, head);
 
     // Asynchronous copies.  Wave w moves tokens 4w .. 4w+3 of every block, 1 KB of K and 1 KB of V;
@@ -797,19 +793,53 @@ __device__ __forceinline__ void dense32_wave(const PacParams &P, const DevTask &
     // follow, the wait is for everything.
     const int nblk = (t.kv_len + 31) >> 5;
     const int nint = (nblk + STRIDE - 1) / STRIDE - 1;                  // the same for every wave
+    // Start of the task.  What the first matrix instruction waits for is a chain of dependent reads:
+    // page ids and the rows' requests, then the first blocks and the query rows.  The two reads of a
+    // stage are issued together; the query rows (32 rows of 32 bytes per instruction, the slowest
+    // requests to issue) are queued behind the copies of the first 2S blocks only, the other copies
+    // of the ring behind them.
     {
         int pg[RING];
 #pragma unroll
         for (int d = 0; d < RING; ++d) pg[d] = page_issue(d < nblk ? d : 0);
+        const char *qp = nullptr;
+        bool live = false;
+        if constexpr (LIVE) {
+            const int row = row0 + l32;
+            live = row < rows;
+            const int qi = live ? row / P.group : row0 / P.group;       // a dead row reads row0's
+            const int hj = live ? row - qi * P.group : row0 - qi * P.group;
+            int req = t.single_req >= 0 ? t.single_req : P.node_q[t.q_off + qi];
+            pin(req);                           // the wait for it stands here, ahead of the copies
+            qp = static_cast<const char *>(P.q)
+                 + (int64_t(req) * P.h_q + int64_t(head) * P.group + hj) * (kHeadDim * 2) + kg * 16;
+        }
 #pragma unroll
-        for (int d = 0; d < RING; ++d)
+        for (int d = 0; d < 2 * STRIDE; ++d)
             if (d < nblk) dma_block(d, pg[d]);
+        if constexpr (LIVE) {
+#pragma unroll
+            for (int ks = 0; ks < 8; ++ks) ld16_pending(qb[ks], qp + ks * 32);
+        }
+#pragma unroll
+        for (int d = 2 * STRIDE; d < RING; ++d)
+            if (d < nblk) dma_block(d, pg[d]);
+        // loads complete in order: with at most the copies of blocks 2S .. RING-1 outstanding, blocks
+        // 0 .. 2S-1 have landed and the query rows are in their registers
+        if (nblk >= RING) __builtin_amdgcn_s_waitcnt(vmcnt_imm(2 * (RING - 2 * STRIDE)));
+        else               __builtin_amdgcn_s_waitcnt(0x0F70);
+        if constexpr (LIVE) {
+            // from here on the query registers may be read; one statement on every path, so that no
+            // copy of a register still being loaded is made where paths join
+            asm volatile("; query rows ready" : "+v"(qb[0]), "+v"(qb[1]), "+v"(qb[2]), "+v"(qb[3]), "+v"(qb[4]), "+v"(qb[5]),
+                              "+v"(qb[6]), "+v"(qb[7]));
+#pragma unroll
+            for (int ks = 0; ks < 8; ++ks) qb[ks] = live ? qb[ks] : u32x4{0u, 0u, 0u, 0u};
+        }
     }
     int pg_next[STRIDE];                                                // pages of the blocks interval 0 requests
 #pragma unroll
     for (int u = 0; u < STRIDE; ++u) pg_next[u] = page_issue(RING + u);
-    if (nblk >= RING) __builtin_amdgcn_s_waitcnt(vmcnt_imm(2 * (RING - 2 * STRIDE)));    // blocks 0 .. 2S-1 have landed
-    else               __builtin_amdgcn_s_waitcnt(0x0F70);
     __syncthreads();
 
     // more: blocks S*j+8 .. S*j+8+S-1 all exist
@@ -936,26 +966,42 @@ __device__ __forceinline__ void dense32_wave(const PacParams &P, const DevTask &
         }
     }
 
+    // The partial rows go out through LDS: in registers a lane holds 16-byte pieces of one row, and a
+    // store instruction of the wave would touch 32 rows with 32 bytes each (measured: 3.1 us to issue
+    // the 128 KB of a 256-row task, the address unit taking one such piece about every two cycles).
+    // Each wave writes its 32 x 128 floats into an area of its own (rows 528 bytes apart: 16 lanes
+    // then cover all banks) and reads them back row by row: a store instruction covers two whole rows,
+    // 1 KB of consecutive memory.  With two waves per row group the area is the one the hand-over
+    // above has just used, and only its own wave touches it from here on.
+    constexpr int kStageRow = 528, kStageWave = 66 * 64 * 4;
+    static_assert(32 * kStageRow <= kStageWave && 8 * kStageWave <= kRingBytes, "staging areas fit the ring");
     if constexpr (ROLE == kMatrixFirst || (STRIDE == 1 && LIVE)) {
         l += __shfl_xor(l, 32);
-        const int row = row0 + l32;
-        if (row < rows) {
-            const int64_t prow = int64_t(head) * P.part_rows + t.part_row_base + row;
-            float *po = P.part_o + prow * kHeadDim + kg * 4;
+        typedef f32x4 __attribute__((address_space(3))) *lds_f32x4_ptr;
+        const uint32_t area = lds_base + uint32_t(STRIDE == 2 ? (wave & 3) : wave) * kStageWave;
+        const uint32_t put = area + uint32_t(l32) * kStageRow + uint32_t(kg) * 16;
 #pragma unroll
-            for (int ct = 0; ct < 4; ++ct)
+        for (int ct = 0; ct < 4; ++ct)
 #pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                    const f32x4 x4 = {o[ct][4 * q], o[ct][4 * q + 1], o[ct][4 * q + 2], o[ct][4 * q + 3]};
-                    *reinterpret_cast<f32x4 *>(po + ct * 32 + q * 8) = x4;
-                }
-            if (kg == 0) {
-                float2 ml = {m, l};
-                *reinterpret_cast<float2 *>(P.part_ml + prow * 2) = ml;
+            for (int q = 0; q < 4; ++q) {
+                const f32x4 x4 = {o[ct][4 * q], o[ct][4 * q + 1], o[ct][4 * q + 2], o[ct][4 * q + 3]};
+                *reinterpret_cast<lds_f32x4_ptr>(uintptr_t(put + ct * 128 + q * 32)) = x4;
             }
+        const int row = row0 + l32;
+        if (row < rows && kg == 0) {
+            const int64_t prow = int64_t(head) * P.part_rows + t.part_row_base + row;
+            float2 ml = {m, l};
+            *reinterpret_cast<float2 *>(P.part_ml + prow * 2) = ml;
+        }
+        const uint32_t get = area + uint32_t(kg) * kStageRow + uint32_t(l32) * 16;
+        float *po = P.part_o + (int64_t(head) * P.part_rows + t.part_row_base + row0 + kg) * kHeadDim + l32 * 4;
+#pragma unroll
+        for (int j = 0; j < 16; ++j) {
+            const f32x4 x4 = *reinterpret_cast<lds_f32x4_ptr>(uintptr_t(get + j * 2 * kStageRow));
+            if (row0 + 2 * j + kg < rows) *reinterpret_cast<f32x4 *>(po + j * 2 * kHeadDim) = x4;
         }
     }
-    if constexpr (STRIDE == 2) __syncthreads();     // the hand-over area is free for the next task
+    __syncthreads();                        // the staging areas (and the hand-over area) are free for the next task
 }
 
 // Dense task.  More than 128 rows: wave w owns rows 32w .. 32w+31; waves 4 .. 7 share their SIMDs with
