@@ -40,8 +40,9 @@ def parse_args():
     ap.add_argument("--workload", default="cfg2", help="headline configuration")
     ap.add_argument("--configs", default="cfg1,cfg2,cfg3,cfg4,cfg5a,cfg5b,cfg5c",
                     help="configurations reported in per_config ('' = headline only)")
-    ap.add_argument("--layout", default="htd", choices=["thd", "htd"],
-                    help="page layout: htd = [page][kv_head][token][d] (a page-head is one 4 KB run), thd = [page][token][kv_head][d]")
+    ap.add_argument("--layout", default="htd", choices=["thd", "htd", "hktd"],
+                    help="page layout: htd = [page][kv_head][token][d] (a page-head is one 4 KB run), thd = [page][token][kv_head][d], "
+                         "hktd = one pool [page][kv_head][K|V][token][d] (K and V of a page-head are one 8 KB run)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-flat", action="store_true")
     ap.add_argument("--num-slots", type=int, default=0)
@@ -61,8 +62,13 @@ class Rotating:
 
     def __init__(self, w, copies):
         import torch
-        self.k = [w.k_pool] + [w.k_pool.clone() for _ in range(copies - 1)]
-        self.v = [w.v_pool] + [w.v_pool.clone() for _ in range(copies - 1)]
+        if getattr(w, "kv_pool", None) is not None:        # K and V are views of one pool: clone that
+            pools = [w.kv_pool] + [w.kv_pool.clone() for _ in range(copies - 1)]
+            self.k = [p[:, :, 0] for p in pools]
+            self.v = [p[:, :, 1] for p in pools]
+        else:
+            self.k = [w.k_pool] + [w.k_pool.clone() for _ in range(copies - 1)]
+            self.v = [w.v_pool] + [w.v_pool.clone() for _ in range(copies - 1)]
         self.n = copies
         torch.cuda.synchronize()
 

@@ -62,8 +62,22 @@ class PlannedAttention:
             raise B.CodecError(st, "codec_plan_export")
         return view
 
+    def _check_pool(self, pool: torch.Tensor, what: str) -> None:
+        """The kernels address `pool` through the plan's strides from its first element: the farthest
+        element they can touch must lie inside the tensor's storage (a view whose strides differ from
+        the plan's, e.g. a compacted copy of a strided view, would send them outside)."""
+        p, h = self.paged, self.head
+        last = ((p.num_pages - 1) * p.page_stride + (h.page_size - 1) * p.token_stride
+                + (h.num_kv_heads - 1) * p.head_stride + h.head_dim)
+        have = pool.untyped_storage().nbytes() // pool.element_size() - pool.storage_offset()
+        if pool.device != self.device or pool.element_size() != 2 or last > have:
+            raise ValueError(f"{what}: {have} elements from the tensor's first one on {pool.device}, "
+                             f"the page table and strides reach {last} on {self.device}")
+
     def decode(self, q: torch.Tensor, k_pool: torch.Tensor, v_pool: torch.Tensor,
                out: torch.Tensor = None, stream=None) -> torch.Tensor:
+        self._check_pool(k_pool, "k_pool")
+        self._check_pool(v_pool, "v_pool")
         if out is None:
             out = torch.empty_like(q)
         s = (stream or torch.cuda.current_stream(self.device)).cuda_stream
@@ -77,6 +91,8 @@ class PlannedAttention:
         return out
 
     def partial_attention(self, q, k_pool, v_pool, stream=None) -> None:
+        self._check_pool(k_pool, "k_pool")
+        self._check_pool(v_pool, "v_pool")
         s = (stream or torch.cuda.current_stream(self.device)).cuda_stream
         p = self.paged
         st = B.codec_partial_attention(self.plan, q.data_ptr(), k_pool.data_ptr(), v_pool.data_ptr(),

@@ -118,3 +118,24 @@ def test_empty_batch_is_a_valid_plan():
     # an empty batch decodes to nothing, without touching the device
     assert C.codec_decode_attention(plan, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0) == C.CODEC_OK
     C.codec_plan_destroy(plan)
+
+
+def test_runtime_refuses_pools_smaller_than_the_strides_reach():
+    """The binding checks on the host that the page table and strides stay inside the K/V tensors
+    before anything is launched: a compacted copy of a strided view is half as long as the kernels
+    would walk."""
+    from workloads import make_workload, three_level_forest
+    f = three_level_forest(70, [130, 45], 3, [5, 33, 64, 1, 17, 48])
+    head = HeadConfig(8, 2, 128, DTYPE_BF16)
+    w = make_workload("one-pool", f, head, seed=3, layout="hktd")
+    pa = C.PlannedAttention(w.forest, w.paged, w.head, device="cpu")
+    pa._check_pool(w.k_pool, "k_pool")
+    pa._check_pool(w.v_pool, "v_pool")
+    with pytest.raises(ValueError, match="k_pool"):
+        pa._check_pool(w.k_pool.contiguous(), "k_pool")
+    with pytest.raises(ValueError, match="v_pool"):
+        pa.decode(w.q, w.k_pool, w.v_pool[:-1].contiguous())        # refused before any pointer is used
+    two = make_workload("two-pools", f, head, seed=3, layout="htd")
+    with pytest.raises(ValueError):
+        pa._check_pool(two.k_pool, "k_pool")                         # the other layout's pool: half the stride
+    pa.close()

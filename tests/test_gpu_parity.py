@@ -117,7 +117,8 @@ def test_division_granularity(slots, align):
         assert max(it["b"] for it in view["items"]) > 4
 
 
-@pytest.mark.parametrize("layout,page_size", [("htd", 16), ("thd", 32), ("htd", 64), ("thd", 128)])
+@pytest.mark.parametrize("layout,page_size", [("htd", 16), ("thd", 32), ("htd", 64), ("thd", 128),
+                                              ("hktd", 16), ("hktd", 32)])
 def test_layouts_and_page_sizes(layout, page_size):
     f = three_level_forest(200, [333, 90], 2, [5, 70, 130, 17])
     head = HeadConfig(8, 2, 128, DTYPE_BF16, page_size=page_size)

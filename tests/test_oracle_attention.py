@@ -186,6 +186,21 @@ def test_invariant_to_physical_page_order_and_layout():
     assert np.array_equal(oa, ob)
 
 
+def test_one_pool_for_keys_and_values_changes_nothing():
+    """The layout with K and V of a page and head side by side holds the values of the layout with two
+    pools (same seed); the oracle, addressing both through their strides, returns the same bits."""
+    f = three_level_forest(70, [130, 45], 3, [5, 33, 64, 1, 17, 48])
+    head = HeadConfig(8, 2, 128, DTYPE_BF16)
+    a = make_workload("two", f, head, seed=3, poison=True, layout="htd")
+    b = make_workload("one", f, head, seed=3, poison=True, layout="hktd")
+    assert b.kv_pool is not None and b.paged.page_stride == 2 * a.paged.page_stride
+    assert b.k_pool.data_ptr() == b.kv_pool.data_ptr()
+    assert b.v_pool.data_ptr() == b.kv_pool.data_ptr() + 2 * head.page_size * head.head_dim
+    oa, la = A.decode_attention_workload(a)
+    ob, lb = A.decode_attention_workload(b)
+    assert np.array_equal(oa, ob) and np.array_equal(la, lb)
+
+
 def test_selection_matches_full_run_and_threads_do_not_matter():
     f = two_level_forest(40, [7, 13, 2])
     w = make_workload("sel", f, HeadConfig(4, 2, 32, DTYPE_BF16, page_size=8), seed=6, poison=True)

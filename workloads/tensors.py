@@ -52,7 +52,9 @@ class PagedKV:
     node_page_off: np.ndarray     # int32 [N+1] into page_ids
     page_ids: np.ndarray          # int32, physical page of each logical page of each node
     num_pages: int                # pool size (>= pages referenced)
-    layout: str                   # "thd": [page][token][kv_head][d];  "htd": [page][kv_head][token][d]
+    layout: str                   # "thd": [page][token][kv_head][d];  "htd": [page][kv_head][token][d];
+                                  # "hktd": one pool [page][kv_head][K|V][token][d], K and V of a page and
+                                  # head side by side (8 KB of consecutive memory with 16-token pages)
     page_stride: int = 0          # in elements
     token_stride: int = 0
     head_stride: int = 0
@@ -69,15 +71,23 @@ class Workload:
     v_pool: torch.Tensor
     seed: int = 0
     notes: dict = field(default_factory=dict)
+    kv_pool: Optional[torch.Tensor] = None    # "hktd": the pool k_pool and v_pool are views of
 
     # raw 16-bit patterns, host side, for the CPU oracle
     def q_bits(self) -> np.ndarray:
         return self.q.detach().cpu().contiguous().view(torch.int16).numpy().view(np.uint16)
 
+    def _pool_bits(self) -> np.ndarray:
+        return self.kv_pool.detach().cpu().contiguous().view(torch.int16).numpy().view(np.uint16).reshape(-1)
+
     def k_bits(self) -> np.ndarray:
+        if self.kv_pool is not None:            # addressed with the pool's strides from K's first element
+            return self._pool_bits()
         return self.k_pool.detach().cpu().contiguous().view(torch.int16).numpy().view(np.uint16)
 
     def v_bits(self) -> np.ndarray:
+        if self.kv_pool is not None:            # the same strides from V's first element
+            return self._pool_bits()[self.paged.page_size * self.head.head_dim:]
         return self.v_pool.detach().cpu().contiguous().view(torch.int16).numpy().view(np.uint16)
 
     @property
@@ -86,6 +96,10 @@ class Workload:
         return forest_stats(self.forest)["unique_tokens"] * self.head.bytes_per_token
 
     def to(self, device) -> "Workload":
+        if self.kv_pool is not None:
+            pool = self.kv_pool.to(device)
+            return Workload(self.name, self.forest, self.head, self.paged, self.q.to(device),
+                            pool[:, :, 0], pool[:, :, 1], self.seed, dict(self.notes), pool)
         return Workload(self.name, self.forest, self.head, self.paged, self.q.to(device),
                         self.k_pool.to(device), self.v_pool.to(device), self.seed, dict(self.notes))
 
@@ -112,10 +126,13 @@ def build_paged_kv(forest: Forest, head: HeadConfig, seed: int, spare_pages: int
         token_stride, head_stride = h * d, d
     elif layout == "htd":
         token_stride, head_stride = d, ps * d
+    elif layout == "hktd":
+        token_stride, head_stride = d, 2 * ps * d
     else:
         raise ValueError(layout)
+    page_stride = (2 if layout == "hktd" else 1) * ps * h * d
     return PagedKV(ps, off.astype(np.int32), page_ids, total, layout,
-                   page_stride=ps * h * d, token_stride=token_stride, head_stride=head_stride)
+                   page_stride=page_stride, token_stride=token_stride, head_stride=head_stride)
 
 
 def _randn_into(dst: torch.Tensor, gen: torch.Generator, chunk: int = 1 << 26) -> None:
@@ -152,6 +169,12 @@ def make_workload(name: str, forest: Forest, head: HeadConfig, seed: int,
     v_pool = torch.empty(shape, dtype=dt, device=device)
     _randn_into(k_pool, gen)
     _randn_into(v_pool, gen)
+    kv_pool = None
+    if paged.layout == "hktd":                  # the values of "htd", K and V of a (page, head) side by side
+        kv_pool = torch.empty((paged.num_pages, h, 2, ps, d), dtype=dt, device=device)
+        kv_pool[:, :, 0] = k_pool
+        kv_pool[:, :, 1] = v_pool
+        k_pool, v_pool = kv_pool[:, :, 0], kv_pool[:, :, 1]
     if poison:
         nan = float("nan")
         referenced = torch.zeros(paged.num_pages, dtype=torch.bool)
@@ -169,7 +192,7 @@ def make_workload(name: str, forest: Forest, head: HeadConfig, seed: int,
             else:
                 k_pool[last, :, t0:] = nan
                 v_pool[last, :, t0:] = nan
-    return Workload(name, forest, head, paged, q, k_pool, v_pool, seed)
+    return Workload(name, forest, head, paged, q, k_pool, v_pool, seed, kv_pool=kv_pool)
 
 
 def bits_to_float64(bits: np.ndarray, dtype: int) -> np.ndarray:
