@@ -261,6 +261,7 @@ int codec_partial_reduction(const codec_plan_t *plan, const void *workspace, siz
     mp.part_ml = reinterpret_cast<const float *>(ws + part_o_bytes(d));
     mp.req_part_off = reinterpret_cast<const int32_t *>(meta + L.req_part_off);
     mp.req_part = reinterpret_cast<const int32_t *>(meta + L.req_part);
+    mp.req_inline = reinterpret_cast<const int32_t *>(meta + L.req_inline);
     mp.out = out;
     mp.num_requests = d.num_requests;
     mp.h_q = d.head.num_q_heads;

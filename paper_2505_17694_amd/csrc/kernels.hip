@@ -1128,16 +1128,21 @@ __global__ void __launch_bounds__(kMergeWaves * 64) merge_kernel(const MergePara
     if (row >= P.num_requests * P.h_q) return;
     const int r = row / P.h_q, hq = row - r * P.h_q;
     const int head = hq / P.group, hj = hq - head * P.group;
-    const int e0 = P.req_part_off[r], e1 = P.req_part_off[r + 1];
+    // The request's line: its number of partial rows and the first kInlineParts of them.  The count and
+    // the first eight rows are read together (no address waits for another read); what follows them
+    // comes from the same line or, for a longer list, from the CSR arrays.
+    const int32_t *line = P.req_inline + int64_t(r) * (kInlineParts + 1);
+    const int total = line[0];
+    int first[kChunk];
+#pragma unroll
+    for (int j = 0; j < kChunk; ++j) first[j] = line[1 + j];        // zero behind the end: a valid row
     const int64_t head_base = int64_t(head) * P.part_rows + hj;
     float M = -INFINITY, L = 0.f, a0 = 0.f, a1 = 0.f;
-#pragma unroll 1
-    for (int base = e0; base < e1; base += kChunk) {
-        const int cnt = e1 - base < kChunk ? e1 - base : kChunk;
+    auto fold = [&](const int (&rows)[kChunk], int cnt) {
         float2 ml[kChunk], o[kChunk];
 #pragma unroll
         for (int j = 0; j < kChunk; ++j) {
-            const int64_t prow = head_base + P.req_part[base + (j < cnt ? j : 0)];
+            const int64_t prow = head_base + rows[j];
             ml[j] = *reinterpret_cast<const float2 *>(P.part_ml + prow * 2);
             o[j] = *reinterpret_cast<const float2 *>(P.part_o + prow * kHeadDim + lane * 2);
         }
@@ -1158,6 +1163,18 @@ __global__ void __launch_bounds__(kMergeWaves * 64) merge_kernel(const MergePara
                 a1 += o[j].y * wb;
             }
         M = mm;
+    };
+    fold(first, total < kChunk ? total : kChunk);
+    if (total > kChunk) {
+        const int32_t *list = total > kInlineParts ? P.req_part + P.req_part_off[r] : line + 1;
+#pragma unroll 1
+        for (int base = kChunk; base < total; base += kChunk) {
+            const int cnt = total - base < kChunk ? total - base : kChunk;
+            int rows[kChunk];
+#pragma unroll
+            for (int j = 0; j < kChunk; ++j) rows[j] = list[base + (j < cnt ? j : 0)];
+            fold(rows, cnt);
+        }
     }
     const float inv = 1.f / L;
     unsigned int *out = static_cast<unsigned int *>(P.out) + int64_t(row) * (kHeadDim / 2) + lane;

@@ -35,6 +35,7 @@ struct MergeParams {
     const float *part_ml;
     const int32_t *req_part_off;
     const int32_t *req_part;
+    const int32_t *req_inline;      // [B][1 + kInlineParts]: count, then the first rows of the list
     void *out;                      // [B][h_q][128], 16-bit
     int32_t num_requests, h_q, group, part_rows;
 };

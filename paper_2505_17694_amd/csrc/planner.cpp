@@ -107,6 +107,7 @@ void build_device_image(PlanData &p)
     L.page_ids = place(p.page_ids.size() * 4);
     L.req_part_off = place(p.req_part_off.size() * 4);
     L.req_part = place(p.req_part.size() * 4);
+    L.req_inline = place(size_t(p.num_requests) * (kInlineParts + 1) * 4);
     // Run-time queue.  Short tasks (the ones a single wave runs) are bundled, in order of decreasing
     // cost, into entries that a workgroup hands out one wave each, like a run of short tasks in a
     // slot's list; every other task is an entry of its own.  The bundle size is the smallest that lets
@@ -197,6 +198,14 @@ void build_device_image(PlanData &p)
     put(L.page_ids, p.page_ids);
     put(L.req_part_off, p.req_part_off);
     put(L.req_part, p.req_part);
+    {
+        int32_t *line = reinterpret_cast<int32_t *>(p.blob.data() + L.req_inline);
+        for (int32_t r = 0; r < p.num_requests; ++r, line += kInlineParts + 1) {
+            const int32_t e0 = p.req_part_off[r], cnt = p.req_part_off[r + 1] - e0;
+            line[0] = cnt;
+            for (int32_t j = 0; j < kInlineParts; ++j) line[1 + j] = j < cnt ? p.req_part[e0 + j] : 0;
+        }
+    }
     put(L.queue_off, p.queue_off);
 }
 

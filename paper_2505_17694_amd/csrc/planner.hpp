@@ -42,10 +42,16 @@ struct DevTask {
     int32_t single_req;     // n_req == 1: the request itself (saves the read of node_q); else -1
 };
 
+// Per request, the reduction kernel reads one 64-byte line: the number of partial rows on the request's
+// path and, if there are at most kInlineParts of them, the rows themselves; longer lists are read
+// from the CSR arrays.  One dependent read less than offset -> list -> partial rows.
+constexpr int32_t kInlineParts = 15;
+
 // Byte offsets of the arrays inside the device metadata blob.
 struct DevLayout {
     size_t slot_recs = 0, slot_off = 0, node_q = 0, page_ids = 0,
-           req_part_off = 0, req_part = 0, queue_off = 0, queue_recs = 0, counters = 0, total = 0;
+           req_part_off = 0, req_part = 0, req_inline = 0, queue_off = 0, queue_recs = 0, counters = 0,
+           total = 0;
 };
 
 struct PlanData {

@@ -344,6 +344,19 @@ def test_drafted_token_trees(drafted, hq, hkv, share, schedule):
     check(w, share=share, schedule=schedule)
 
 
+@pytest.mark.parametrize("slices", [1, 6, 7, 8, 14, 15, 16, 23, 40])
+def test_reduction_lists_of_every_length(slices):
+    """A request's partial rows number slices + 1 or slices + 2 here (root cut evenly, one or two leaf
+    slices): 2, 7 .. 10, 15 .. 18, 24, 25, 41, 42 over the cases.  The reduction kernel reads the first
+    eight rows and the count from one line per request, rows nine to fifteen from the same line, and
+    lists of sixteen and more from the CSR arrays: every boundary is hit from both sides."""
+    f = two_level_forest(32 * slices * 3, [33, 7, 64])
+    w = make_workload(f"parts{slices}", f, HeadConfig(8, 2, 128, DTYPE_BF16), seed=300 + slices, poison=True)
+    got, view = check(w, num_slots=5, split_align=32, fixed_slices=slices)
+    lens = {int(view["req_part_off"][r + 1] - view["req_part_off"][r]) for r in range(3)}
+    assert lens == ({2} if slices == 1 else {slices + 1, slices + 2}), lens
+
+
 def _queue_cases():
     short = [7, 40, 1024, 33, 1025, 64, 300, 5, 2000, 96, 17, 1000, 31, 640, 1, 129] * 3
     dense = two_level_forest(1, [43] * 17)
