@@ -1116,8 +1116,8 @@ __global__ void __launch_bounds__(WIDE ? kWideWaves * 64 : kNarrowWaves * 64, 2)
 }
 
 // Partial output reduction (Alg. 3), n-ary: one wave per (request, query head) folds the request's
-// partials in list order; each lane owns two channels.  Partials are taken eight at a time: their
-// loads are issued together, then the eight are folded against their common maximum (by
+// partials in list order; each lane owns two channels.  Partials are taken eight or fifteen at a time:
+// their loads are issued together, then they are folded against their common maximum (by
 // associativity of the reduction this equals any binary bracketing).
 template <int DT>
 __global__ void __launch_bounds__(kMergeWaves * 64) merge_kernel(const MergeParams P)
@@ -1128,34 +1128,35 @@ __global__ void __launch_bounds__(kMergeWaves * 64) merge_kernel(const MergePara
     if (row >= P.num_requests * P.h_q) return;
     const int r = row / P.h_q, hq = row - r * P.h_q;
     const int head = hq / P.group, hj = hq - head * P.group;
-    // The request's line: its number of partial rows and the first kInlineParts of them.  The count and
-    // the first eight rows are read together (no address waits for another read); what follows them
-    // comes from the same line or, for a longer list, from the CSR arrays.
+    // The request's line: its number of partial rows and the first kInlineParts of them, read together
+    // (no address waits for another read).  Lists of up to eight rows, and of up to kInlineParts, are
+    // folded in one round of loads; what lies beyond comes from the CSR arrays, eight rows a round.
     const int32_t *line = P.req_inline + int64_t(r) * (kInlineParts + 1);
     const int total = line[0];
-    int first[kChunk];
+    int first[kInlineParts];
 #pragma unroll
-    for (int j = 0; j < kChunk; ++j) first[j] = line[1 + j];        // zero behind the end: a valid row
+    for (int j = 0; j < kInlineParts; ++j) first[j] = line[1 + j];  // zero behind the end: a valid row
     const int64_t head_base = int64_t(head) * P.part_rows + hj;
     float M = -INFINITY, L = 0.f, a0 = 0.f, a1 = 0.f;
-    auto fold = [&](const int (&rows)[kChunk], int cnt) {
-        float2 ml[kChunk], o[kChunk];
+    auto fold = [&](const int *rows, int cnt, auto width) {
+        constexpr int N = decltype(width)::value;
+        float2 ml[N], o[N];
 #pragma unroll
-        for (int j = 0; j < kChunk; ++j) {
+        for (int j = 0; j < N; ++j) {
             const int64_t prow = head_base + rows[j];
             ml[j] = *reinterpret_cast<const float2 *>(P.part_ml + prow * 2);
             o[j] = *reinterpret_cast<const float2 *>(P.part_o + prow * kHeadDim + lane * 2);
         }
         float mm = M;
 #pragma unroll
-        for (int j = 0; j < kChunk; ++j)
+        for (int j = 0; j < N; ++j)
             if (j < cnt) mm = fmaxf(mm, ml[j].x);
         const float wa = weight(M, mm);
         L *= wa;
         a0 *= wa;
         a1 *= wa;
 #pragma unroll
-        for (int j = 0; j < kChunk; ++j)
+        for (int j = 0; j < N; ++j)
             if (j < cnt) {
                 const float wb = weight(ml[j].x, mm);
                 L += ml[j].y * wb;
@@ -1164,16 +1165,20 @@ __global__ void __launch_bounds__(kMergeWaves * 64) merge_kernel(const MergePara
             }
         M = mm;
     };
-    fold(first, total < kChunk ? total : kChunk);
-    if (total > kChunk) {
-        const int32_t *list = total > kInlineParts ? P.req_part + P.req_part_off[r] : line + 1;
+    if (total <= kChunk) {
+        fold(first, total, std::integral_constant<int, kChunk>{});
+    } else {
+        fold(first, total < kInlineParts ? total : kInlineParts, std::integral_constant<int, kInlineParts>{});
+        if (total > kInlineParts) {
+            const int32_t *list = P.req_part + P.req_part_off[r];
 #pragma unroll 1
-        for (int base = kChunk; base < total; base += kChunk) {
-            const int cnt = total - base < kChunk ? total - base : kChunk;
-            int rows[kChunk];
+            for (int base = kInlineParts; base < total; base += kChunk) {
+                const int cnt = total - base < kChunk ? total - base : kChunk;
+                int rows[kChunk];
 #pragma unroll
-            for (int j = 0; j < kChunk; ++j) rows[j] = list[base + (j < cnt ? j : 0)];
-            fold(rows, cnt);
+                for (int j = 0; j < kChunk; ++j) rows[j] = list[base + (j < cnt ? j : 0)];
+                fold(rows, cnt, std::integral_constant<int, kChunk>{});
+            }
         }
     }
     const float inv = 1.f / L;
