@@ -180,15 +180,17 @@ def run_config(name, args, steps, warmup, want_flat):
         res["tree_queued"] = {"us_per_step": round(t["step_ms"] * 1e3, 2), "pac_us": round(t["pac_ms_avg"] * 1e3, 2),
                               "entries": len(view["queue_off"]) - 1, "slots": view["num_slots"]}
         pa.close()
-        # the plan the library picks by estimated makespan among its candidates (share = 2)
+        # the library's own choices: the plan with the lowest estimated makespan among its candidates
+        # (share = 2), static schedule or run-time queue by the number of queue entries (schedule = 2)
         t0 = time.perf_counter()
-        pa = C.PlannedAttention(w.forest, w.paged, w.head, device="cuda:0", share=2,
+        pa = C.PlannedAttention(w.forest, w.paged, w.head, device="cuda:0", share=2, schedule=2,
                                 num_slots=args.num_slots, split_align=args.split_align, max_rows=args.max_rows)
         plan_ms = (time.perf_counter() - t0) * 1e3
         view = pa.export()
         t, _ = time_plan(pa, w, rot, steps, warmup)
         res["best_plan"] = {"us_per_step": round(t["step_ms"] * 1e3, 2), "pac_us": round(t["pac_ms_avg"] * 1e3, 2),
-                            "picked": {"share": view["share"], "max_rows": view["max_rows"]},
+                            "picked": {"share": view["share"], "max_rows": view["max_rows"],
+                                       "schedule": view["schedule"]},
                             "plan_ms": round(plan_ms, 2), "est_makespan": view["makespan"]}
         pa.close()
         res["speedup_vs_flat"] = round(res["flat"]["us_per_step"] / res["tree"]["us_per_step"], 3)
@@ -217,7 +219,7 @@ def run_sweep(args):
                     ("division_only", {"share": 0}), ("all", {"share": 1})]
     else:
         points = sweep_points(args.sweep)
-        variants = [("tree", {"share": 1}), ("flat", {"share": 0}), ("best_plan", {"share": 2})]
+        variants = [("tree", {"share": 1}), ("flat", {"share": 0}), ("best_plan", {"share": 2, "schedule": 2})]
     steps = max(5, min(args.steps, 20))
     out_points = []
     for label, forest in points:
@@ -241,7 +243,7 @@ def run_sweep(args):
                        "unique_kv_GBps": round(unique_bytes / (t["step_ms"] * 1e-3) / 1e9, 1),
                        "tasks": len(view["tasks"]), "est_makespan": view["makespan"]}
             if opts["share"] == 2:
-                pt[key]["picked"] = {"share": view["share"], "max_rows": view["max_rows"]}
+                pt[key]["picked"] = {"share": view["share"], "max_rows": view["max_rows"], "schedule": view["schedule"]}
             pa.close()
         base = {"ablation": "none", "granularity": "fixed=1"}.get(args.sweep, "flat")
         best = {"ablation": "all", "granularity": "adaptive"}.get(args.sweep, "tree")

@@ -119,7 +119,10 @@ typedef struct {
                                do not leave workgroups idle.  The first num_slots entries go to the
                                workgroups they would go to anyway; runs of short tasks form one entry.
                                The queue keeps two counters per KV head in the plan's device metadata:
-                               one launch of a plan at a time                                        */
+                               one launch of a plan at a time; 2 = the library chooses: the queue if it
+                               has at least eight entries per slot (measured on irregular forests: with
+                               that many the queue is 3-6 % faster, with few it changes nothing), else
+                               static.  The plan view reports the schedule in use (0 or 1)           */
 } codec_plan_options;
 
 /* One work item of the division problem: a node (or a row tile of it) with its queries. */

@@ -149,6 +149,8 @@ void build_device_image(PlanData &p)
             p.queue_off.push_back(int32_t(p.queue_tasks.size()));
         }
     }
+    if (p.schedule == 2)
+        p.schedule = int64_t(p.queue_off.size()) - 1 >= int64_t(kAutoQueueEntriesPerSlot) * p.num_slots ? 1 : 0;
     L.queue_off = place(p.queue_off.size() * 4);
     L.queue_recs = place(p.queue_tasks.size() * sizeof(DevTask));
     L.counters = place(size_t(p.head.num_kv_heads) * 2 * 4);               // zero: nothing taken, nobody done
@@ -289,7 +291,7 @@ int build_plan(const codec_tree &tree, const codec_head_config &head,
     if (max_rows > 256 || max_rows < group) return CODEC_ERR_INVALID_ARGUMENT;
     if (opt.share != 0 && opt.share != 1) return CODEC_ERR_INVALID_ARGUMENT;
     if (opt.fixed_slices < 0) return CODEC_ERR_INVALID_ARGUMENT;
-    if (opt.schedule != 0 && opt.schedule != 1) return CODEC_ERR_INVALID_ARGUMENT;
+    if (opt.schedule < 0 || opt.schedule > 2) return CODEC_ERR_INVALID_ARGUMENT;
 
     CostTable user;
     const CostTable *table = nullptr;           // nullptr: the built-in table of the kernel variant

@@ -26,6 +26,8 @@ constexpr int32_t kSoloMaxLen = 1024;
 // Most short tasks in one entry of the run-time queue (measured on cfg3/cfg4: 2 costs fetches, 8 and
 // more make the last entries long).
 constexpr int32_t kQueueBundle = 4;
+// schedule = 2 takes the run-time queue from this many entries per slot on.
+constexpr int32_t kAutoQueueEntriesPerSlot = 8;
 
 // Task record as the kernels read it (32 bytes).  The device image holds the records twice: in the
 // order of the slots' lists and in the order of the run-time queue, so that a workgroup reads record

@@ -305,9 +305,37 @@ def test_schedule_option_is_checked():
     f = two_level_forest(100, [5, 9])
     head = HeadConfig(8, 8, 128, 0)
     paged = build_paged_kv(f, head, seed=1)
-    for bad in (2, -1):
+    for bad in (3, -1):
         st, plan = C.codec_plan_create(f.parent, f.node_len, f.req_node, paged.node_page_off, paged.page_ids,
                                        head.num_q_heads, head.num_kv_heads, head.head_dim, head.dtype,
                                        head.page_size, head.scale, schedule=bad)
         assert st == C.CODEC_ERR_INVALID_ARGUMENT and plan is None
 
+
+
+@pytest.mark.parametrize("name", ["cfg2", "cfg3", "cfg4", "cfg5c"])
+def test_automatic_schedule_follows_the_entry_count(name):
+    """schedule = 2 resolves to the run-time queue from eight entries per slot on, to the static
+    schedule below; everything else in the plan is the same in the three modes."""
+    f, head = config_forest(name), config_head(name)
+    paged = build_paged_kv(f, head, seed=1)
+    views = {}
+    for schedule in (0, 1, 2):
+        st, plan = C.codec_plan_create(f.parent, f.node_len, f.req_node, paged.node_page_off, paged.page_ids,
+                                       head.num_q_heads, head.num_kv_heads, head.head_dim, head.dtype,
+                                       head.page_size, head.scale, schedule=schedule)
+        assert st == C.CODEC_OK
+        st, views[schedule] = C.codec_plan_export(plan)
+        C.codec_plan_destroy(plan)
+    entries = len(views[2]["queue_off"]) - 1
+    assert views[0]["schedule"] == 0 and views[1]["schedule"] == 1
+    assert views[2]["schedule"] == (1 if entries >= 8 * views[2]["num_slots"] else 0)
+    assert views[2]["schedule"] == {"cfg2": 0, "cfg3": 0, "cfg4": 1, "cfg5c": 0}[name]
+    for key in ("tasks", "slot_off", "slot_tasks", "queue_off", "queue_tasks", "makespan"):
+        assert _same(views[0][key], views[2][key]) and _same(views[1][key], views[2][key]), key
+
+
+def _same(a, b):
+    if isinstance(a, list):
+        return a == b
+    return np.array_equal(np.asarray(a), np.asarray(b))
