@@ -120,7 +120,7 @@ typedef struct {
                                workgroups they would go to anyway; runs of short tasks form one entry.
                                The queue keeps two counters per KV head in the plan's device metadata:
                                one launch of a plan at a time; 2 = the library chooses: the queue if it
-                               has at least eight entries per slot (measured on irregular forests: with
+                               has at least six entries per slot (measured on irregular forests: with
                                that many the queue is 3-6 % faster, with few it changes nothing), else
                                static.  The plan view reports the schedule in use (0 or 1)           */
 } codec_plan_options;

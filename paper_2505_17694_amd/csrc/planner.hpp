@@ -27,7 +27,7 @@ constexpr int32_t kSoloMaxLen = 1024;
 // more make the last entries long).
 constexpr int32_t kQueueBundle = 4;
 // schedule = 2 takes the run-time queue from this many entries per slot on.
-constexpr int32_t kAutoQueueEntriesPerSlot = 8;
+constexpr int32_t kAutoQueueEntriesPerSlot = 6;
 
 // Task record as the kernels read it (32 bytes).  The device image holds the records twice: in the
 // order of the slots' lists and in the order of the run-time queue, so that a workgroup reads record

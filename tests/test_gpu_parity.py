@@ -230,7 +230,7 @@ def test_best_candidate_plan_on_the_gpu():
 
 @pytest.mark.parametrize("slots,expect", [(2, 1), (64, 0)])
 def test_automatic_schedule_on_the_gpu(slots, expect):
-    """schedule = 2: with two slots the forest below has far more than eight queue entries per slot and
+    """schedule = 2: with two slots the forest below has far more than six queue entries per slot and
     runs from the queue, with 64 slots it stays on the static lists; both against the oracle."""
     f = random_forest(40, 4, 2.0, 300, 1.0, 8, 4000, seed=77)
     w = make_workload(f"auto{slots}", f, HeadConfig(16, 4, 128, DTYPE_BF16), seed=78, poison=True)

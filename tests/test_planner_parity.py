@@ -315,7 +315,7 @@ def test_schedule_option_is_checked():
 
 @pytest.mark.parametrize("name", ["cfg2", "cfg3", "cfg4", "cfg5c"])
 def test_automatic_schedule_follows_the_entry_count(name):
-    """schedule = 2 resolves to the run-time queue from eight entries per slot on, to the static
+    """schedule = 2 resolves to the run-time queue from six entries per slot on, to the static
     schedule below; everything else in the plan is the same in the three modes."""
     f, head = config_forest(name), config_head(name)
     paged = build_paged_kv(f, head, seed=1)
@@ -329,7 +329,7 @@ def test_automatic_schedule_follows_the_entry_count(name):
         C.codec_plan_destroy(plan)
     entries = len(views[2]["queue_off"]) - 1
     assert views[0]["schedule"] == 0 and views[1]["schedule"] == 1
-    assert views[2]["schedule"] == (1 if entries >= 8 * views[2]["num_slots"] else 0)
+    assert views[2]["schedule"] == (1 if entries >= 6 * views[2]["num_slots"] else 0)
     assert views[2]["schedule"] == {"cfg2": 0, "cfg3": 0, "cfg4": 1, "cfg5c": 0}[name]
     for key in ("tasks", "slot_off", "slot_tasks", "queue_off", "queue_tasks", "makespan"):
         assert _same(views[0][key], views[2][key]) and _same(views[1][key], views[2][key]), key
