@@ -14,7 +14,7 @@ from scipy.special import logsumexp
 
 from oracle import attention as A
 from workloads import (HeadConfig, make_workload, two_level_forest, three_level_forest,
-                       unshared_forest, random_forest, DTYPE_FP16, DTYPE_BF16, Forest)
+                       unshared_forest, random_forest, draft_tree_forest, DTYPE_FP16, DTYPE_BF16, Forest)
 from helpers import request_context, q_float64, set_token, token_slot, pool_row
 
 
@@ -84,6 +84,29 @@ def test_brute_force_random_forest_internal_request():
     out, _ = A.decode_attention_workload(w)
     ref, _ = brute_force(w)
     assert np.max(np.abs(out - ref)) < 1e-13
+
+
+def test_brute_force_drafted_token_trees():
+    """Multi-token decoding: a request at every drafted token (one-token nodes) and at every context;
+    a query sees its path only, so a drafted token on another branch must not leak in.  The second
+    part plants a huge key on a sibling branch and checks that only its own branch notices."""
+    f = draft_tree_forest(5, [7, 3], 6, seed=2)
+    w = make_workload("drafts", f, HeadConfig(4, 2, 8, DTYPE_BF16, page_size=4), seed=9, poison=True)
+    out, lse = A.decode_attention_workload(w)
+    ref, ref_lse = brute_force(w)
+    assert np.max(np.abs(out - ref)) < 1e-13 and np.max(np.abs(lse - ref_lse)) < 1e-12
+    # the first drafted token with a sibling: a key of 100s in it changes the requests below it only
+    parents = [int(p) for p in f.parent]
+    node = next(n for n in range(f.num_nodes) if f.node_len[n] == 1 and parents.count(parents[n]) > 1)
+    page, slot = token_slot(w, node, 0)
+    for kvh in range(w.head.num_kv_heads):
+        pool_row(w.k_pool, w, page, slot, kvh)[:] = 100.0
+    out2, _ = A.decode_attention_workload(w)
+    below = [r for r in range(f.num_requests) if node in f.path(r)]
+    others = [r for r in range(f.num_requests) if node not in f.path(r)]
+    assert below and others
+    assert np.array_equal(out2[others], out[others])
+    assert all(np.max(np.abs(out2[r] - out[r])) > 1e-6 for r in below)
 
 
 def test_single_sequence_equals_torch_softmax():
