@@ -3,20 +3,27 @@ back (queued between asynchronous copies, waited for by hand) are named by no in
 load and the statement that releases them, on any path through the generated gfx950 assembly."""
 import re
 
+import pytest
+
 from paper_2505_17694_amd import check_pending_loads as chk
 
 
-def test_no_instruction_touches_a_register_that_is_still_being_loaded():
-    asm = chk.assembly()
+@pytest.fixture(scope="module")
+def assembly():
+    return chk.assembly()
+
+
+def test_no_instruction_touches_a_register_that_is_still_being_loaded(assembly):
+    asm = assembly
     loads, marks, bad = chk.check(asm)
     # per instantiation of the dense path (2 element types x 2 live roles x 2 strides): 8 loads, 1 release
     assert loads == 64 and marks == 8, (loads, marks)
     assert not bad, bad[:10]
 
 
-def test_the_check_sees_a_planted_copy():
+def test_the_check_sees_a_planted_copy(assembly):
     """A copy of a pending register planted behind the first label after a load sequence is reported."""
-    asm = chk.assembly().splitlines()
+    asm = assembly.splitlines()
     is_load = lambda i: chk._LOAD.match(asm[i]) and asm[i - 1].strip() == ";;#ASMSTART"
     first = next(i for i in range(1, len(asm)) if is_load(i))
     reg = int(re.match(r"v\[(\d+):", chk._LOAD.match(asm[first]).group(1)).group(1))
