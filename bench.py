@@ -8,11 +8,15 @@ the K/V pools that nothing of a pool survives in L2 / Infinity Cache until its
 next use, which is what a multi-layer decode loop sees.
 
 Prints ONE JSON line.  ``value`` is GB/s of unique KV bytes (every node counted
-once) over the whole step of the headline workload; ``roofline`` prices the
-partial-attention kernel alone against the 8 TB/s HBM peak; ``per_config``
-carries the same figures, the flat (no-sharing) baseline of the same library
-and the tree/flat speedup for every configuration; ``cpu_baseline`` is the fp64
-oracle timed on this machine's host cores on a bounded sample.
+once) over the whole step of the headline workload (cfg5c, the largest
+configuration that fits one GPU); ``roofline`` prices the partial-attention
+kernel alone against the 8 TB/s HBM peak and against a plain streaming-read
+kernel measured in the same run; ``cpu_baseline`` is the fp64 oracle timed on
+this machine's host cores on a bounded sample.  ``per_config`` carries, for every
+configuration, its own ``roofline`` and ``cpu_baseline`` objects, the planner
+variants (the solver of Sec. 5.1 as printed and the library's two extensions
+of it, one at a time and together), the flat (no-sharing) baseline of the same
+library and the tree/flat speedup.
 """
 from __future__ import annotations
 
@@ -28,6 +32,7 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBPS = 8000.0
+MFMA_BF16_PEAK_TFLOPS = 2500.0        # dense bf16 / fp16 matrix peak of the chip
 COLD_FOOTPRINT_BYTES = 3 << 30        # rotate pool copies until this much K/V is cycled through
 MIN_WARM_SECONDS = 0.25
 
@@ -37,7 +42,7 @@ def parse_args():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--workload", default="cfg2", help="headline configuration")
+    ap.add_argument("--workload", default="cfg5c", help="headline configuration")
     ap.add_argument("--configs", default="cfg1,cfg2,cfg3,cfg4,cfg5a,cfg5b,cfg5c",
                     help="configurations reported in per_config ('' = headline only)")
     ap.add_argument("--layout", default="htd", choices=["thd", "htd", "hktd"],
@@ -48,7 +53,11 @@ def parse_args():
     ap.add_argument("--num-slots", type=int, default=0)
     ap.add_argument("--split-align", type=int, default=0)
     ap.add_argument("--max-rows", type=int, default=0)
-    ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU time of the oracle sample")
+    ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU time of the oracle sample (headline)")
+    ap.add_argument("--cpu-seconds-other", type=float, default=3.0,
+                    help="target CPU time of the oracle sample of the other configurations")
+    ap.add_argument("--no-stream-calibration", action="store_true",
+                    help="skip the plain streaming-read kernel (roofline.frac_of_measured_stream is then null)")
     ap.add_argument("--sweep", default="", help="run one of the paper-shaped synthetic sweeps instead of the "
                     "configurations: seqlen, batch, depth, ratio, shape, ablation, granularity")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -141,16 +150,17 @@ def run_config(name, args, steps, warmup, want_flat):
            "mean_sharing": round(st["mean_sharing"], 3), "pool_copies": copies,
            "requests": st["num_requests"], "nodes": st["num_nodes"]}
     outs = {}
-    for share in ([1, 0] if want_flat else [1]):
+    # "tree": the prefix-shared plan with both planner extensions (what the library is measured on);
+    # "flat": the no-sharing baseline of the same library
+    for key, share, ext in ([("tree", 1, 3), ("flat", 0, 0)] if want_flat else [("tree", 1, 3)]):
         t0 = time.perf_counter()
-        pa = C.PlannedAttention(w.forest, w.paged, w.head, device="cuda:0", share=share,
+        pa = C.PlannedAttention(w.forest, w.paged, w.head, device="cuda:0", share=share, extensions=ext,
                                 num_slots=args.num_slots, split_align=args.split_align,
                                 max_rows=args.max_rows)
         plan_ms = (time.perf_counter() - t0) * 1e3
         view = pa.export()
         t, out = time_plan(pa, w, rot, steps, warmup)
         outs[share] = out.clone()
-        key = "tree" if share else "flat"
         res[key] = {
             "us_per_step": round(t["step_ms"] * 1e3, 2),
             "pac_us": round(t["pac_ms_avg"] * 1e3, 2), "pac_us_min": round(t["pac_ms_min"] * 1e3, 2),
@@ -158,8 +168,6 @@ def run_config(name, args, steps, warmup, want_flat):
             "unique_kv_GBps": round(unique_bytes / (t["step_ms"] * 1e-3) / 1e9, 1),
             "frac_of_hbm_peak": round(unique_bytes / (t["step_ms"] * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4),
             "read_GBps": round((unique_bytes if share else flat_bytes) / (t["step_ms"] * 1e-3) / 1e9, 1),
-            "pac_unique_kv_GBps": round(unique_bytes / (t["pac_ms_avg"] * 1e-3) / 1e9, 1),
-            "pac_frac_of_hbm_peak": round(unique_bytes / (t["pac_ms_avg"] * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4),
             "plan_ms": round(plan_ms, 2), "tasks": len(view["tasks"]), "part_rows": view["part_rows"],
             "est_makespan": view["makespan"], "cost_l": view["cost_l"],
         }
@@ -172,8 +180,18 @@ def run_config(name, args, steps, warmup, want_flat):
             res[key]["refresh_ms"] = round((time.perf_counter() - t0) * 1e3, 3)
         pa.close()
     if want_flat:
+        # the solver of Sec. 5.1 as printed (Eq. 5 bound, node-by-node grid search), then each of the
+        # library's two extensions of it alone: what each addition is worth on this workload
+        for key, ext in (("tree_sec5_as_printed", 0), ("tree_slack_only", 1), ("tree_diagonal_only", 2)):
+            pa = C.PlannedAttention(w.forest, w.paged, w.head, device="cuda:0", share=1, extensions=ext,
+                                    num_slots=args.num_slots, split_align=args.split_align, max_rows=args.max_rows)
+            view = pa.export()
+            t, _ = time_plan(pa, w, rot, steps, warmup)
+            res[key] = {"us_per_step": round(t["step_ms"] * 1e3, 2), "pac_us": round(t["pac_ms_avg"] * 1e3, 2),
+                        "tasks": len(view["tasks"]), "est_makespan": view["makespan"]}
+            pa.close()
         # the same prefix-shared tasks taken from a run-time queue instead of the static slot lists
-        pa = C.PlannedAttention(w.forest, w.paged, w.head, device="cuda:0", share=1, schedule=1,
+        pa = C.PlannedAttention(w.forest, w.paged, w.head, device="cuda:0", share=1, schedule=1, extensions=3,
                                 num_slots=args.num_slots, split_align=args.split_align, max_rows=args.max_rows)
         view = pa.export()
         t, _ = time_plan(pa, w, rot, steps, warmup)
@@ -183,7 +201,7 @@ def run_config(name, args, steps, warmup, want_flat):
         # the library's own choices: the plan with the lowest estimated makespan among its candidates
         # (share = 2), static schedule or run-time queue by the number of queue entries (schedule = 2)
         t0 = time.perf_counter()
-        pa = C.PlannedAttention(w.forest, w.paged, w.head, device="cuda:0", share=2, schedule=2,
+        pa = C.PlannedAttention(w.forest, w.paged, w.head, device="cuda:0", share=2, schedule=2, extensions=3,
                                 num_slots=args.num_slots, split_align=args.split_align, max_rows=args.max_rows)
         plan_ms = (time.perf_counter() - t0) * 1e3
         view = pa.export()
@@ -196,6 +214,76 @@ def run_config(name, args, steps, warmup, want_flat):
         res["speedup_vs_flat"] = round(res["flat"]["us_per_step"] / res["tree"]["us_per_step"], 3)
         res["tree_vs_flat_max_abs_diff"] = float((outs[1].float() - outs[0].float()).abs().max())
     return res, w, outs[1]
+
+
+def roofline_of(name, res, w, args, stream_gbps):
+    """Roofline objects of the partial-attention kernel for one configuration.
+
+    Algorithmic bytes per launch = unique KV bytes (512 B per token and KV head, every node once);
+    duration = the kernel's average over the timed launches, HIP events on the launch stream.
+    """
+    raw = res["tree"]["_raw"]
+    unique = res["unique_kv_bytes"]
+    achieved = unique / (raw["pac_ms_avg"] * 1e-3) / 1e9
+    # HBM bytes per launch as counted by rocprofv3 (--pmc FETCH_SIZE / WRITE_SIZE, scaled by a known
+    # copy): a committed measurement of the same command, not taken live
+    traffic = None
+    try:
+        with open(os.path.join(ROOT, "profiles", "pac_kernel_traffic.json")) as f:
+            t = json.load(f).get(name)
+        if t and args.layout == "htd" and not (args.num_slots or args.split_align or args.max_rows):
+            traffic = t["fetch_bytes"] + t["write_bytes"]
+    except OSError:
+        pass
+    roof = {"bound": "hbm", "kernel": "pac_kernel (partial attention)",
+            "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+            "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": traffic,
+            "algorithmic_bytes_per_launch": unique,
+            "avg_launch_us": round(raw["pac_ms_avg"] * 1e3, 2),
+            "measured_stream_read_GBps": stream_gbps,
+            "frac_of_measured_stream": round(achieved / stream_gbps, 4) if stream_gbps else None}
+    out = {"roofline": roof}
+    # algorithmic flops: 4 * head_dim per (query row, token) pair = 4 d * sum over requests of context * h_q
+    f = w.forest
+    ctx = sum(int(f.node_len[n]) for r in range(f.num_requests) for n in f.path(r))
+    flops = 4.0 * w.head.head_dim * ctx * w.head.num_q_heads
+    tf = flops / (raw["pac_ms_avg"] * 1e-3) / 1e12
+    out["roofline_mfma"] = {"bound": "mfma", "kernel": "pac_kernel (partial attention)", "achieved": round(tf, 1),
+                            "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                            "frac": round(tf / MFMA_BF16_PEAK_TFLOPS, 4), "traffic": None,
+                            "algorithmic_flops_per_launch": flops}
+    return out
+
+
+def stream_calibration():
+    """Read rate of a plain streaming kernel on this machine: 8 GiB, 16-byte loads, 4 KB chunks per workgroup."""
+    import torch
+    import paper_2505_17694_amd as C
+    nbytes = 8 << 30
+    buf = torch.empty(nbytes, dtype=torch.uint8, device="cuda:0")
+    buf.view(torch.int32).random_(0, 1 << 30)
+    sink = torch.zeros(1 << 16, dtype=torch.int32, device="cuda:0")
+    stream = torch.cuda.current_stream()
+    res = {}
+    for label, pattern, nt in (("linear", 0, 0), ("linear_nontemporal", 0, 1),
+                               ("scattered_4KB", 1, 0), ("scattered_4KB_nontemporal", 1, 1)):
+        best = None
+        for groups in (2048, 4096, 8192):
+            for _ in range(3):
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record(stream)
+                st = C.codec_stream_read_probe(buf.data_ptr(), nbytes, pattern, nt, groups, sink.data_ptr(),
+                                               stream.cuda_stream)
+                e1.record(stream)
+                if st != C.CODEC_OK:
+                    raise C.CodecError(st, "codec_stream_read_probe")
+                torch.cuda.synchronize()
+                gbps = nbytes / (e0.elapsed_time(e1) * 1e-3) / 1e9
+                best = gbps if best is None else max(best, gbps)
+        res[label] = round(best, 1)
+    del buf, sink
+    torch.cuda.empty_cache()
+    return res
 
 
 NO_DIVISION = 1 << 20          # split_align above every node length: no node is divided
@@ -234,7 +322,8 @@ def run_sweep(args):
         pt = {"point": label, "requests": st["num_requests"], "nodes": st["num_nodes"],
               "unique_kv_bytes": unique_bytes, "mean_sharing": round(st["mean_sharing"], 3)}
         for key, kw in variants:
-            opts = {"share": 1, "num_slots": args.num_slots, "split_align": args.split_align, "max_rows": args.max_rows}
+            opts = {"share": 1, "num_slots": args.num_slots, "split_align": args.split_align, "max_rows": args.max_rows,
+                    "extensions": 3}
             opts.update(kw)
             pa = C.PlannedAttention(w.forest, w.paged, w.head, device="cuda:0", **opts)
             view = pa.export()
@@ -325,6 +414,14 @@ def main():
         run_sweep(args)
         return
 
+    stream = None
+    if not args.no_stream_calibration:
+        stream = stream_calibration()
+        print(f"[bench] streaming-read kernel, 8 GiB: {stream} GB/s", file=sys.stderr, flush=True)
+    # the reference rate for the attention kernel: the scattered 4 KB walk (a paged pool's pattern) with
+    # the hint the kernel itself uses for slices that are read once
+    stream_gbps = stream["scattered_4KB_nontemporal"] if stream else None
+
     names = [c for c in args.configs.split(",") if c]
     if args.workload not in names:
         names.append(args.workload)
@@ -338,11 +435,19 @@ def main():
               f"({res['tree']['unique_kv_GBps']} GB/s unique KV)"
               + (f", flat {res['flat']['us_per_step']} us, speedup {res['speedup_vs_flat']}x" if "flat" in res else ""),
               file=sys.stderr, flush=True)
+        res.update(roofline_of(name, res, w, args, stream_gbps))
+        if name != "cfg5a" and not (is_head and name == "cfg5c"):
+            res.pop("roofline_mfma")                    # the matrix roof matters where query sets are large
+        if not args.no_cpu_baseline:
+            res["cpu_baseline"] = cpu_baseline(w, out, args.cpu_seconds if is_head else args.cpu_seconds_other)
+        raw = res["tree"]["_raw"]
+        for k in ("tree", "flat"):
+            if k in res:
+                res[k].pop("_raw", None)
         if is_head:
-            headline = (res, w, out)
-        else:
-            del w, out
-            torch.cuda.empty_cache()
+            headline = (res, w.head, raw)
+        del w, out
+        torch.cuda.empty_cache()
         per_config[name] = res
 
     if args.copy_calibration:
@@ -354,28 +459,7 @@ def main():
         torch.cuda.synchronize()
         del src, dst
 
-    res, w, out = headline
-    raw = res["tree"]["_raw"]
-    cpu = None
-    if not args.no_cpu_baseline:
-        cpu = cpu_baseline(w, out, args.cpu_seconds)
-    for r in per_config.values():
-        for k in ("tree", "flat"):
-            if k in r:
-                r[k].pop("_raw", None)
-
-    unique = res["unique_kv_bytes"]
-    achieved = unique / (raw["pac_ms_avg"] * 1e-3) / 1e9
-    # HBM bytes per launch of the partial-attention kernel as counted by rocprofv3 (--pmc FETCH_SIZE and
-    # WRITE_SIZE, scaled by a known copy): a committed measurement of the same command, not taken live
-    traffic = None
-    try:
-        with open(os.path.join(ROOT, "profiles", "pac_kernel_traffic.json")) as f:
-            t = json.load(f).get(args.workload)
-        if t and args.layout == "htd" and not (args.num_slots or args.split_align or args.max_rows):
-            traffic = t["fetch_bytes"] + t["write_bytes"]
-    except OSError:
-        pass
+    res, head, raw = headline
     line = {
         "metric": "decode_attention_unique_kv_bandwidth",
         "value": res["tree"]["unique_kv_GBps"],
@@ -384,19 +468,17 @@ def main():
         "ms_per_step": round(raw["step_ms"], 5),
         "us_per_step": res["tree"]["us_per_step"],
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "bf16" if w.head.dtype == 1 else "fp16",
+        "dtype": "bf16" if head.dtype == 1 else "fp16",
         "data": "synthetic",
-        "config": {"workload": args.workload, "q_heads": w.head.num_q_heads, "kv_heads": w.head.num_kv_heads,
-                   "head_dim": w.head.head_dim, "page_size": w.head.page_size, "kv_layout": args.layout,
-                   "requests": res["requests"], "nodes": res["nodes"], "unique_kv_bytes": unique,
+        "config": {"workload": args.workload, "q_heads": head.num_q_heads, "kv_heads": head.num_kv_heads,
+                   "head_dim": head.head_dim, "page_size": head.page_size, "kv_layout": args.layout,
+                   "requests": res["requests"], "nodes": res["nodes"], "unique_kv_bytes": res["unique_kv_bytes"],
+                   "plan": "prefix-shared, static schedule, planner extensions slack+diagonal",
                    "cold_cache": f"rotation over {res['pool_copies']} K/V pool copies"},
         "speedup_vs_flat": res.get("speedup_vs_flat"),
-        "roofline": {"bound": "hbm", "kernel": "pac_kernel (partial attention)",
-                     "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                     "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": traffic,
-                     "algorithmic_bytes_per_launch": unique,
-                     "avg_launch_us": round(raw["pac_ms_avg"] * 1e3, 2)},
-        "cpu_baseline": cpu,
+        "roofline": res["roofline"],
+        "cpu_baseline": res.get("cpu_baseline"),
+        "stream_read_calibration_GBps": stream,
         "per_config": per_config,
     }
     print(json.dumps(line))

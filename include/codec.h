@@ -123,7 +123,20 @@ typedef struct {
                                has at least six entries per slot (measured on irregular forests: with
                                that many the queue is 3-6 % faster, with few it changes nothing), else
                                static.  The plan view reports the schedule in use (0 or 1)           */
+    int32_t extensions;     /* 0 = the solver of Sec. 5.1 as printed: slice counts bounded by
+                               ceil(C_est / cost_l) (Eq. 5), one node-by-node pass of the grid search.
+                               Bits add this library's own extensions of it (CODEC_PLAN_EXT_*)       */
 } codec_plan_options;
+
+/*
+ * Extensions of the Sec. 5.1 solver (not in the paper; each measured against the printed solver):
+ *  CODEC_PLAN_EXT_SLACK     a node whose cost is at least cost_l / 4 may take one slice more than
+ *                           the bound of Eq. 5 (lets a few nodes of 0.3 .. 1 average loads pack evenly)
+ *  CODEC_PLAN_EXT_DIAGONAL  after the node-by-node pass the search also evaluates nine points on
+ *                           the diagonal of the grid (every node at its Eq. 5 quotient for a common
+ *                           target cost_l * (1 + k/8), k = 0 .. 8) and keeps the best point seen
+ */
+enum { CODEC_PLAN_EXT_SLACK = 1, CODEC_PLAN_EXT_DIAGONAL = 2 };
 
 /* One work item of the division problem: a node (or a row tile of it) with its queries. */
 typedef struct {
@@ -132,7 +145,9 @@ typedef struct {
     int32_t n_req;          /* requests in the item; rows = n_req * group                         */
     int32_t rows;
     int32_t len;            /* tokens of the node                                                 */
-    int32_t ub;             /* upper bound on KV slices from Eq. 5                                */
+    int32_t ub;             /* most KV slices the search may give the item: the bound of Eq. 5,
+                               ceil(cost / cost_l), one more under CODEC_PLAN_EXT_SLACK for an item
+                               of at least cost_l / 4, as a count of aligned slices                  */
     int32_t b;              /* chosen number of KV slices b_k                                     */
     int32_t reserved;
     int64_t cost;           /* C_est(rows, len)                                                   */
@@ -298,6 +313,39 @@ int codec_partial_attention(const codec_plan_t *plan, const void *q,
                             void *workspace, size_t workspace_bytes, void *stream);
 int codec_partial_reduction(const codec_plan_t *plan, const void *workspace,
                             size_t workspace_bytes, void *out, void *stream);
+
+/*
+ * codec_decode_attention for callers that cannot allocate device memory and hold no workspace:
+ * code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  The same
+ * two kernels run with the partial results in a scratch array of the library's own (static device
+ * memory, CODEC_STATIC_SCRATCH_BYTES = 64 MiB per GPU, held until the process ends); the call
+ * allocates and frees nothing.  q, k_pages, v_pages, layout, out and stream are those of
+ * codec_decode_attention; the plan must have been uploaded (codec_plan_upload, which is also where
+ * the one-off kernel attributes are set) with the device it was uploaded to current.
+ * Errors: CODEC_ERR_WORKSPACE_TOO_SMALL if codec_plan_workspace_bytes(plan) exceeds the array
+ * (codec_last_error_message names both sizes); otherwise as codec_decode_attention.
+ * Every call on a GPU uses that GPU's one array, which keeps the previous call's contents (nothing in
+ * it has to start at zero: every partial row a call reads, it has written first): calls that
+ * overlap on one GPU, on any streams, race.
+ */
+#define CODEC_STATIC_SCRATCH_BYTES ((size_t)64 << 20)
+int codec_decode_attention_static(const codec_plan_t *plan, const void *q,
+                                  const void *k_pages, const void *v_pages,
+                                  const codec_kv_layout *layout, void *out, void *stream);
+size_t codec_static_scratch_bytes(void);       /* CODEC_STATIC_SCRATCH_BYTES of the built library */
+
+/*
+ * Measurement support (no part of the method): a read-only streaming kernel that gives the HBM read
+ * rate this machine reaches, for pricing the attention kernel against something measured beside the
+ * vendor's 8 TB/s.  Reads `bytes` (a power of two, >= 4096) of device memory at `buffer` (16-byte
+ * aligned) once, 16 bytes per lane, with `workgroups` workgroups of 256 threads taking 4 KB chunks
+ * round-robin; pattern 0 = chunks in address order, 1 = in a scattered order (the pattern of a paged
+ * pool with 4 KB page-heads); nontemporal != 0 = loads with the streaming hint.  `sink` is device
+ * memory of `workgroups` 32-bit words (written practically never; keeps the loads alive).
+ * Enqueues on `stream` and returns; the caller times it.
+ */
+int codec_stream_read_probe(const void *buffer, size_t bytes, int32_t pattern, int32_t nontemporal,
+                            int32_t workgroups, void *sink, void *stream);
 
 /* Static, human-readable name of a status code. */
 const char *codec_status_string(int status);

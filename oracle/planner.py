@@ -8,22 +8,23 @@ found by binary search on the average-load inequality (Eq. 4), the per-node
 upper bound on the number of KV slices (Eq. 5), a grid search over each node's
 slice count, and greedy longest-first scheduling onto m slots (Eq. 3).
 
-Reading of Eq. 5.  The bound ceil(C_est / cost_l) exists to prune the search:
-the paper notes that it leaves most nodes, whose cost is far below the average
-load, undivided.  Taken to the letter it also forbids the one extra slice that
-lets a few nodes of 0.3 .. 1 average loads pack evenly onto the slots (64
-contexts of 0.4 loads each on 32 slots: two per slot, or three), so a node
-whose cost is at least a quarter of cost_l may take one slice more than the
-quotient; every other node keeps the printed bound.
+With ``slack`` and ``diagonal`` off (the defaults) this is the solver of Sec.
+5.1 as printed: b_k <= ceil(C_est / cost_l) (Eq. 5) and one node-by-node pass
+of the grid search.  The two flags mirror the library's extensions, which are
+not in the paper:
+``slack``: a node whose cost is at least a quarter of cost_l may take one slice
+more than the quotient of Eq. 5 (64 contexts of 0.4 average loads each on 32
+slots: two per slot, or three); every other node keeps the printed bound.
+``diagonal``: after the pass, nine more points of the grid are evaluated (every
+node at its Eq. 5 quotient for a common target cost_l * (1 + k/8), k = 0 .. 8,
+capped by its bound) and the best point seen is kept.
 
 The paper gives the solver in prose; where it is silent this file fixes:
 integer costs; round-half-up bilinear interpolation, clamped below the grid
 and linearly extrapolated above it; slice boundaries on multiples of
 ``align`` tokens with equal-length slices except the last; the grid search as
 one pass node by node, in order of decreasing node cost with ties to the
-smaller slice count, followed by nine points on the diagonal of the grid (every
-node at its Eq. 5 quotient for a common target cost_l * (1 + k/8), k = 0 .. 8),
-the best point seen being kept; ties in the schedule to the lower slot id.
+smaller slice count; ties in the schedule to the lower slot id.
 Python integers are unbounded, so no intermediate can overflow.
 """
 from __future__ import annotations
@@ -118,7 +119,8 @@ def build_index(parent, node_len, req_node):
 
 
 def plan(parent, node_len, req_node, group: int, num_slots: int, align: int,
-         max_rows: int, share: bool, table: Dict, fixed_slices: int = 0) -> Dict:
+         max_rows: int, share: bool, table: Dict, fixed_slices: int = 0,
+         slack: bool = False, diagonal: bool = False) -> Dict:
     parent = [int(x) for x in parent]
     node_len = [int(x) for x in node_len]
     req_node = [int(x) for x in req_node]
@@ -169,8 +171,8 @@ def plan(parent, node_len, req_node, group: int, num_slots: int, align: int,
 
     for it in items:
         want = b_of(it, cost_l)                                   # Eq. 5: the quotient
-        if 4 * it["cost"] >= cost_l:
-            want = min(want + 1, it["max_b"])                     # one slice of slack for nodes that matter
+        if slack and 4 * it["cost"] >= cost_l:
+            want = min(want + 1, it["max_b"])                     # extension: one slice over the printed bound
         it["ub"] = slices(it["len"], want, align)[0]
         it["b"] = it["ub"]
 
@@ -205,8 +207,8 @@ def plan(parent, node_len, req_node, group: int, num_slots: int, align: int,
                 best_b, best_ms = count, ms
         it["b"] = best_b
 
-    if fixed_slices == 0 and items:
-        # the pass above moves one node at a time; the search also looks along the diagonal of the grid:
+    if diagonal and fixed_slices == 0 and items:
+        # extension: the pass above moves one node at a time; the search also looks along the diagonal of the grid:
         # every node at its Eq. 5 quotient for one common target cost_l * (1 + k/8), k = 0 .. 8, capped by
         # its bound; the best point seen is kept (ties: the earlier one)
         best_ms = lpt(subtasks(), m)[0]
@@ -296,7 +298,7 @@ def refresh(plan_out: Dict, table: Dict, new_node_len) -> Dict:
 
 
 def plan_best(parent, node_len, req_node, group: int, align: int, max_rows: int, tables: Dict,
-              num_slots_of) -> Dict:
+              num_slots_of, slack: bool = False, diagonal: bool = False) -> Dict:
     """share = 2 of the library: the candidate with the lowest estimated makespan, ties to the earlier.
 
     Candidates: the prefix-shared plan with row tiles of ``max_rows``; with row tiles of half that (if
@@ -320,7 +322,7 @@ def plan_best(parent, node_len, req_node, group: int, align: int, max_rows: int,
         widest = max((min(qpt, len(q) - a) * group for q in node_q for a in range(0, len(q), qpt)), default=0)
         wide = widest > 16
         p = plan(parent, node_len, req_node, group, num_slots_of(wide), align, rows, share,
-                 tables["wide" if wide else "narrow"])
+                 tables["wide" if wide else "narrow"], slack=slack, diagonal=diagonal)
         p["share"], p["max_rows"] = share, rows
         if best is None or p["makespan"] < best["makespan"]:
             best = p

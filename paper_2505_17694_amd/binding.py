@@ -26,6 +26,8 @@ CODEC_ERR_NOT_UPLOADED = -6
 CODEC_ERR_OUT_OF_MEMORY = -7
 CODEC_DTYPE_FP16 = 0
 CODEC_DTYPE_BF16 = 1
+CODEC_PLAN_EXT_SLACK = 1
+CODEC_PLAN_EXT_DIAGONAL = 2
 
 # every symbol include/codec.h declares
 EXPORTED_SYMBOLS = [
@@ -33,7 +35,8 @@ EXPORTED_SYMBOLS = [
     "codec_default_cost_table", "codec_plan_device_bytes", "codec_plan_upload",
     "codec_plan_workspace_bytes", "codec_decode_attention", "codec_partial_attention",
     "codec_partial_reduction", "codec_status_string", "codec_last_error_message",
-    "codec_plan_refresh_lengths",
+    "codec_plan_refresh_lengths", "codec_decode_attention_static", "codec_static_scratch_bytes",
+    "codec_stream_read_probe",
 ]
 
 _i32p = POINTER(c_int32)
@@ -59,7 +62,7 @@ class codec_cost_table(Structure):
 class codec_plan_options(Structure):
     _fields_ = [("num_slots", c_int32), ("split_align", c_int32), ("max_rows", c_int32),
                 ("share", c_int32), ("cost", POINTER(codec_cost_table)), ("fixed_slices", c_int32),
-                ("schedule", c_int32)]
+                ("schedule", c_int32), ("extensions", c_int32)]
 
 
 class codec_item(Structure):
@@ -131,6 +134,13 @@ _lib.codec_partial_attention.argtypes = [c_void_p, c_void_p, c_void_p, c_void_p,
                                          POINTER(codec_kv_layout), c_void_p, c_size_t, c_void_p]
 _lib.codec_partial_reduction.restype = c_int
 _lib.codec_partial_reduction.argtypes = [c_void_p, c_void_p, c_size_t, c_void_p, c_void_p]
+_lib.codec_decode_attention_static.restype = c_int
+_lib.codec_decode_attention_static.argtypes = [c_void_p, c_void_p, c_void_p, c_void_p,
+                                               POINTER(codec_kv_layout), c_void_p, c_void_p]
+_lib.codec_static_scratch_bytes.restype = c_size_t
+_lib.codec_static_scratch_bytes.argtypes = []
+_lib.codec_stream_read_probe.restype = c_int
+_lib.codec_stream_read_probe.argtypes = [c_void_p, c_size_t, c_int32, c_int32, c_int32, c_void_p, c_void_p]
 _lib.codec_status_string.restype = c_char_p
 _lib.codec_status_string.argtypes = [c_int]
 _lib.codec_last_error_message.restype = c_char_p
@@ -171,7 +181,7 @@ def codec_last_error_message() -> str:
 def codec_plan_create(parent, node_len, req_node, node_page_off, page_ids,
                       num_q_heads, num_kv_heads, head_dim, dtype, page_size, scale,
                       num_slots=0, split_align=0, max_rows=0, share=1, cost_table=None, fixed_slices=0,
-                      schedule=0):
+                      schedule=0, extensions=0):
     """Returns (status, plan handle or None).  ``cost_table``: (row_grid, len_grid, cost) or None."""
     parent, node_len, req_node = _i32(parent), _i32(node_len), _i32(req_node)
     node_page_off, page_ids = _i32(node_page_off), _i32(page_ids)
@@ -183,7 +193,8 @@ def codec_plan_create(parent, node_len, req_node, node_page_off, page_ids,
     if cost_table is not None:
         ct, keep = make_cost_table(*cost_table)
         ct_ptr = ctypes.pointer(ct)
-    opt = codec_plan_options(num_slots, split_align, max_rows, share, ct_ptr, fixed_slices, schedule)
+    opt = codec_plan_options(num_slots, split_align, max_rows, share, ct_ptr, fixed_slices, schedule,
+                             extensions)
     handle = c_void_p()
     st = _lib.codec_plan_create(byref(tree), byref(head), byref(opt), byref(handle))
     del keep
@@ -282,3 +293,21 @@ def codec_partial_reduction(plan, workspace_ptr: int, workspace_bytes: int, out_
                             stream: int = 0) -> int:
     return _lib.codec_partial_reduction(plan, c_void_p(workspace_ptr), workspace_bytes,
                                         c_void_p(out_ptr), c_void_p(stream))
+
+
+def codec_decode_attention_static(plan, q_ptr: int, k_ptr: int, v_ptr: int, num_pages: int,
+                                  page_stride: int, token_stride: int, head_stride: int, out_ptr: int,
+                                  stream: int = 0) -> int:
+    lay = codec_kv_layout(num_pages, page_stride, token_stride, head_stride)
+    return _lib.codec_decode_attention_static(plan, c_void_p(q_ptr), c_void_p(k_ptr), c_void_p(v_ptr),
+                                              byref(lay), c_void_p(out_ptr), c_void_p(stream))
+
+
+def codec_static_scratch_bytes() -> int:
+    return int(_lib.codec_static_scratch_bytes())
+
+
+def codec_stream_read_probe(buffer_ptr: int, nbytes: int, pattern: int, nontemporal: int, workgroups: int,
+                            sink_ptr: int, stream: int = 0) -> int:
+    return _lib.codec_stream_read_probe(c_void_p(buffer_ptr), nbytes, pattern, nontemporal, workgroups,
+                                        c_void_p(sink_ptr), c_void_p(stream))

@@ -149,15 +149,18 @@ int64_t codec_cost_estimate(const codec_cost_table *table, int32_t rows, int32_t
 
 const codec_cost_table *codec_default_cost_table(int32_t wide)
 {
-    static codec_cost_table views[2];
-    const codec::CostTable &t = codec::builtin_cost_table(wide != 0);
-    codec_cost_table &view = views[wide != 0];
-    view.num_row_points = int32_t(t.row_grid.size());
-    view.num_len_points = int32_t(t.len_grid.size());
-    view.row_grid = t.row_grid.data();
-    view.len_grid = t.len_grid.data();
-    view.cost = t.cost.data();
-    return &view;
+    auto view_of = [](bool w) {
+        const codec::CostTable &t = codec::builtin_cost_table(w);
+        codec_cost_table v;
+        v.num_row_points = int32_t(t.row_grid.size());
+        v.num_len_points = int32_t(t.len_grid.size());
+        v.row_grid = t.row_grid.data();
+        v.len_grid = t.len_grid.data();
+        v.cost = t.cost.data();
+        return v;
+    };
+    static const codec_cost_table views[2] = {view_of(false), view_of(true)};   // built once, never rewritten
+    return &views[wide != 0];
 }
 
 size_t codec_plan_device_bytes(const codec_plan_t *plan)
@@ -170,6 +173,7 @@ int codec_plan_upload(codec_plan_t *plan, void *device_meta, size_t device_meta_
     if (!plan || !device_meta) return CODEC_ERR_INVALID_ARGUMENT;
     if (device_meta_bytes < plan->d.layout.total) return CODEC_ERR_WORKSPACE_TOO_SMALL;
     if (reinterpret_cast<uintptr_t>(device_meta) & 255u) return CODEC_ERR_INVALID_ARGUMENT;
+    if (int e = codec::prepare_kernels()) return hip_failure("hipFuncSetAttribute(dynamic LDS size)", e);
     hipStream_t s = static_cast<hipStream_t>(stream);
     if (hipError_t e = hipMemcpyAsync(device_meta, plan->d.blob.data(), plan->d.layout.total, hipMemcpyHostToDevice, s))
         return hip_failure("hipMemcpyAsync(plan metadata)", int(e));
@@ -202,8 +206,9 @@ int codec_partial_attention(const codec_plan_t *plan, const void *q, const void 
     if (layout->page_stride < 1 || layout->token_stride < 128 || layout->head_stride < 128 ||
         layout->page_stride % 8 || layout->token_stride % 8 || layout->head_stride % 8)
         return CODEC_ERR_INVALID_ARGUMENT;
-    // the kernels keep a page's and a token's size in bytes in 32 bits
-    if (layout->page_stride > (int64_t(1) << 30) || layout->token_stride > (int64_t(1) << 30))
+    // the kernels keep a page's size in bytes, and every byte offset of a token inside its page, in 32 bits
+    if (layout->page_stride > (int64_t(1) << 30) || layout->token_stride > (int64_t(1) << 30) ||
+        int64_t(d.head.page_size) * layout->token_stride * 2 >= (int64_t(1) << 32))
         return CODEC_ERR_INVALID_ARGUMENT;
 
     const char *meta = static_cast<const char *>(plan->device_meta);
@@ -280,6 +285,39 @@ int codec_decode_attention(const codec_plan_t *plan, const void *q, const void *
     if (int st = codec_partial_attention(plan, q, k_pages, v_pages, layout, workspace, workspace_bytes, stream))
         return st;
     return codec_partial_reduction(plan, workspace, workspace_bytes, out, stream);
+}
+
+int codec_decode_attention_static(const codec_plan_t *plan, const void *q, const void *k_pages,
+                                  const void *v_pages, const codec_kv_layout *layout, void *out, void *stream)
+{
+    if (!plan) return CODEC_ERR_INVALID_ARGUMENT;
+    const size_t need = codec_plan_workspace_bytes(plan);
+    if (need > codec::kStaticScratchBytes) {
+        std::snprintf(g_last_error, sizeof g_last_error,
+                      "codec_decode_attention_static: the plan needs %zu bytes of scratch, the library holds %zu",
+                      need, codec::kStaticScratchBytes);
+        return CODEC_ERR_WORKSPACE_TOO_SMALL;
+    }
+    void *ws = nullptr;
+    if (int e = codec::static_scratch_address(&ws)) return hip_failure("hipGetSymbolAddress(scratch)", e);
+    return codec_decode_attention(plan, q, k_pages, v_pages, layout, out, ws, codec::kStaticScratchBytes, stream);
+}
+
+size_t codec_static_scratch_bytes(void) { return codec::kStaticScratchBytes; }
+
+int codec_stream_read_probe(const void *buffer, size_t bytes, int32_t pattern, int32_t nontemporal,
+                            int32_t workgroups, void *sink, void *stream)
+{
+    if (!buffer || !sink || workgroups < 1 || workgroups > (1 << 20)) return CODEC_ERR_INVALID_ARGUMENT;
+    if (pattern != 0 && pattern != 1) return CODEC_ERR_INVALID_ARGUMENT;
+    if (!aligned16(buffer)) return CODEC_ERR_INVALID_ARGUMENT;
+    const uint64_t chunks = bytes / 4096;
+    if (chunks < 1 || (chunks & (chunks - 1)) != 0 || chunks * 4096 != bytes) return CODEC_ERR_INVALID_ARGUMENT;
+    // pattern 1: chunk c of the walk is chunk c * mult mod chunks, an odd multiplier near chunks / phi
+    const uint64_t mult = pattern == 0 ? 1 : ((uint64_t(double(chunks) * 0.6180339887498949) | 1u));
+    if (int e = codec::launch_stream_read(buffer, chunks, mult, nontemporal != 0, workgroups, sink, stream))
+        return hip_failure("stream read launch", e);
+    return CODEC_OK;
 }
 
 const char *codec_last_error_message(void) { return g_last_error; }

@@ -35,6 +35,7 @@
 // loaded with the streaming (nontemporal) hint; the plan marks those tasks.
 #include <hip/hip_runtime.h>
 
+#include <mutex>
 #include <type_traits>
 
 #include "kernels.hpp"
@@ -1186,15 +1187,72 @@ __global__ void __launch_bounds__(kMergeWaves * 64) merge_kernel(const MergePara
     *out = pack2<DT>(a0 * inv, a1 * inv);
 }
 
+
+// Read-only streaming kernel (measurement support): every thread sums 16-byte loads; a workgroup takes
+// whole 4 KB chunks, chunk c of the walk being chunk perm(c) of the buffer, so that the order can be
+// that of a paged pool.  One value per workgroup is written so that the loads cannot be dropped.
+template <bool ONCE>
+__global__ void __launch_bounds__(256) stream_read_kernel(const char *buf, uint64_t chunks, uint64_t mult,
+                                                          uint32_t *sink)
+{
+    u32x4 acc = {0u, 0u, 0u, 0u};
+    for (uint64_t c = blockIdx.x; c < chunks; c += gridDim.x) {
+        const uint64_t at = (c * mult) & (chunks - 1);          // chunks is a power of two, mult odd: a permutation
+        const char *p = buf + at * 4096 + threadIdx.x * 16;
+        const u32x4 x = ONCE ? ld16_once(p) : ld16(p);
+        acc ^= x;
+    }
+    const uint32_t v = acc[0] ^ acc[1] ^ acc[2] ^ acc[3];
+    if (v == 0x9E3779B9u && threadIdx.x == 0) sink[blockIdx.x] = v;       // practically never: keeps the loads alive
+}
+
 }  // namespace
 
-// The wide variant needs more dynamic LDS than the 64 KB a kernel gets by default.
-template <typename K>
-int allow_ring_lds(K kernel)
+// Scratch for callers that cannot provide a workspace (codec_decode_attention_static): partial outputs
+// and their softmax statistics of one decode call.  Every GPU the library is loaded on holds one copy
+// of this array at an address of its own until the process ends.  In host code the name below is only a
+// handle for hipGetSymbolAddress; kernels get the address that call returns, as an ordinary argument.
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+int static_scratch_address(void **ptr)
 {
-    static int status = int(hipFuncSetAttribute(reinterpret_cast<const void *>(kernel),
-                                                hipFuncAttributeMaxDynamicSharedMemorySize, kRingBytes));
-    return status;
+    // one lookup per device, with that device current; the table is filled under a lock and read-only after
+    constexpr int kMaxDevices = 64;
+    static void *address[kMaxDevices] = {};
+    static std::mutex lock;
+    int dev = -1;
+    if (hipError_t e = hipGetDevice(&dev)) return int(e);
+    if (dev < 0 || dev >= kMaxDevices) return int(hipErrorInvalidDevice);
+    std::lock_guard<std::mutex> guard(lock);
+    if (!address[dev]) {
+        void *p = nullptr;
+        if (hipError_t e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch))) return int(e);
+        address[dev] = p;
+    }
+    *ptr = address[dev];
+    return 0;
+}
+
+// The wide variant needs more dynamic LDS than the 64 KB a kernel gets by default.  Set once per
+// process and device, outside any stream capture (codec_plan_upload calls this).
+int prepare_kernels()
+{
+    constexpr int kMaxDevices = 64;
+    static bool done[kMaxDevices] = {};
+    static std::mutex lock;
+    int dev = -1;
+    if (hipError_t e = hipGetDevice(&dev)) return int(e);
+    if (dev < 0 || dev >= kMaxDevices) return int(hipErrorInvalidDevice);
+    std::lock_guard<std::mutex> guard(lock);
+    if (done[dev]) return 0;
+    if (hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(pac_kernel<CODEC_DTYPE_FP16, 1>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, kRingBytes))
+        return int(e);
+    if (hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(pac_kernel<CODEC_DTYPE_BF16, 1>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, kRingBytes))
+        return int(e);
+    done[dev] = true;
+    return 0;
 }
 
 int launch_pac(const PacParams &p, int dtype, int num_slots, int max_rows_in_plan, void *stream)
@@ -1203,15 +1261,22 @@ int launch_pac(const PacParams &p, int dtype, int num_slots, int max_rows_in_pla
     const dim3 grid(unsigned(num_slots) * unsigned(p.h_kv)), block((wide ? kWideWaves : kNarrowWaves) * 64);
     hipStream_t s = static_cast<hipStream_t>(stream);
     if (wide) {
-        auto k16 = pac_kernel<CODEC_DTYPE_FP16, 1>;
-        auto kbf = pac_kernel<CODEC_DTYPE_BF16, 1>;
-        if (int e = (dtype == CODEC_DTYPE_FP16 ? allow_ring_lds(k16) : allow_ring_lds(kbf))) return e;
-        if (dtype == CODEC_DTYPE_FP16) hipLaunchKernelGGL(k16, grid, block, kRingBytes, s, p);
-        else                           hipLaunchKernelGGL(kbf, grid, block, kRingBytes, s, p);
+        if (dtype == CODEC_DTYPE_FP16) hipLaunchKernelGGL((pac_kernel<CODEC_DTYPE_FP16, 1>), grid, block, kRingBytes, s, p);
+        else                           hipLaunchKernelGGL((pac_kernel<CODEC_DTYPE_BF16, 1>), grid, block, kRingBytes, s, p);
     } else {
         if (dtype == CODEC_DTYPE_FP16) hipLaunchKernelGGL((pac_kernel<CODEC_DTYPE_FP16, 0>), grid, block, 0, s, p);
         else                           hipLaunchKernelGGL((pac_kernel<CODEC_DTYPE_BF16, 0>), grid, block, 0, s, p);
     }
+    return int(hipGetLastError());
+}
+
+int launch_stream_read(const void *buf, uint64_t chunks, uint64_t mult, int once, int blocks, void *sink, void *stream)
+{
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const char *b = static_cast<const char *>(buf);
+    uint32_t *k = static_cast<uint32_t *>(sink);
+    if (once) hipLaunchKernelGGL(stream_read_kernel<true>, dim3(unsigned(blocks)), dim3(256), 0, s, b, chunks, mult, k);
+    else      hipLaunchKernelGGL(stream_read_kernel<false>, dim3(unsigned(blocks)), dim3(256), 0, s, b, chunks, mult, k);
     return int(hipGetLastError());
 }
 

@@ -1,6 +1,7 @@
 // Launch interface of the gfx950 kernels (partial attention and partial-output reduction).
 #pragma once
 
+#include <cstddef>
 #include <cstdint>
 
 #include "planner.hpp"
@@ -39,6 +40,20 @@ struct MergeParams {
     void *out;                      // [B][h_q][128], 16-bit
     int32_t num_requests, h_q, group, part_rows;
 };
+
+// Size of the library's own scratch array (one per GPU) behind codec_decode_attention_static.
+constexpr size_t kStaticScratchBytes = size_t(64) << 20;
+
+// Address of that array on the current device (looked up once per device); returns a hipError_t value.
+int static_scratch_address(void **ptr);
+
+// One-off kernel attributes for the current device (dynamic LDS size of the wide variant); a
+// hipError_t value.  Not to be called under stream capture; launches need it to have run once.
+int prepare_kernels();
+
+// Read-only streaming kernel over `chunks` (a power of two) 4 KB chunks in the order c -> c * mult mod
+// chunks (mult odd); `once` = nontemporal loads; `sink` holds one word per workgroup.
+int launch_stream_read(const void *buf, uint64_t chunks, uint64_t mult, int once, int blocks, void *sink, void *stream);
 
 // Both return a hipError_t value (0 = success) without synchronising.
 // `max_rows_in_plan` selects the register-budget variant of the attention kernel.

@@ -8,7 +8,8 @@
 // integer costs, round-half-up bilinear interpolation, slices of equal length
 // on aligned boundaries, one grid-search pass in order of decreasing node cost
 // with ties to fewer slices, longest-first scheduling with ties to the lower
-// slot id.
+// slot id.  Two extensions of that solver (a slice of slack over Eq. 5, extra
+// search points on the diagonal of the grid) are options, off unless asked for.
 #include "planner.hpp"
 
 #include <algorithm>
@@ -292,6 +293,10 @@ int build_plan(const codec_tree &tree, const codec_head_config &head,
     if (opt.share != 0 && opt.share != 1) return CODEC_ERR_INVALID_ARGUMENT;
     if (opt.fixed_slices < 0) return CODEC_ERR_INVALID_ARGUMENT;
     if (opt.schedule < 0 || opt.schedule > 2) return CODEC_ERR_INVALID_ARGUMENT;
+    if (opt.extensions < 0 || opt.extensions > (CODEC_PLAN_EXT_SLACK | CODEC_PLAN_EXT_DIAGONAL))
+        return CODEC_ERR_INVALID_ARGUMENT;
+    const bool ext_slack = (opt.extensions & CODEC_PLAN_EXT_SLACK) != 0;
+    const bool ext_diagonal = (opt.extensions & CODEC_PLAN_EXT_DIAGONAL) != 0;
 
     CostTable user;
     const CostTable *table = nullptr;           // nullptr: the built-in table of the kernel variant
@@ -425,12 +430,13 @@ int build_plan(const codec_tree &tree, const codec_head_config &head,
         }
         p.cost_l = lo;
     }
-    // Eq. 5 prunes the search (most nodes cost far less than the average load and stay whole).  A node
-    // whose cost is at least a quarter of cost_l may take one slice more than the quotient: without it
-    // a few nodes of 0.3 .. 1 average loads cannot be packed evenly onto the slots.
+    // Eq. 5 prunes the search (most nodes cost far less than the average load and stay whole).
+    // Extension (CODEC_PLAN_EXT_SLACK, not in the paper): a node whose cost is at least a quarter of
+    // cost_l may take one slice more than the quotient: without it a few nodes of 0.3 .. 1 average
+    // loads cannot be packed evenly onto the slots.
     for (size_t j = 0; j < J; ++j) {
         int64_t want = slices_at(j, p.cost_l);
-        if (4 * p.items[j].cost >= p.cost_l) want = std::min(want + 1, max_b[j]);
+        if (ext_slack && 4 * p.items[j].cost >= p.cost_l) want = std::min(want + 1, max_b[j]);
         p.items[j].ub = slice_node(p.items[j].len, want, align).count;
         p.items[j].b = p.items[j].ub;
     }
@@ -489,16 +495,17 @@ int build_plan(const codec_tree &tree, const codec_head_config &head,
             }
             it.b = best_b;
         }
-        // The pass above moves one node at a time and stops where no single move helps; equal nodes
-        // started at their bound can stay one slice short of an even packing.  So the search also
-        // looks along the diagonal of the grid: every node at its Eq. 5 quotient for one common target
-        // cost_l * (1 + k/8), k = 0 .. 8 (capped by its bound), and keeps the best point seen.
+        // Extension (CODEC_PLAN_EXT_DIAGONAL, not in the paper).  The pass above moves one node at a
+        // time and stops where no single move helps; equal nodes started at their bound can stay one
+        // slice short of an even packing.  So the search also looks along the diagonal of the grid:
+        // every node at its Eq. 5 quotient for one common target cost_l * (1 + k/8), k = 0 .. 8 (capped
+        // by its bound), and keeps the best point seen.
         expand();
         schedule_lpt(sub, m, false, trial);
         int64_t best_ms = trial.makespan;
         std::vector<int32_t> best_b(J);
         for (size_t j = 0; j < J; ++j) best_b[j] = p.items[j].b;
-        for (int k = 0; k <= 8; ++k) {
+        for (int k = 0; ext_diagonal && k <= 8; ++k) {
             const int64_t target = std::max<int64_t>(1, p.cost_l + p.cost_l * k / 8);
             for (size_t j = 0; j < J; ++j) {
                 const int64_t want = std::min<int64_t>(p.items[j].ub, slices_at(j, target));

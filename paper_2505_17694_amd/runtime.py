@@ -16,12 +16,14 @@ class PlannedAttention:
     """
 
     def __init__(self, forest, paged, head, device="cuda:0", num_slots=0, split_align=0,
-                 max_rows=0, share=1, cost_table=None, fixed_slices=0, schedule=0):
+                 max_rows=0, share=1, cost_table=None, fixed_slices=0, schedule=0,
+                 extensions=0):
         st, plan = B.codec_plan_create(forest.parent, forest.node_len, forest.req_node,
                                        paged.node_page_off, paged.page_ids,
                                        head.num_q_heads, head.num_kv_heads, head.head_dim,
                                        head.dtype, head.page_size, head.scale,
-                                       num_slots, split_align, max_rows, share, cost_table, fixed_slices, schedule)
+                                       num_slots, split_align, max_rows, share, cost_table, fixed_slices, schedule,
+                                       extensions)
         if st != B.CODEC_OK:
             raise B.CodecError(st, "codec_plan_create")
         self.plan = plan
@@ -74,12 +76,23 @@ class PlannedAttention:
             raise ValueError(f"{what}: {have} elements from the tensor's first one on {pool.device}, "
                              f"the page table and strides reach {last} on {self.device}")
 
+    def _check_rows(self, t: torch.Tensor, what: str) -> None:
+        """q and out are dense [num_requests][num_q_heads][head_dim] tensors of the plan's dtype on its device."""
+        h = self.head
+        want = (self.num_requests, h.num_q_heads, h.head_dim)
+        if (tuple(t.shape) != want or t.dtype != h.torch_dtype or t.device != self.device
+                or not t.is_contiguous()):
+            raise ValueError(f"{what}: need a contiguous {h.torch_dtype} tensor of shape {want} on {self.device}, "
+                             f"got {t.dtype} {tuple(t.shape)} on {t.device}, contiguous={t.is_contiguous()}")
+
     def decode(self, q: torch.Tensor, k_pool: torch.Tensor, v_pool: torch.Tensor,
                out: torch.Tensor = None, stream=None) -> torch.Tensor:
         self._check_pool(k_pool, "k_pool")
         self._check_pool(v_pool, "v_pool")
+        self._check_rows(q, "q")
         if out is None:
             out = torch.empty_like(q)
+        self._check_rows(out, "out")
         s = (stream or torch.cuda.current_stream(self.device)).cuda_stream
         p = self.paged
         st = B.codec_decode_attention(self.plan, q.data_ptr(), k_pool.data_ptr(), v_pool.data_ptr(),
@@ -93,6 +106,7 @@ class PlannedAttention:
     def partial_attention(self, q, k_pool, v_pool, stream=None) -> None:
         self._check_pool(k_pool, "k_pool")
         self._check_pool(v_pool, "v_pool")
+        self._check_rows(q, "q")
         s = (stream or torch.cuda.current_stream(self.device)).cuda_stream
         p = self.paged
         st = B.codec_partial_attention(self.plan, q.data_ptr(), k_pool.data_ptr(), v_pool.data_ptr(),
@@ -102,6 +116,7 @@ class PlannedAttention:
             raise B.CodecError(st, "codec_partial_attention")
 
     def partial_reduction(self, out, stream=None) -> None:
+        self._check_rows(out, "out")
         s = (stream or torch.cuda.current_stream(self.device)).cuda_stream
         st = B.codec_partial_reduction(self.plan, self.workspace.data_ptr(), self.workspace.numel(),
                                        out.data_ptr(), s)

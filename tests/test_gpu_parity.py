@@ -334,7 +334,7 @@ def test_random_forests_heads_and_plan_options(seed):
     opts = {"num_slots": int(rng.choice([0, 1, 5, 17])),
             "split_align": int(rng.choice([1, 2, 8])) * max(32, page_size),
             "max_rows": int(rng.choice([0, 0, 16, 64, 128, 200])),
-            "schedule": int(rng.integers(0, 2))}
+            "schedule": int(rng.integers(0, 2)), "extensions": int(rng.integers(0, 4))}
     if opts["max_rows"] and opts["max_rows"] < hq // hkv:
         opts["max_rows"] = 0
     check(w, share=int(rng.choice([1, 1, 0, 2])), **opts)
@@ -473,26 +473,41 @@ def _sample_pairs(w, n, seed):
     return [(int(i // H), int(i % H)) for i in idx]
 
 
-@pytest.mark.parametrize("name,n_pairs", [("cfg1", 10 ** 9), ("cfg2", 10 ** 9), ("cfg3", 1024),
-                                          ("cfg4", 1024), ("cfg5a", 96), ("cfg5b", 96), ("cfg5c", 96)])
-def test_full_size_configurations_on_sampled_outputs(name, n_pairs):
-    """Inputs are generated on the GPU, copied back for the oracle; sampled (request, head) pairs."""
-    w = make_config(name, device="cuda:0")
+# what bench.py times: layout "htd"; the prefix-shared plan with both planner extensions ("tree", the
+# headline), the solver of Sec. 5.1 as printed, the flat plan, the run-time queue, the library's own
+# choice of plan and schedule
+BENCH_VARIANTS = [
+    {"share": 1, "schedule": 0, "extensions": 3},
+    {"share": 1, "schedule": 0, "extensions": 0},
+    {"share": 0, "schedule": 0, "extensions": 0},
+    {"share": 1, "schedule": 1, "extensions": 3},
+    {"share": 2, "schedule": 2, "extensions": 3},
+]
+
+
+@pytest.mark.parametrize("name,layout,n_pairs", [
+    ("cfg1", "htd", 10 ** 9), ("cfg2", "htd", 10 ** 9), ("cfg3", "htd", 10 ** 9), ("cfg4", "htd", 10 ** 9),
+    ("cfg5a", "htd", 10 ** 9), ("cfg5b", "htd", 10 ** 9), ("cfg5c", "htd", 10 ** 9),
+    ("cfg3", "thd", 1024), ("cfg4", "hktd", 1024)])
+def test_full_size_configurations(name, layout, n_pairs):
+    """Inputs are generated on the GPU and copied back for the oracle.  In the benchmark's layout every
+    (request, head) pair of every configuration is compared (the oracle needs about ten seconds for
+    the largest); the other two layouts are sampled."""
+    w = make_config(name, device="cuda:0", layout=layout)
     C = _C()
-    print(f"[case] full {name} unique_kv_bytes={w.unique_kv_bytes}", flush=True)
+    print(f"[case] full {name} {layout} unique_kv_bytes={w.unique_kv_bytes}", flush=True)
     sel = _sample_pairs(w, n_pairs, seed=77)
-    ref = None
-    for share, schedule in ((1, 0), (0, 0), (1, 1)):        # shared plan, flat plan, shared plan from the queue
-        pa = C.PlannedAttention(w.forest, w.paged, w.head, device="cuda:0", share=share, schedule=schedule)
+    ref, _ = A.decode_attention_workload(w, sel=sel)
+    print(f"[case] full {name} {layout}: oracle done on {len(sel)} pairs", flush=True)
+    for opts in BENCH_VARIANTS:
+        pa = C.PlannedAttention(w.forest, w.paged, w.head, device="cuda:0", **opts)
         out = pa.decode(w.q, w.k_pool, w.v_pool)
         torch.cuda.synchronize()
         got = out.to(torch.float64).cpu().numpy()
         pa.close()
-        if ref is None:
-            ref, _ = A.decode_attention_workload(w, sel=sel)
         g = np.stack([got[r, h] for r, h in sel])
         err = np.abs(g - ref)
-        print(f"[case] full {name} share={share} schedule={schedule} max_err={err.max():.3e}", flush=True)
+        print(f"[case] full {name} {layout} {opts} max_err={err.max():.3e}", flush=True)
         assert not np.any(np.isnan(got))
         assert err.max() <= TOL
         assert np.all(err <= 2e-3 + 2.0 ** -7 * np.abs(ref))

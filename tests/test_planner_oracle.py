@@ -123,7 +123,7 @@ def test_hand_worked_three_node_plan():
     assert p["part_rows"] == 8
 
 
-def _check_invariants(f, p, group, m, align):
+def _check_invariants(f, p, group, m, align, slack=False):
     n_q = np.zeros(f.num_nodes, dtype=np.int64)
     for r in range(f.num_requests):
         for n in f.path(r):
@@ -148,11 +148,11 @@ def _check_invariants(f, p, group, m, align):
     assert max(loads) == p["makespan"]
     total = sum(t["cost"] for t in p["tasks"])
     assert p["makespan"] >= max(-(-total // m), max(t["cost"] for t in p["tasks"]))
-    # Eq. 5: slice counts stay within the bound derived from cost_l (the quotient, plus one slice for a
-    # node whose cost is at least a quarter of cost_l)
+    # Eq. 5 as printed: b_k <= ceil(C_est / cost_l).  Only under the library's slack extension may a
+    # node whose cost is at least a quarter of cost_l exceed it, and then by one slice.
     for it in p["items"]:
-        slack = 1 if 4 * it["cost"] >= p["cost_l"] else 0
-        assert 1 <= it["b"] <= it["ub"] <= max(1, -(-it["cost"] // p["cost_l"])) + slack
+        over = 1 if slack and 4 * it["cost"] >= p["cost_l"] else 0
+        assert 1 <= it["b"] <= it["ub"] <= max(1, -(-it["cost"] // p["cost_l"])) + over
     # Eq. 4 at cost_l: the division it induces fits m slots on average, the next finer T does not
     def tot(T):
         return sum(P.division_cost(p["table"], it["rows"], it["len"],
@@ -180,11 +180,18 @@ FORESTS = {
 @pytest.mark.parametrize("name", sorted(FORESTS))
 @pytest.mark.parametrize("share", [True, False])
 @pytest.mark.parametrize("m,align,max_rows,group", [(8, 256, 64, 4), (3, 32, 16, 8), (64, 64, 64, 1)])
-def test_plan_invariants(name, share, m, align, max_rows, group):
+@pytest.mark.parametrize("slack,diagonal", [(False, False), (True, False), (False, True), (True, True)])
+def test_plan_invariants(name, share, m, align, max_rows, group, slack, diagonal):
+    """With both extensions off the bound asserted is the printed Eq. 5, with no slack term."""
     f = FORESTS[name]()
-    p = P.plan(f.parent, f.node_len, f.req_node, group, m, align, max_rows, share, TABLE2)
+    p = P.plan(f.parent, f.node_len, f.req_node, group, m, align, max_rows, share, TABLE2,
+               slack=slack, diagonal=diagonal)
     p["table"] = TABLE2
-    _check_invariants(f, p, group, m, align)
+    _check_invariants(f, p, group, m, align, slack=slack)
+    if not slack and not diagonal:
+        # extensions only ever add candidates to the search: the printed solver's makespan is an upper bound
+        q = P.plan(f.parent, f.node_len, f.req_node, group, m, align, max_rows, share, TABLE2, diagonal=True)
+        assert q["makespan"] <= p["makespan"]
 
 
 def test_docqa_leaves_are_not_divided():
@@ -374,16 +381,24 @@ def test_slice_bound_slack_hand_worked():
     """
     f = unshared_forest([1000] * 8 + [100])
     p = P.plan(f.parent, f.node_len, f.req_node, group=1, num_slots=4, align=100,
-               max_rows=64, share=True, table=LINEAR)
+               max_rows=64, share=True, table=LINEAR, slack=True)
     assert p["cost_l"] == 2025
     assert [it["ub"] for it in p["items"]] == [2] * 8 + [1]
     assert p["makespan"] == 2100
+    strict = P.plan(f.parent, f.node_len, f.req_node, group=1, num_slots=4, align=100,
+                    max_rows=64, share=True, table=LINEAR)
+    assert strict["cost_l"] == 2025 and [it["ub"] for it in strict["items"]] == [1] * 9      # Eq. 5 as printed
+    assert strict["makespan"] == 2100
     # three contexts of 1000 on 2 slots: whole -> 2000; the slack lets one be halved -> 1500
     g = unshared_forest([1000] * 3)
     q = P.plan(g.parent, g.node_len, g.req_node, group=1, num_slots=2, align=100,
-               max_rows=64, share=True, table=LINEAR)
+               max_rows=64, share=True, table=LINEAR, slack=True)
     assert q["cost_l"] == 1500 and [it["ub"] for it in q["items"]] == [2, 2, 2]
     assert q["makespan"] == 1500 and sorted(it["b"] for it in q["items"]) == [1, 1, 2]
+    # the printed bound: ceil(1000 / 1500) = 1 slice each, nothing to search, two contexts on one slot
+    q0 = P.plan(g.parent, g.node_len, g.req_node, group=1, num_slots=2, align=100,
+                max_rows=64, share=True, table=LINEAR)
+    assert q0["cost_l"] == 1500 and [it["ub"] for it in q0["items"]] == [1, 1, 1] and q0["makespan"] == 2000
 
 
 def test_diagonal_of_the_grid_hand_worked():
@@ -397,8 +412,19 @@ def test_diagonal_of_the_grid_hand_worked():
     (4, 4), packs 8 slices of 300 onto the 8 slots: makespan 300, which is the lower bound.
     """
     f = unshared_forest([1200, 1200])
+    # Sec. 5.1 as printed: bound 4 each; from (4, 4): first node 3 slices of 400 beside 4 of 300 -> 7 tasks
+    # on 8 slots, makespan 400; 4 slices -> 8 x 300 on 8 slots, 300: kept; second node likewise stays at 4
+    p0 = P.plan(f.parent, f.node_len, f.req_node, group=1, num_slots=8, align=20,
+                max_rows=64, share=True, table=LINEAR)
+    assert p0["cost_l"] == 300 and [it["ub"] for it in p0["items"]] == [4, 4]
+    assert [it["b"] for it in p0["items"]] == [4, 4] and p0["makespan"] == 300
+    # with the slack alone the pass starts from (5, 5) and stops at (3, 3), as worked out above
+    p1 = P.plan(f.parent, f.node_len, f.req_node, group=1, num_slots=8, align=20,
+                max_rows=64, share=True, table=LINEAR, slack=True)
+    assert [it["ub"] for it in p1["items"]] == [5, 5] and [it["b"] for it in p1["items"]] == [3, 3]
+    assert p1["makespan"] == 400
     p = P.plan(f.parent, f.node_len, f.req_node, group=1, num_slots=8, align=20,
-               max_rows=64, share=True, table=LINEAR)
+               max_rows=64, share=True, table=LINEAR, slack=True, diagonal=True)
     assert p["cost_l"] == 300
     assert [it["ub"] for it in p["items"]] == [5, 5]
     assert [it["b"] for it in p["items"]] == [4, 4]

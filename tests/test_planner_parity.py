@@ -29,12 +29,12 @@ def _default_table(wide=1):
     return {"row_grid": rg, "len_grid": lg, "cost": c}
 
 
-def _lib_plan(f, head, m, align, max_rows, share, table):
+def _lib_plan(f, head, m, align, max_rows, share, table, extensions=0):
     paged = build_paged_kv(f, head, seed=1)
     st, plan = C.codec_plan_create(f.parent, f.node_len, f.req_node, paged.node_page_off, paged.page_ids,
                                    head.num_q_heads, head.num_kv_heads, head.head_dim, head.dtype,
                                    head.page_size, head.scale, m, align, max_rows, int(share),
-                                   _tuple(table) if table is not None else None)
+                                   _tuple(table) if table is not None else None, extensions=extensions)
     assert st == C.CODEC_OK, C.codec_status_string(st)
     st, view = C.codec_plan_export(plan)
     assert st == C.CODEC_OK
@@ -90,31 +90,42 @@ FORESTS = {
 @pytest.mark.parametrize("m,align,max_rows,hq,hkv,table", [
     (8, 256, 64, 32, 8, "table2"), (3, 32, 16, 8, 1, "default"), (64, 64, 256, 8, 8, "table2"),
     (17, 32, 7, 28, 4, "default"), (32, 256, 130, 64, 8, "default")])
-def test_library_plan_equals_rederivation(name, share, m, align, max_rows, hq, hkv, table):
+@pytest.mark.parametrize("extensions", [0, 1, 2, 3])
+def test_library_plan_equals_rederivation(name, share, m, align, max_rows, hq, hkv, table, extensions):
+    """extensions = 0 is the solver of Sec. 5.1 as printed; bit 0 the slack over Eq. 5, bit 1 the diagonal."""
     f = FORESTS[name]()
     head = HeadConfig(hq, hkv, 128)
-    view = _lib_plan(f, head, m, align, max_rows, share, TABLE2 if table == "table2" else None)
+    view = _lib_plan(f, head, m, align, max_rows, share, TABLE2 if table == "table2" else None, extensions)
     # without a caller's table the library takes the built-in one of the kernel variant the plan needs
     wide = max(it["rows"] for it in view["items"]) > 16
     tab = TABLE2 if table == "table2" else _default_table(wide)
-    ref = P.plan(f.parent, f.node_len, f.req_node, head.group, m, align, max_rows, share, tab)
+    ref = P.plan(f.parent, f.node_len, f.req_node, head.group, m, align, max_rows, share, tab,
+                 slack=bool(extensions & 1), diagonal=bool(extensions & 2))
     _compare(view, ref)
+    if extensions == 0:             # Eq. 5 as printed, on the library's own numbers, no slack term
+        for it in view["items"]:
+            assert 1 <= it["b"] <= it["ub"] <= max(1, -(-it["cost"] // view["cost_l"]))
 
 
 @pytest.mark.parametrize("name", CONFIG_NAMES)
 @pytest.mark.parametrize("share", [True, False])
-def test_measured_configurations_with_library_defaults(name, share):
-    """Full-size forests of the measured configurations, default options of the library."""
+@pytest.mark.parametrize("extensions", [0, 3])
+def test_measured_configurations_with_library_defaults(name, share, extensions):
+    """Full-size forests of the measured configurations, default options of the library: the printed
+    solver (extensions = 0) and the one the benchmark's headline runs (both extensions)."""
     f, head = config_forest(name), config_head(name)
-    view = _lib_plan(f, head, 0, 0, 0, share, None)
+    view = _lib_plan(f, head, 0, 0, 0, share, None, extensions)
     # library defaults: 256-token alignment, row tiles of 256, and as many slots as workgroups that
     # run at once (one per CU if any task holds more than 16 rows, else two)
     widest = max(it["rows"] for it in view["items"])
     m = (256 if widest > 16 else 512) // head.num_kv_heads
     assert view["num_slots"] == m
     ref = P.plan(f.parent, f.node_len, f.req_node, head.group, m, 256, 256, share,
-                 _default_table(widest > 16))
+                 _default_table(widest > 16), slack=bool(extensions & 1), diagonal=bool(extensions & 2))
     _compare(view, ref)
+    if extensions == 0:
+        for it in view["items"]:
+            assert 1 <= it["b"] <= it["ub"] <= max(1, -(-it["cost"] // view["cost_l"]))
 
 
 # ---- codec_plan_refresh_lengths against the oracle's refresh ---------------------------------------
@@ -309,6 +320,11 @@ def test_schedule_option_is_checked():
         st, plan = C.codec_plan_create(f.parent, f.node_len, f.req_node, paged.node_page_off, paged.page_ids,
                                        head.num_q_heads, head.num_kv_heads, head.head_dim, head.dtype,
                                        head.page_size, head.scale, schedule=bad)
+        assert st == C.CODEC_ERR_INVALID_ARGUMENT and plan is None
+    for bad in (4, -1):
+        st, plan = C.codec_plan_create(f.parent, f.node_len, f.req_node, paged.node_page_off, paged.page_ids,
+                                       head.num_q_heads, head.num_kv_heads, head.head_dim, head.dtype,
+                                       head.page_size, head.scale, extensions=bad)
         assert st == C.CODEC_ERR_INVALID_ARGUMENT and plan is None
 
 
