@@ -245,23 +245,11 @@ int64_t CostTable::estimate(int64_t rows, int64_t len) const
 // with the profiler of the Python package (one launch with three tasks per slot minus one launch with
 // one task per slot, halved; every slot and KV head busy, K/V cold).  The kernel has two launch
 // variants with different workgroup shapes, hence two tables: `wide` for plans that hold a task of
-// more than 16 rows, `narrow` for the others.
+// more than 16 rows, `narrow` for the others.  The numbers come straight from the profiler's output:
+// the build writes cost_table_generated.inc from cost_table_mi355x.json.
 const CostTable &builtin_cost_table(bool wide)
 {
-    static const CostTable narrow_table = {
-        {1, 16},
-        {32, 128, 512, 2048, 8192, 32768},
-        {1400, 5919, 22457, 90230, 363960, 1449535,
-         2939, 7539, 24677, 100789, 376977, 1461894}};
-    static const CostTable wide_table = {
-        {1, 16, 32, 64, 128, 256},
-        {32, 128, 512, 2048, 8192, 32768},
-        {220, 2559, 11159, 46395, 181640, 727736,
-         559, 3140, 11679, 48754, 185579, 732795,
-         3660, 6959, 16439, 48714, 177419, 684020,
-         5119, 8299, 18618, 52654, 189138, 695999,
-         8339, 10858, 22178, 53614, 201436, 821064,
-         11439, 16439, 28236, 71011, 315323, 1105291}};
+#include "cost_table_generated.inc"
     return wide ? wide_table : narrow_table;
 }
 

@@ -12,16 +12,24 @@ Two tables are measured because the kernel has two launch variants: "narrow"
 (only tasks of at most 16 rows; 4 waves per workgroup, two workgroups per CU)
 and "wide" (any task; 8 waves, one workgroup per CU).
 
-    python -m paper_2505_17694_amd.profile --out profiles/cost_table_mi355x.json
+The K/V pools are laid out [page][kv_head][token][d]: a (page, head) is one contiguous 4 KB run.
+
+    python -m paper_2505_17694_amd.profile            # writes the package's cost_table_mi355x.json
+
+The build turns that file into the library's built-in tables (build.py: generate_cost_tables), so a
+rebuild after profiling is all it takes for the planner to use the new numbers.
 """
 from __future__ import annotations
 
 import argparse
 import json
 import math
+import os
 import sys
 
 import numpy as np
+
+DEFAULT_OUT = os.path.join(os.path.dirname(os.path.abspath(__file__)), "cost_table_mi355x.json")
 
 
 def _forest(num_tasks, rows, length, force_wide):
@@ -60,7 +68,7 @@ def launch_time(rows: int, length: int, wide: bool, per_slot: int, iters: int = 
     paged.num_pages = int(off[-1])
     rng = np.random.Generator(np.random.PCG64(rows * 1000003 + length))
     paged.page_ids = rng.permutation(paged.num_pages).astype(np.int32)
-    paged.page_stride, paged.token_stride, paged.head_stride = ps * h_kv * d, h_kv * d, d
+    paged.page_stride, paged.token_stride, paged.head_stride = ps * h_kv * d, d, ps * d
     head.num_q_heads = head.num_kv_heads = h_kv
     head.head_dim, head.dtype, head.page_size, head.scale = d, B.CODEC_DTYPE_BF16, ps, 1.0 / math.sqrt(d)
 
@@ -121,7 +129,7 @@ def profile(row_grid, len_grid, wide: bool, verbose: bool = True):
 
 def main():
     ap = argparse.ArgumentParser()
-    ap.add_argument("--out", default="")
+    ap.add_argument("--out", default=DEFAULT_OUT, help="'' = print only")
     ap.add_argument("--lens", default="32,128,512,2048,8192,32768")
     ap.add_argument("--wide-rows", default="1,16,17,32,64,128,256")
     ap.add_argument("--narrow-rows", default="1,16")

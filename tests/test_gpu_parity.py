@@ -464,6 +464,19 @@ def test_error_paths_on_the_device_side():
     pa.close()
 
 
+def test_cost_table_profiler_agrees_with_the_built_in_table():
+    """The profiler that writes the built-in table, on two grid points of the wide variant (a stream
+    task and a dense task): what it measures on this machine is within 25 % of what the library plans with."""
+    C = _C()
+    from paper_2505_17694_amd import profile
+    row_grid, len_grid, cost = C.codec_default_cost_table(1)
+    for rows, length in ((16, 2048), (256, 2048)):
+        got = profile.measure(rows, length, wide=True)
+        want = cost[row_grid.index(rows)][len_grid.index(length)]
+        print(f"[case] profiler rows={rows} len={length}: measured {got:.0f} ns, table {want} ns", flush=True)
+        assert 0.75 * want <= got <= 1.25 * want, (rows, length, got, want)
+
+
 # ---- full-size configurations, in the launch configuration the benchmark times -------------------
 
 def _sample_pairs(w, n, seed):

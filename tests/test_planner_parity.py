@@ -73,6 +73,25 @@ def test_cost_estimate_matches_oracle_everywhere():
     assert C.codec_cost_estimate(_tuple(TABLE2), 100, 16384) == 746
 
 
+def test_built_in_tables_are_the_profilers_output():
+    """The tables the library plans with are generated from the profiler's JSON at build time: every
+    grid point and cost of codec_default_cost_table equals the file (no hand copy in between)."""
+    import json
+    import os
+    path = os.path.join(os.path.dirname(C.LIB_PATH), "cost_table_mi355x.json")
+    with open(path) as f:
+        tables = json.load(f)
+    for wide, key in ((0, "narrow"), (1, "wide")):
+        got = _default_table(wide)
+        assert got["row_grid"] == tables[key]["row_grid"]
+        assert got["len_grid"] == tables[key]["len_grid"]
+        assert got["cost"] == tables[key]["cost"]
+    # the jump between the stream path (16 rows) and the dense path (17 rows) is a grid line of its own
+    assert 16 in tables["wide"]["row_grid"] and 17 in tables["wide"]["row_grid"]
+    i17, j32 = tables["wide"]["row_grid"].index(17), tables["wide"]["len_grid"].index(32)
+    assert C.codec_cost_estimate(None, 17, 32) == tables["wide"]["cost"][i17][j32]
+
+
 FORESTS = {
     "docqa": lambda: two_level_forest(10000, [50] * 24),
     "three": lambda: three_level_forest(2048, [8192] * 4, 5, [37 + 13 * i for i in range(20)]),
