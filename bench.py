@@ -85,7 +85,7 @@ class Rotating:
         return self.k[i % self.n], self.v[i % self.n]
 
 
-def time_plan(pa, w, rot, steps, warmup):
+def time_plan(pa, w, rot, steps, warmup, phases=True):
     """Whole-step time over exactly ``steps`` steps plus per-phase kernel times from HIP events."""
     import torch
     out = torch.empty_like(w.q)
@@ -115,6 +115,8 @@ def time_plan(pa, w, rot, steps, warmup):
     wall_ms = (time.perf_counter() - t0) * 1e3 / steps
     step_ms = e0.elapsed_time(e1) / steps
 
+    if not phases:
+        return {"step_ms": step_ms, "wall_ms": wall_ms}, out
     # second pass over the same steps: events around each phase, on the stream the kernels run on
     ev = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(steps)]
     for i in range(steps):
@@ -198,17 +200,24 @@ def run_config(name, args, steps, warmup, want_flat):
         res["tree_queued"] = {"us_per_step": round(t["step_ms"] * 1e3, 2), "pac_us": round(t["pac_ms_avg"] * 1e3, 2),
                               "entries": len(view["queue_off"]) - 1, "slots": view["num_slots"]}
         pa.close()
+        # one launch: the workgroup that delivers a request's last partial result reduces it (fused = 1)
+        pa = C.PlannedAttention(w.forest, w.paged, w.head, device="cuda:0", share=1, fused=1, extensions=3,
+                                num_slots=args.num_slots, split_align=args.split_align, max_rows=args.max_rows)
+        t, _ = time_plan(pa, w, rot, steps, warmup, phases=False)
+        res["tree_single_launch"] = {"us_per_step": round(t["step_ms"] * 1e3, 2)}
+        pa.close()
         # the library's own choices: the plan with the lowest estimated makespan among its candidates
-        # (share = 2), static schedule or run-time queue by the number of queue entries (schedule = 2)
+        # (share = 2), static schedule or run-time queue by the number of queue entries (schedule = 2),
+        # one launch or two by the estimated makespan (fused = 2)
         t0 = time.perf_counter()
-        pa = C.PlannedAttention(w.forest, w.paged, w.head, device="cuda:0", share=2, schedule=2, extensions=3,
+        pa = C.PlannedAttention(w.forest, w.paged, w.head, device="cuda:0", share=2, schedule=2, fused=2, extensions=3,
                                 num_slots=args.num_slots, split_align=args.split_align, max_rows=args.max_rows)
         plan_ms = (time.perf_counter() - t0) * 1e3
         view = pa.export()
         t, _ = time_plan(pa, w, rot, steps, warmup)
         res["best_plan"] = {"us_per_step": round(t["step_ms"] * 1e3, 2), "pac_us": round(t["pac_ms_avg"] * 1e3, 2),
                             "picked": {"share": view["share"], "max_rows": view["max_rows"],
-                                       "schedule": view["schedule"]},
+                                       "schedule": view["schedule"], "fused": view["fused"]},
                             "plan_ms": round(plan_ms, 2), "est_makespan": view["makespan"]}
         pa.close()
         res["speedup_vs_flat"] = round(res["flat"]["us_per_step"] / res["tree"]["us_per_step"], 3)

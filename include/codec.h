@@ -123,6 +123,16 @@ typedef struct {
                                has at least six entries per slot (measured on irregular forests: with
                                that many the queue is 3-6 % faster, with few it changes nothing), else
                                static.  The plan view reports the schedule in use (0 or 1)           */
+    int32_t fused;          /* 0 = Alg. 4 in two launches (partial attention, then reduction); 1 = one
+                               launch: the workgroup whose task completes a request's set of partial
+                               results (the last to arrive, counted per request and KV head in the
+                               plan's device metadata) reduces them itself (the single-launch form
+                               of the parallel reduction of Sec. 4.3, for trees whose step time is
+                               of the order of a kernel launch); 2 = the library chooses: one launch
+                               if the estimated makespan is below 40 us.  Only codec_decode_attention
+                               (and its static variant) fuse; the two phase calls stay separate.  As
+                               with the run-time queue, launches of one plan must not overlap.  The
+                               plan view reports 0 or 1                                             */
     int32_t extensions;     /* 0 = the solver of Sec. 5.1 as printed: slice counts bounded by
                                ceil(C_est / cost_l) (Eq. 5), one node-by-node pass of the grid search.
                                Bits add this library's own extensions of it (CODEC_PLAN_EXT_*)       */
@@ -194,6 +204,7 @@ typedef struct {
     int32_t           max_rows;
     int32_t           share;
     int32_t           schedule;
+    int32_t           fused;
     int32_t           num_entries;  /* run-time queue (also built for static plans): entry e holds tasks */
     const int32_t    *queue_off;    /* queue_tasks[queue_off[e] .. queue_off[e+1]); entries in order of  */
     const int32_t    *queue_tasks;  /* decreasing cost of their first task                               */

@@ -62,7 +62,7 @@ class codec_cost_table(Structure):
 class codec_plan_options(Structure):
     _fields_ = [("num_slots", c_int32), ("split_align", c_int32), ("max_rows", c_int32),
                 ("share", c_int32), ("cost", POINTER(codec_cost_table)), ("fixed_slices", c_int32),
-                ("schedule", c_int32), ("extensions", c_int32)]
+                ("schedule", c_int32), ("fused", c_int32), ("extensions", c_int32)]
 
 
 class codec_item(Structure):
@@ -85,7 +85,7 @@ class codec_plan_view(Structure):
                 ("num_requests", c_int32), ("req_part_off", _i32p), ("req_part", _i32p),
                 ("cost_l", c_int64), ("makespan", c_int64), ("part_rows", c_int32),
                 ("split_align", c_int32), ("max_rows", c_int32), ("share", c_int32),
-                ("schedule", c_int32), ("num_entries", c_int32), ("queue_off", _i32p), ("queue_tasks", _i32p)]
+                ("schedule", c_int32), ("fused", c_int32), ("num_entries", c_int32), ("queue_off", _i32p), ("queue_tasks", _i32p)]
 
 
 class codec_kv_layout(Structure):
@@ -181,7 +181,7 @@ def codec_last_error_message() -> str:
 def codec_plan_create(parent, node_len, req_node, node_page_off, page_ids,
                       num_q_heads, num_kv_heads, head_dim, dtype, page_size, scale,
                       num_slots=0, split_align=0, max_rows=0, share=1, cost_table=None, fixed_slices=0,
-                      schedule=0, extensions=0):
+                      schedule=0, extensions=0, fused=0):
     """Returns (status, plan handle or None).  ``cost_table``: (row_grid, len_grid, cost) or None."""
     parent, node_len, req_node = _i32(parent), _i32(node_len), _i32(req_node)
     node_page_off, page_ids = _i32(node_page_off), _i32(page_ids)
@@ -194,7 +194,7 @@ def codec_plan_create(parent, node_len, req_node, node_page_off, page_ids,
         ct, keep = make_cost_table(*cost_table)
         ct_ptr = ctypes.pointer(ct)
     opt = codec_plan_options(num_slots, split_align, max_rows, share, ct_ptr, fixed_slices, schedule,
-                             extensions)
+                             fused, extensions)
     handle = c_void_p()
     st = _lib.codec_plan_create(byref(tree), byref(head), byref(opt), byref(handle))
     del keep
@@ -227,7 +227,7 @@ def codec_plan_export(plan):
         "req_part_off": _arr(v.req_part_off, v.num_requests + 1),
         "cost_l": v.cost_l, "makespan": v.makespan, "part_rows": v.part_rows,
         "split_align": v.split_align, "max_rows": v.max_rows, "share": v.share,
-        "schedule": v.schedule, "queue_off": _arr(v.queue_off, v.num_entries + 1),
+        "schedule": v.schedule, "fused": v.fused, "queue_off": _arr(v.queue_off, v.num_entries + 1),
         "queue_tasks": _arr(v.queue_tasks, v.num_tasks),
     }
     out["node_q"] = _arr(v.node_q, int(out["node_q_off"][-1]) if v.num_nodes else 0)

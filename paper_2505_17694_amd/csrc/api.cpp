@@ -106,6 +106,7 @@ int codec_plan_export(const codec_plan_t *plan, codec_plan_view *v)
     v->max_rows = d.max_rows;
     v->share = d.share;
     v->schedule = d.schedule;
+    v->fused = d.fused;
     v->num_entries = int32_t(d.queue_off.size()) - 1;
     v->queue_off = d.queue_off.data();
     v->queue_tasks = d.queue_tasks.data();
@@ -190,9 +191,34 @@ size_t codec_plan_workspace_bytes(const codec_plan_t *plan)
     return n ? n : 256;
 }
 
-int codec_partial_attention(const codec_plan_t *plan, const void *q, const void *k_pages,
-                            const void *v_pages, const codec_kv_layout *layout,
-                            void *workspace, size_t workspace_bytes, void *stream)
+}  // extern "C"
+
+namespace {
+
+codec::MergeParams merge_params(const codec_plan_t *plan, const void *workspace, void *out)
+{
+    const codec::PlanData &d = plan->d;
+    const char *meta = static_cast<const char *>(plan->device_meta);
+    const codec::DevLayout &L = d.layout;
+    const char *ws = static_cast<const char *>(workspace);
+    codec::MergeParams mp{};
+    mp.part_o = reinterpret_cast<const float *>(ws);
+    mp.part_ml = reinterpret_cast<const float *>(ws + part_o_bytes(d));
+    mp.req_part_off = reinterpret_cast<const int32_t *>(meta + L.req_part_off);
+    mp.req_part = reinterpret_cast<const int32_t *>(meta + L.req_part);
+    mp.req_inline = reinterpret_cast<const int32_t *>(meta + L.req_inline);
+    mp.out = out;
+    mp.num_requests = d.num_requests;
+    mp.h_q = d.head.num_q_heads;
+    mp.group = d.group;
+    mp.part_rows = d.part_rows;
+    return mp;
+}
+
+// Partial attention over the plan's tasks; with `fused_out` the launch also reduces (single-launch mode).
+int partial_attention(const codec_plan_t *plan, const void *q, const void *k_pages,
+                      const void *v_pages, const codec_kv_layout *layout,
+                      void *workspace, size_t workspace_bytes, void *fused_out, void *stream)
 {
     if (!plan || !layout) return CODEC_ERR_INVALID_ARGUMENT;
     const codec::PlanData &d = plan->d;
@@ -242,9 +268,24 @@ int codec_partial_attention(const codec_plan_t *plan, const void *q, const void 
         pp.counters = reinterpret_cast<int32_t *>(const_cast<char *>(meta) + L.counters);
         pp.num_entries = int32_t(d.queue_off.size()) - 1;
     }
+    if (fused_out) {
+        pp.merge = merge_params(plan, workspace, fused_out);
+        pp.arrive = reinterpret_cast<int32_t *>(const_cast<char *>(meta) + L.arrive);
+    }
     if (int e = codec::launch_pac(pp, d.head.dtype, d.num_slots, plan->max_task_rows, stream))
         return hip_failure("partial attention launch", e);
     return CODEC_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int codec_partial_attention(const codec_plan_t *plan, const void *q, const void *k_pages,
+                            const void *v_pages, const codec_kv_layout *layout,
+                            void *workspace, size_t workspace_bytes, void *stream)
+{
+    return partial_attention(plan, q, k_pages, v_pages, layout, workspace, workspace_bytes, nullptr, stream);
 }
 
 int codec_partial_reduction(const codec_plan_t *plan, const void *workspace, size_t workspace_bytes,
@@ -258,20 +299,7 @@ int codec_partial_reduction(const codec_plan_t *plan, const void *workspace, siz
     if (workspace_bytes < codec_plan_workspace_bytes(plan)) return CODEC_ERR_WORKSPACE_TOO_SMALL;
     if (!aligned16(out) || (reinterpret_cast<uintptr_t>(workspace) & 255u)) return CODEC_ERR_INVALID_ARGUMENT;
 
-    const char *meta = static_cast<const char *>(plan->device_meta);
-    const codec::DevLayout &L = d.layout;
-    const char *ws = static_cast<const char *>(workspace);
-    codec::MergeParams mp{};
-    mp.part_o = reinterpret_cast<const float *>(ws);
-    mp.part_ml = reinterpret_cast<const float *>(ws + part_o_bytes(d));
-    mp.req_part_off = reinterpret_cast<const int32_t *>(meta + L.req_part_off);
-    mp.req_part = reinterpret_cast<const int32_t *>(meta + L.req_part);
-    mp.req_inline = reinterpret_cast<const int32_t *>(meta + L.req_inline);
-    mp.out = out;
-    mp.num_requests = d.num_requests;
-    mp.h_q = d.head.num_q_heads;
-    mp.group = d.group;
-    mp.part_rows = d.part_rows;
+    const codec::MergeParams mp = merge_params(plan, workspace, out);
     if (int e = codec::launch_merge(mp, d.head.dtype, stream)) return hip_failure("partial reduction launch", e);
     return CODEC_OK;
 }
@@ -282,6 +310,8 @@ int codec_decode_attention(const codec_plan_t *plan, const void *q, const void *
 {
     if (plan && plan->d.num_requests == 0) return layout ? CODEC_OK : CODEC_ERR_INVALID_ARGUMENT;
     if (!out || !aligned16(out)) return CODEC_ERR_INVALID_ARGUMENT;
+    if (plan && plan->d.fused)          // one launch: the last workgroup to arrive at a request reduces it
+        return partial_attention(plan, q, k_pages, v_pages, layout, workspace, workspace_bytes, out, stream);
     if (int st = codec_partial_attention(plan, q, k_pages, v_pages, layout, workspace, workspace_bytes, stream))
         return st;
     return codec_partial_reduction(plan, workspace, workspace_bytes, out, stream);

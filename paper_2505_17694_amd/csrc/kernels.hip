@@ -1027,107 +1027,14 @@ __device__ void run_dense32(const PacParams &P, const DevTask &t, int head, char
     }
 }
 
-// WIDE: kRingBytes of dynamic LDS.  The dense path XORs the channel tile into operand addresses, so
-// the ring must start on a 256-byte boundary (no static LDS in that variant).
-extern __shared__ __attribute__((aligned(1024))) char dyn_lds[];
-
-template <int DT, int WIDE>
-__global__ void __launch_bounds__(WIDE ? kWideWaves * 64 : kNarrowWaves * 64, 2) pac_kernel(const PacParams P)
-{
-    constexpr int W = WIDE ? kWideWaves : kNarrowWaves;
-    char *lds;
-    if constexpr (WIDE != 0) {
-        lds = dyn_lds;
-    } else {
-        __shared__ __attribute__((aligned(16))) char static_lds[merge_bytes(kNarrowWaves, 1)];
-        lds = static_lds;
-    }
-    const int head = blockIdx.x % P.h_kv;
-    const int slot = blockIdx.x / P.h_kv;
-    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    // Runs the task records recs[t0 .. t1).  Tasks of more than 16 rows take the dense path (wide variant
-    // only).  Tasks of at most 16 rows take the stream path, as a rule with all waves of the workgroup
-    // as one team.  Runs of two or more short ones are handed out one wave each through a counter in
-    // LDS: the latencies of a short task (descriptor, query rows, page ids, first blocks, merge of a
-    // team) then overlap with the other tasks' instead of adding up.  In a slot's list the plan marks
-    // such runs (they are neighbours there, the list being sorted by cost); an entry of the run-time
-    // queue with several tasks is one such run.
-    auto run_tasks = [&](const DevTask *recs, int t0, int t1, bool marked) __attribute__((always_inline)) {
-        int i = t0;
-#pragma unroll 1
-        while (i < t1) {
-            const DevTask t = recs[i];
-            const int n = marked ? t.solo_run : t1 - i;
-            if (n >= 2) {
-                int *next = reinterpret_cast<int *>(lds);
-                if (threadIdx.x == 0) *next = 0;
-                __syncthreads();
-#pragma unroll 1
-                for (;;) {
-                    int k = 0;
-                    if ((threadIdx.x & 63) == 0) k = atomicAdd(next, 1);
-                    k = __builtin_amdgcn_readfirstlane(k);
-                    if (k >= n) break;
-                    const DevTask mine = recs[i + k];
-                    if (mine.read_once) run_stream<DT, true, 1, 1>(P, mine, head, lds, 0);
-                    else                run_stream<DT, false, 1, 1>(P, mine, head, lds, 0);
-                }
-                __syncthreads();                // the counter is done with before LDS is used again
-                i += n;
-            } else {
-                if (t.n_req * P.group <= 16) {
-                    if (t.read_once) run_stream<DT, true, 1, W>(P, t, head, lds, wave);
-                    else             run_stream<DT, false, 1, W>(P, t, head, lds, wave);
-                }
-                else if constexpr (WIDE != 0) run_dense32<DT>(P, t, head, lds);
-                ++i;
-            }
-        }
-    };
-
-    // Static schedule: the slot's own list, once.  Run-time queue: entry `slot` is this workgroup's
-    // first; every further one is the next entry nobody has taken, fetched by one thread (one atomic)
-    // and spread to the waves through LDS.  Every path through run_tasks ends with a barrier behind
-    // its last LDS access, so the word can be written right away; the second barrier keeps the next
-    // task's block copies from overwriting it before everyone has read it.
-    const bool queued = P.queue_off != nullptr;
-    const bool fetching = queued && P.num_entries > P.num_slots;        // else: an entry per workgroup at most
-    const DevTask *recs = queued ? P.queue_recs : P.slot_recs;
-    const int32_t *off = queued ? P.queue_off : P.slot_off;
-    const int limit = queued ? P.num_entries : slot + 1;
-    int32_t *taken = P.counters + 2 * head, *finished = taken + 1;
-    int *word = reinterpret_cast<int *>(lds);
-    int e = slot;
-#pragma unroll 1
-    while (e < limit) {
-        run_tasks(recs, off[e], off[e + 1], !queued);
-        if (!fetching) break;
-        // taken when the workgroup is free, not ahead of time: an entry reserved early would wait for
-        // the end of a long task while other workgroups idle
-        if (threadIdx.x == 0) *word = P.num_slots + atomicAdd(taken, 1);
-        __syncthreads();
-        e = __builtin_amdgcn_readfirstlane(*word);
-        __syncthreads();
-    }
-    // the last workgroup of this KV head to get here leaves the counters at zero for the next launch
-    if (fetching && threadIdx.x == 0 && atomicAdd(finished, 1) == P.num_slots - 1) {
-        atomicExch(taken, 0);
-        atomicExch(finished, 0);
-    }
-}
-
-// Partial output reduction (Alg. 3), n-ary: one wave per (request, query head) folds the request's
-// partials in list order; each lane owns two channels.  Partials are taken eight or fifteen at a time:
-// their loads are issued together, then they are folded against their common maximum (by
-// associativity of the reduction this equals any binary bracketing).
+// Partial output reduction (Alg. 3), n-ary: one wave folds the partials of one (request, query head)
+// in list order; each lane owns two channels.  Partials are taken eight or fifteen at a time: their
+// loads are issued together, then they are folded against their common maximum (by associativity of
+// the reduction this equals any binary bracketing).
 template <int DT>
-__global__ void __launch_bounds__(kMergeWaves * 64) merge_kernel(const MergeParams P)
+__device__ __forceinline__ void merge_one(const MergeParams &P, int r, int hq, int lane)
 {
     constexpr int kChunk = 8;
-    const int lane = threadIdx.x & 63;
-    const int row = blockIdx.x * kMergeWaves + (threadIdx.x >> 6);
-    if (row >= P.num_requests * P.h_q) return;
-    const int r = row / P.h_q, hq = row - r * P.h_q;
     const int head = hq / P.group, hj = hq - head * P.group;
     // The request's line: its number of partial rows and the first kInlineParts of them, read together
     // (no address waits for another read).  Lists of up to eight rows, and of up to kInlineParts, are
@@ -1183,10 +1090,175 @@ __global__ void __launch_bounds__(kMergeWaves * 64) merge_kernel(const MergePara
         }
     }
     const float inv = 1.f / L;
-    unsigned int *out = static_cast<unsigned int *>(P.out) + int64_t(row) * (kHeadDim / 2) + lane;
+    unsigned int *out = static_cast<unsigned int *>(P.out) + (int64_t(r) * P.h_q + hq) * (kHeadDim / 2) + lane;
     *out = pack2<DT>(a0 * inv, a1 * inv);
 }
 
+template <int DT>
+__global__ void __launch_bounds__(kMergeWaves * 64) merge_kernel(const MergeParams P)
+{
+    const int row = blockIdx.x * kMergeWaves + (threadIdx.x >> 6);
+    if (row >= P.num_requests * P.h_q) return;
+    const int r = row / P.h_q;
+    merge_one<DT>(P, r, row - r * P.h_q, threadIdx.x & 63);
+}
+
+// ---- single-launch mode: the reduction inside the attention launch (Sec. 4.3, parallel reduction) ----
+//
+// Every task delivers one partial result to each of its requests.  arrive[head][request] counts them
+// (device-scope atomics); the delivery that completes a request's reduction list (its length is the
+// first word of the request's line) makes the delivering workgroup reduce that request's rows of this
+// KV head right away, and put the counter back to zero for the next launch.  Order: the partial rows
+// are stored, then released together with the count (release at device scope); the workgroup that
+// sees the last count acquires before it reads the rows.
+__device__ __forceinline__ bool deliver(const PacParams &P, const DevTask &t, int head, int i, int &req)
+{
+    req = t.single_req >= 0 ? t.single_req : P.node_q[t.q_off + i];
+    const int want = P.merge.req_inline[int64_t(req) * (kInlineParts + 1)];
+    int32_t *c = P.arrive + int64_t(head) * P.merge.num_requests + req;
+    const int old = __hip_atomic_fetch_add(c, 1, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT);
+    if (old + 1 != want) return false;
+    __hip_atomic_store(c, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // nobody else counts on it in this launch
+    return true;
+}
+
+// A task that the whole workgroup ran (every thread calls this after the task).
+template <int DT>
+__device__ void task_delivered_by_workgroup(const PacParams &P, const DevTask &t, int head, char *lds_raw, int waves)
+{
+    int *count = reinterpret_cast<int *>(lds_raw), *ready = count + 1;
+    __syncthreads();                    // every wave's partial rows are on their way out; LDS is free
+    if (threadIdx.x == 0) *count = 0;
+    __syncthreads();
+    if (int(threadIdx.x) < t.n_req) {
+        int req;
+        if (deliver(P, t, head, threadIdx.x, req)) ready[atomicAdd(count, 1)] = req;
+    }
+    __syncthreads();
+    const int n = *count * P.group;
+    if (n > 0) {
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+        const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+#pragma unroll 1
+        for (int i = wave; i < n; i += waves) {
+            const int k = i / P.group;
+            merge_one<DT>(P.merge, ready[k], head * P.group + (i - k * P.group), threadIdx.x & 63);
+        }
+    }
+    __syncthreads();                    // the list is done with before LDS is used again
+}
+
+// A task that one wave ran on its own (no barrier: the other waves are inside other tasks).
+template <int DT>
+__device__ void task_delivered_by_wave(const PacParams &P, const DevTask &t, int head)
+{
+    const int lane = threadIdx.x & 63;
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");      // the wave's partial rows, stored by all its lanes
+    int req = 0;
+    const bool last = lane < t.n_req && deliver(P, t, head, lane, req);
+    unsigned long long ready = __ballot(last);
+    if (ready == 0) return;
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+#pragma unroll 1
+    while (ready) {
+        const int src = __builtin_ctzll(ready);
+        ready &= ready - 1;
+        const int r = __shfl(req, src);
+#pragma unroll 1
+        for (int hj = 0; hj < P.group; ++hj) merge_one<DT>(P.merge, r, head * P.group + hj, lane);
+    }
+}
+
+// WIDE: kRingBytes of dynamic LDS.  The dense path XORs the channel tile into operand addresses, so
+// the ring must start on a 256-byte boundary (no static LDS in that variant).
+extern __shared__ __attribute__((aligned(1024))) char dyn_lds[];
+
+template <int DT, int WIDE>
+__global__ void __launch_bounds__(WIDE ? kWideWaves * 64 : kNarrowWaves * 64, 2) pac_kernel(const PacParams P)
+{
+    constexpr int W = WIDE ? kWideWaves : kNarrowWaves;
+    char *lds;
+    if constexpr (WIDE != 0) {
+        lds = dyn_lds;
+    } else {
+        __shared__ __attribute__((aligned(16))) char static_lds[merge_bytes(kNarrowWaves, 1)];
+        lds = static_lds;
+    }
+    const int head = blockIdx.x % P.h_kv;
+    const int slot = blockIdx.x / P.h_kv;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    // Runs the task records recs[t0 .. t1).  Tasks of more than 16 rows take the dense path (wide variant
+    // only).  Tasks of at most 16 rows take the stream path, as a rule with all waves of the workgroup
+    // as one team.  Runs of two or more short ones are handed out one wave each through a counter in
+    // LDS: the latencies of a short task (descriptor, query rows, page ids, first blocks, merge of a
+    // team) then overlap with the other tasks' instead of adding up.  In a slot's list the plan marks
+    // such runs (they are neighbours there, the list being sorted by cost); an entry of the run-time
+    // queue with several tasks is one such run.
+    auto run_tasks = [&](const DevTask *recs, int t0, int t1, bool marked) __attribute__((always_inline)) {
+        int i = t0;
+#pragma unroll 1
+        while (i < t1) {
+            const DevTask t = recs[i];
+            const int n = marked ? t.solo_run : t1 - i;
+            if (n >= 2) {
+                int *next = reinterpret_cast<int *>(lds);
+                if (threadIdx.x == 0) *next = 0;
+                __syncthreads();
+#pragma unroll 1
+                for (;;) {
+                    int k = 0;
+                    if ((threadIdx.x & 63) == 0) k = atomicAdd(next, 1);
+                    k = __builtin_amdgcn_readfirstlane(k);
+                    if (k >= n) break;
+                    const DevTask mine = recs[i + k];
+                    if (mine.read_once) run_stream<DT, true, 1, 1>(P, mine, head, lds, 0);
+                    else                run_stream<DT, false, 1, 1>(P, mine, head, lds, 0);
+                    if (P.arrive) task_delivered_by_wave<DT>(P, mine, head);
+                }
+                __syncthreads();                // the counter is done with before LDS is used again
+                i += n;
+            } else {
+                if (t.n_req * P.group <= 16) {
+                    if (t.read_once) run_stream<DT, true, 1, W>(P, t, head, lds, wave);
+                    else             run_stream<DT, false, 1, W>(P, t, head, lds, wave);
+                }
+                else if constexpr (WIDE != 0) run_dense32<DT>(P, t, head, lds);
+                if (P.arrive) task_delivered_by_workgroup<DT>(P, t, head, lds, W);
+                ++i;
+            }
+        }
+    };
+
+    // Static schedule: the slot's own list, once.  Run-time queue: entry `slot` is this workgroup's
+    // first; every further one is the next entry nobody has taken, fetched by one thread (one atomic)
+    // and spread to the waves through LDS.  Every path through run_tasks ends with a barrier behind
+    // its last LDS access, so the word can be written right away; the second barrier keeps the next
+    // task's block copies from overwriting it before everyone has read it.
+    const bool queued = P.queue_off != nullptr;
+    const bool fetching = queued && P.num_entries > P.num_slots;        // else: an entry per workgroup at most
+    const DevTask *recs = queued ? P.queue_recs : P.slot_recs;
+    const int32_t *off = queued ? P.queue_off : P.slot_off;
+    const int limit = queued ? P.num_entries : slot + 1;
+    int32_t *taken = P.counters + 2 * head, *finished = taken + 1;
+    int *word = reinterpret_cast<int *>(lds);
+    int e = slot;
+#pragma unroll 1
+    while (e < limit) {
+        run_tasks(recs, off[e], off[e + 1], !queued);
+        if (!fetching) break;
+        // taken when the workgroup is free, not ahead of time: an entry reserved early would wait for
+        // the end of a long task while other workgroups idle
+        if (threadIdx.x == 0) *word = P.num_slots + atomicAdd(taken, 1);
+        __syncthreads();
+        e = __builtin_amdgcn_readfirstlane(*word);
+        __syncthreads();
+    }
+    // the last workgroup of this KV head to get here leaves the counters at zero for the next launch
+    if (fetching && threadIdx.x == 0 && atomicAdd(finished, 1) == P.num_slots - 1) {
+        atomicExch(taken, 0);
+        atomicExch(finished, 0);
+    }
+}
 
 // Read-only streaming kernel (measurement support): every thread sums 16-byte loads; a workgroup takes
 // whole 4 KB chunks, chunk c of the walk being chunk perm(c) of the buffer, so that the order can be

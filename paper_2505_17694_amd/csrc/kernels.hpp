@@ -8,6 +8,16 @@
 
 namespace codec {
 
+struct MergeParams {
+    const float *part_o;
+    const float *part_ml;
+    const int32_t *req_part_off;
+    const int32_t *req_part;
+    const int32_t *req_inline;      // [B][1 + kInlineParts]: count, then the first rows of the list
+    void *out;                      // [B][h_q][128], 16-bit
+    int32_t num_requests, h_q, group, part_rows;
+};
+
 struct PacParams {
     const void *q;                  // [B][h_q][128], 16-bit
     const void *k_pages;
@@ -29,17 +39,14 @@ struct PacParams {
     const DevTask *queue_recs;
     int32_t *counters;
     int32_t num_entries, num_slots;
+    // Single-launch mode (arrive == nullptr: off).  arrive[head * num_requests + r] counts the partial
+    // results of request r that tasks of KV head `head` have delivered in this launch; the workgroup
+    // that delivers the last one (the count reaches the length of the request's reduction list) reduces
+    // the request's rows of that head into merge.out and puts the counter back to zero.
+    int32_t *arrive;
+    MergeParams merge;
 };
 
-struct MergeParams {
-    const float *part_o;
-    const float *part_ml;
-    const int32_t *req_part_off;
-    const int32_t *req_part;
-    const int32_t *req_inline;      // [B][1 + kInlineParts]: count, then the first rows of the list
-    void *out;                      // [B][h_q][128], 16-bit
-    int32_t num_requests, h_q, group, part_rows;
-};
 
 // Size of the library's own scratch array (one per GPU) behind codec_decode_attention_static.
 constexpr size_t kStaticScratchBytes = size_t(64) << 20;

@@ -155,6 +155,8 @@ void build_device_image(PlanData &p)
     L.queue_off = place(p.queue_off.size() * 4);
     L.queue_recs = place(p.queue_tasks.size() * sizeof(DevTask));
     L.counters = place(size_t(p.head.num_kv_heads) * 2 * 4);               // zero: nothing taken, nobody done
+    L.arrive = place(size_t(p.head.num_kv_heads) * size_t(p.num_requests) * 4);   // zero: nothing arrived
+    if (p.fused == 2) p.fused = p.makespan < kAutoFusedMakespanNs ? 1 : 0;
     L.total = std::max<size_t>(off, 256);
     p.blob.assign(L.total, 0);
     // Streaming hint (kernels.hip): a task reads its slice with it when no other task reads that slice
@@ -281,6 +283,7 @@ int build_plan(const codec_tree &tree, const codec_head_config &head,
     if (opt.share != 0 && opt.share != 1) return CODEC_ERR_INVALID_ARGUMENT;
     if (opt.fixed_slices < 0) return CODEC_ERR_INVALID_ARGUMENT;
     if (opt.schedule < 0 || opt.schedule > 2) return CODEC_ERR_INVALID_ARGUMENT;
+    if (opt.fused < 0 || opt.fused > 2) return CODEC_ERR_INVALID_ARGUMENT;
     if (opt.extensions < 0 || opt.extensions > (CODEC_PLAN_EXT_SLACK | CODEC_PLAN_EXT_DIAGONAL))
         return CODEC_ERR_INVALID_ARGUMENT;
     const bool ext_slack = (opt.extensions & CODEC_PLAN_EXT_SLACK) != 0;
@@ -340,6 +343,7 @@ int build_plan(const codec_tree &tree, const codec_head_config &head,
     p.max_rows = max_rows;
     p.share = opt.share;
     p.schedule = opt.schedule;
+    p.fused = opt.fused;
     p.num_nodes = N;
     p.num_requests = B;
     p.node_len.assign(tree.node_len, tree.node_len + N);

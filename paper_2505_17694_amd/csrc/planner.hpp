@@ -28,6 +28,9 @@ constexpr int32_t kSoloMaxLen = 1024;
 constexpr int32_t kQueueBundle = 4;
 // schedule = 2 takes the run-time queue from this many entries per slot on.
 constexpr int32_t kAutoQueueEntriesPerSlot = 6;
+// fused = 2 reduces inside the attention launch when the estimated makespan (ns) is below this: where a
+// second launch (about 5 us with the gap in front of it) is a large part of the step.
+constexpr int64_t kAutoFusedMakespanNs = 40000;
 
 // Task record as the kernels read it (32 bytes).  The device image holds the records twice: in the
 // order of the slots' lists and in the order of the run-time queue, so that a workgroup reads record
@@ -53,13 +56,14 @@ constexpr int32_t kInlineParts = 15;
 struct DevLayout {
     size_t slot_recs = 0, slot_off = 0, node_q = 0, page_ids = 0,
            req_part_off = 0, req_part = 0, req_inline = 0, queue_off = 0, queue_recs = 0, counters = 0,
+           arrive = 0,      // [h_kv][num_requests] partial results arrived (single-launch mode), zero between launches
            total = 0;
 };
 
 struct PlanData {
     codec_head_config head{};
     int32_t group = 1;
-    int32_t num_slots = 0, split_align = 0, max_rows = 0, share = 1, schedule = 0;
+    int32_t num_slots = 0, split_align = 0, max_rows = 0, share = 1, schedule = 0, fused = 0;
     int32_t num_nodes = 0, num_requests = 0;
 
     std::vector<int32_t> node_len, node_page_off, page_ids;

@@ -17,13 +17,13 @@ class PlannedAttention:
 
     def __init__(self, forest, paged, head, device="cuda:0", num_slots=0, split_align=0,
                  max_rows=0, share=1, cost_table=None, fixed_slices=0, schedule=0,
-                 extensions=0):
+                 extensions=0, fused=0):
         st, plan = B.codec_plan_create(forest.parent, forest.node_len, forest.req_node,
                                        paged.node_page_off, paged.page_ids,
                                        head.num_q_heads, head.num_kv_heads, head.head_dim,
                                        head.dtype, head.page_size, head.scale,
                                        num_slots, split_align, max_rows, share, cost_table, fixed_slices, schedule,
-                                       extensions)
+                                       extensions, fused)
         if st != B.CODEC_OK:
             raise B.CodecError(st, "codec_plan_create")
         self.plan = plan

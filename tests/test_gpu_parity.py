@@ -282,15 +282,16 @@ def test_limits_of_the_interface():
     assert np.abs(got - ref).max() <= TOL
 
 
-@pytest.mark.parametrize("schedule", [0, 1])
-def test_decode_replayed_from_a_hip_graph(schedule):
+@pytest.mark.parametrize("schedule,fused", [(0, 0), (1, 0), (0, 1), (1, 1)])
+def test_decode_replayed_from_a_hip_graph(schedule, fused):
     """The decode call is two kernel launches on the caller's stream and nothing else, so it can be
     captured; every replay (with eager work and new queries in between) must equal the eager result.
-    With the run-time queue the kernel itself puts the queue's counters back (no memset node)."""
+    With the run-time queue, and in single-launch mode (fused = 1: one launch, the reduction inside it),
+    the kernel itself puts its counters back (no memset node)."""
     C = _C()
     w = make_small_config("cfg3", 16, 2, poison=True)
     wd = w.to("cuda:0")
-    pa = C.PlannedAttention(w.forest, w.paged, w.head, device="cuda:0", schedule=schedule)
+    pa = C.PlannedAttention(w.forest, w.paged, w.head, device="cuda:0", schedule=schedule, fused=fused)
     q = wd.q.clone()
     out = torch.empty_like(q)
     pa.decode(q, wd.k_pool, wd.v_pool, out)                         # warm-up outside the capture
@@ -334,7 +335,8 @@ def test_random_forests_heads_and_plan_options(seed):
     opts = {"num_slots": int(rng.choice([0, 1, 5, 17])),
             "split_align": int(rng.choice([1, 2, 8])) * max(32, page_size),
             "max_rows": int(rng.choice([0, 0, 16, 64, 128, 200])),
-            "schedule": int(rng.integers(0, 2)), "extensions": int(rng.integers(0, 4))}
+            "schedule": int(rng.integers(0, 2)), "extensions": int(rng.integers(0, 4)),
+            "fused": int(rng.integers(0, 2))}
     if opts["max_rows"] and opts["max_rows"] < hq // hkv:
         opts["max_rows"] = 0
     check(w, share=int(rng.choice([1, 1, 0, 2])), **opts)
@@ -437,6 +439,57 @@ def test_run_time_queue_equals_the_static_schedule(name):
     queued.close()
 
 
+def _fused_cases():
+    cases = dict(_queue_cases())
+    cases["cfg1"] = (lambda: make_small_config("cfg1", 4, 1, poison=True), {})
+    cases["cfg5a"] = (lambda: make_small_config("cfg5a", 64, 4, poison=True), {})
+    cases["drafted"] = (lambda: make_workload("f-drafted", draft_tree_forest(300, [900, 33, 2100, 260], 24, seed=94),
+                                               HeadConfig(32, 8, 128, DTYPE_BF16), seed=95, poison=True), {})
+    cases["long-lists"] = (lambda: make_workload("f-lists", two_level_forest(32 * 23 * 3, [33, 7, 64]),
+                                                  HeadConfig(8, 2, 128, DTYPE_BF16), seed=96, poison=True),
+                           {"num_slots": 5, "split_align": 32, "fixed_slices": 23})
+    return cases
+
+
+@pytest.mark.parametrize("schedule", [0, 1])
+@pytest.mark.parametrize("name", sorted(_fused_cases()))
+def test_single_launch_equals_two_launches(name, schedule):
+    """fused = 1: the workgroup that delivers a request's last partial result reduces the request inside
+    the attention launch.  The reduction folds the same rows in the same order as the reduction kernel,
+    so the output equals the two-launch output bit for bit, launch after launch (the arrival counters
+    are back at zero after every launch), whichever workgroup happens to be last; and it is held against
+    the oracle with both bars of this file."""
+    C = _C()
+    make, opts = _fused_cases()[name]
+    w = make()
+    wd = w.to("cuda:0")
+    two = C.PlannedAttention(w.forest, w.paged, w.head, device="cuda:0", schedule=schedule, **opts)
+    one = C.PlannedAttention(w.forest, w.paged, w.head, device="cuda:0", schedule=schedule, fused=1, **opts)
+    assert one.export()["fused"] == 1 and two.export()["fused"] == 0
+    want = two.decode(wd.q, wd.k_pool, wd.v_pool)
+    torch.cuda.synchronize()
+    ref, _ = A.decode_attention_workload(w)
+    for launch in range(3):
+        got = torch.full_like(wd.q, float("nan"))
+        one.decode(wd.q, wd.k_pool, wd.v_pool, got)
+        torch.cuda.synchronize()
+        g = got.double().cpu().numpy()
+        assert not np.any(np.isnan(g)), f"launch {launch}: a request was never reduced"
+        assert np.abs(g - ref).max() <= TOL, f"launch {launch}: {np.abs(g - ref).max():.3e}"
+        assert np.all(np.abs(g - ref) <= 2e-3 + 2.0 ** -7 * np.abs(ref)), f"launch {launch}: mixed bar"
+        assert torch.equal(got.view(torch.int16), want.view(torch.int16)), f"launch {launch} differs from two launches"
+    # the two phase calls of a fused plan stay separate and leave the counters alone
+    out = torch.empty_like(wd.q)
+    one.partial_attention(wd.q, wd.k_pool, wd.v_pool)
+    one.partial_reduction(out)
+    got = one.decode(wd.q, wd.k_pool, wd.v_pool)
+    torch.cuda.synchronize()
+    assert torch.equal(out.view(torch.int16), want.view(torch.int16))
+    assert torch.equal(got.view(torch.int16), want.view(torch.int16))
+    one.close()
+    two.close()
+
+
 def test_tree_equals_flat_on_the_gpu():
     w = make_small_config("cfg3", 16, 2, poison=True)
     tree, _ = run_gpu(w, share=1)
@@ -494,7 +547,8 @@ BENCH_VARIANTS = [
     {"share": 1, "schedule": 0, "extensions": 0},
     {"share": 0, "schedule": 0, "extensions": 0},
     {"share": 1, "schedule": 1, "extensions": 3},
-    {"share": 2, "schedule": 2, "extensions": 3},
+    {"share": 2, "schedule": 2, "extensions": 3, "fused": 2},
+    {"share": 1, "schedule": 0, "extensions": 3, "fused": 1},
 ]
 
 

@@ -374,3 +374,31 @@ def _same(a, b):
     if isinstance(a, list):
         return a == b
     return np.array_equal(np.asarray(a), np.asarray(b))
+
+
+def test_single_launch_option():
+    """fused = 2 resolves by the estimated makespan (40 us with the built-in tables); 3 and -1 are refused."""
+    picked = {}
+    for name in ("cfg1", "cfg2", "cfg3", "cfg5c"):
+        f, head = config_forest(name), config_head(name)
+        paged = build_paged_kv(f, head, seed=1)
+        for fused in (0, 1, 2):
+            st, plan = C.codec_plan_create(f.parent, f.node_len, f.req_node, paged.node_page_off, paged.page_ids,
+                                           head.num_q_heads, head.num_kv_heads, head.head_dim, head.dtype,
+                                           head.page_size, head.scale, fused=fused, extensions=3)
+            assert st == C.CODEC_OK
+            st, v = C.codec_plan_export(plan)
+            C.codec_plan_destroy(plan)
+            if fused < 2:
+                assert v["fused"] == fused
+            else:
+                assert v["fused"] == (1 if v["makespan"] < 40000 else 0)
+                picked[name] = v["fused"]
+    assert picked == {"cfg1": 1, "cfg2": 1, "cfg3": 0, "cfg5c": 0}
+    f, head = config_forest("cfg1"), config_head("cfg1")
+    paged = build_paged_kv(f, head, seed=1)
+    for bad in (3, -1):
+        st, plan = C.codec_plan_create(f.parent, f.node_len, f.req_node, paged.node_page_off, paged.page_ids,
+                                       head.num_q_heads, head.num_kv_heads, head.head_dim, head.dtype,
+                                       head.page_size, head.scale, fused=bad)
+        assert st == C.CODEC_ERR_INVALID_ARGUMENT and plan is None
