@@ -129,7 +129,9 @@ typedef struct {
                                plan's device metadata) reduces them itself (the single-launch form
                                of the parallel reduction of Sec. 4.3, for trees whose step time is
                                of the order of a kernel launch); 2 = the library chooses: one launch
-                               if the estimated makespan is below 40 us.  Only codec_decode_attention
+                               if the estimated makespan is below 40000 cost units (40 us with the
+                               built-in tables) and the batch has at most 64 query rows per KV head
+                               (one workgroup may be the last for all of them).  Only codec_decode_attention
                                (and its static variant) fuse; the two phase calls stay separate.  As
                                with the run-time queue, launches of one plan must not overlap.  The
                                plan view reports 0 or 1                                             */

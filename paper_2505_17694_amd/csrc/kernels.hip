@@ -93,6 +93,39 @@ __device__ __forceinline__ u32x4 ld16_once(const char *p)
     return __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(p));
 }
 
+// Accesses that are coherent across the whole device without cache maintenance: relaxed atomic
+// accesses at device scope go past the caches that are not coherent at that scope (the `sc1` forms of
+// the load and store instructions).  The single-launch mode moves partial results between workgroups
+// of one launch through them; everywhere else partial results cross a kernel boundary and use plain
+// accesses.
+__device__ __forceinline__ void st8_device(float *p, float a, float b)
+{
+    const float2 v = {a, b};
+    __hip_atomic_store(reinterpret_cast<unsigned long long *>(p), __builtin_bit_cast(unsigned long long, v),
+                       __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ float2 ld8_device(const float *p)
+{
+    const unsigned long long v = __hip_atomic_load(reinterpret_cast<const unsigned long long *>(p),
+                                                   __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    return __builtin_bit_cast(float2, v);
+}
+// 16 bytes of a partial row: plain (the row is read by a later launch) or device-coherent
+__device__ __forceinline__ void st16_partial(float *p, f32x4 v, bool coherent)
+{
+    if (coherent) {
+        st8_device(p, v[0], v[1]);
+        st8_device(p + 2, v[2], v[3]);
+    } else {
+        *reinterpret_cast<f32x4 *>(p) = v;
+    }
+}
+__device__ __forceinline__ void st8_partial(float *p, float a, float b, bool coherent)
+{
+    if (coherent) st8_device(p, a, b);
+    else          *reinterpret_cast<float2 *>(p) = float2{a, b};
+}
+
 // A 16-byte load the compiler does not know is pending: the caller waits for it itself (a vector-memory
 // wait that names dst, see wait_pending) and must not touch dst before.  Used where loads are queued
 // between asynchronous copies: a wait placed by the compiler would count those copies as its own.
@@ -367,13 +400,10 @@ __device__ __forceinline__ void store_partial(const PacParams &P, const DevTask 
             for (int e = 0; e < 4; ++e) {
                 f32x4 lo = {st.o[nt][0][e], st.o[nt][1][e], st.o[nt][2][e], st.o[nt][3][e]};
                 f32x4 hi = {st.o[nt][4][e], st.o[nt][5][e], st.o[nt][6][e], st.o[nt][7][e]};
-                *reinterpret_cast<f32x4 *>(po + e * 8) = lo;
-                *reinterpret_cast<f32x4 *>(po + e * 8 + 4) = hi;
+                st16_partial(po + e * 8, lo, P.arrive != nullptr);
+                st16_partial(po + e * 8 + 4, hi, P.arrive != nullptr);
             }
-            if (grp == 0) {
-                float2 ml = {st.m[nt], st.l[nt]};
-                *reinterpret_cast<float2 *>(P.part_ml + prow * 2) = ml;
-            }
+            if (grp == 0) st8_partial(P.part_ml + prow * 2, st.m[nt], st.l[nt], P.arrive != nullptr);
         }
     }
 }
@@ -991,15 +1021,14 @@ __device__ __forceinline__ void dense32_wave(const PacParams &P, const DevTask &
         const int row = row0 + l32;
         if (row < rows && kg == 0) {
             const int64_t prow = int64_t(head) * P.part_rows + t.part_row_base + row;
-            float2 ml = {m, l};
-            *reinterpret_cast<float2 *>(P.part_ml + prow * 2) = ml;
+            st8_partial(P.part_ml + prow * 2, m, l, P.arrive != nullptr);
         }
         const uint32_t get = area + uint32_t(kg) * kStageRow + uint32_t(l32) * 16;
         float *po = P.part_o + (int64_t(head) * P.part_rows + t.part_row_base + row0 + kg) * kHeadDim + l32 * 4;
 #pragma unroll
         for (int j = 0; j < 16; ++j) {
             const f32x4 x4 = *reinterpret_cast<lds_f32x4_ptr>(uintptr_t(get + j * 2 * kStageRow));
-            if (row0 + 2 * j + kg < rows) *reinterpret_cast<f32x4 *>(po + j * 2 * kHeadDim) = x4;
+            if (row0 + 2 * j + kg < rows) st16_partial(po + j * 2 * kHeadDim, x4, P.arrive != nullptr);
         }
     }
     __syncthreads();                        // the staging areas (and the hand-over area) are free for the next task
@@ -1031,7 +1060,7 @@ __device__ void run_dense32(const PacParams &P, const DevTask &t, int head, char
 // in list order; each lane owns two channels.  Partials are taken eight or fifteen at a time: their
 // loads are issued together, then they are folded against their common maximum (by associativity of
 // the reduction this equals any binary bracketing).
-template <int DT>
+template <int DT, bool COHERENT>
 __device__ __forceinline__ void merge_one(const MergeParams &P, int r, int hq, int lane)
 {
     constexpr int kChunk = 8;
@@ -1052,8 +1081,13 @@ __device__ __forceinline__ void merge_one(const MergeParams &P, int r, int hq, i
 #pragma unroll
         for (int j = 0; j < N; ++j) {
             const int64_t prow = head_base + rows[j];
-            ml[j] = *reinterpret_cast<const float2 *>(P.part_ml + prow * 2);
-            o[j] = *reinterpret_cast<const float2 *>(P.part_o + prow * kHeadDim + lane * 2);
+            if constexpr (COHERENT) {       // rows written by other workgroups of this launch
+                ml[j] = ld8_device(P.part_ml + prow * 2);
+                o[j] = ld8_device(P.part_o + prow * kHeadDim + lane * 2);
+            } else {
+                ml[j] = *reinterpret_cast<const float2 *>(P.part_ml + prow * 2);
+                o[j] = *reinterpret_cast<const float2 *>(P.part_o + prow * kHeadDim + lane * 2);
+            }
         }
         float mm = M;
 #pragma unroll
@@ -1100,7 +1134,7 @@ __global__ void __launch_bounds__(kMergeWaves * 64) merge_kernel(const MergePara
     const int row = blockIdx.x * kMergeWaves + (threadIdx.x >> 6);
     if (row >= P.num_requests * P.h_q) return;
     const int r = row / P.h_q;
-    merge_one<DT>(P, r, row - r * P.h_q, threadIdx.x & 63);
+    merge_one<DT, false>(P, r, row - r * P.h_q, threadIdx.x & 63);
 }
 
 // ---- single-launch mode: the reduction inside the attention launch (Sec. 4.3, parallel reduction) ----
@@ -1108,15 +1142,18 @@ __global__ void __launch_bounds__(kMergeWaves * 64) merge_kernel(const MergePara
 // Every task delivers one partial result to each of its requests.  arrive[head][request] counts them
 // (device-scope atomics); the delivery that completes a request's reduction list (its length is the
 // first word of the request's line) makes the delivering workgroup reduce that request's rows of this
-// KV head right away, and put the counter back to zero for the next launch.  Order: the partial rows
-// are stored, then released together with the count (release at device scope); the workgroup that
-// sees the last count acquires before it reads the rows.
+// KV head right away, and put the counter back to zero for the next launch.  In this mode partial rows
+// are written and read with device-coherent accesses (st8_device / ld8_device), so no cache has to be
+// written back or invalidated: a delivering wave waits until its stores have been acknowledged (they are
+// then visible device-wide), and only then counts; the workgroup that sees the last count reads the rows
+// after that.  (Fences at device scope instead, with plain accesses, cost a write-back and an
+// invalidation of the whole L2 per task: measured, several times the launch they were to save.)
 __device__ __forceinline__ bool deliver(const PacParams &P, const DevTask &t, int head, int i, int &req)
 {
     req = t.single_req >= 0 ? t.single_req : P.node_q[t.q_off + i];
     const int want = P.merge.req_inline[int64_t(req) * (kInlineParts + 1)];
     int32_t *c = P.arrive + int64_t(head) * P.merge.num_requests + req;
-    const int old = __hip_atomic_fetch_add(c, 1, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT);
+    const int old = __hip_atomic_fetch_add(c, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     if (old + 1 != want) return false;
     __hip_atomic_store(c, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // nobody else counts on it in this launch
     return true;
@@ -1127,7 +1164,7 @@ template <int DT>
 __device__ void task_delivered_by_workgroup(const PacParams &P, const DevTask &t, int head, char *lds_raw, int waves)
 {
     int *count = reinterpret_cast<int *>(lds_raw), *ready = count + 1;
-    __syncthreads();                    // every wave's partial rows are on their way out; LDS is free
+    __syncthreads();                    // every wave has waited for its stores of partial rows; LDS is free
     if (threadIdx.x == 0) *count = 0;
     __syncthreads();
     if (int(threadIdx.x) < t.n_req) {
@@ -1137,12 +1174,12 @@ __device__ void task_delivered_by_workgroup(const PacParams &P, const DevTask &t
     __syncthreads();
     const int n = *count * P.group;
     if (n > 0) {
-        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");     // no load of a partial row moves above the count
         const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
 #pragma unroll 1
         for (int i = wave; i < n; i += waves) {
             const int k = i / P.group;
-            merge_one<DT>(P.merge, ready[k], head * P.group + (i - k * P.group), threadIdx.x & 63);
+            merge_one<DT, true>(P.merge, ready[k], head * P.group + (i - k * P.group), threadIdx.x & 63);
         }
     }
     __syncthreads();                    // the list is done with before LDS is used again
@@ -1153,19 +1190,19 @@ template <int DT>
 __device__ void task_delivered_by_wave(const PacParams &P, const DevTask &t, int head)
 {
     const int lane = threadIdx.x & 63;
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");      // the wave's partial rows, stored by all its lanes
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");  // waits for the wave's stores of partial rows
     int req = 0;
     const bool last = lane < t.n_req && deliver(P, t, head, lane, req);
     unsigned long long ready = __ballot(last);
     if (ready == 0) return;
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
 #pragma unroll 1
     while (ready) {
         const int src = __builtin_ctzll(ready);
         ready &= ready - 1;
         const int r = __shfl(req, src);
 #pragma unroll 1
-        for (int hj = 0; hj < P.group; ++hj) merge_one<DT>(P.merge, r, head * P.group + hj, lane);
+        for (int hj = 0; hj < P.group; ++hj) merge_one<DT, true>(P.merge, r, head * P.group + hj, lane);
     }
 }
 

@@ -156,7 +156,10 @@ void build_device_image(PlanData &p)
     L.queue_recs = place(p.queue_tasks.size() * sizeof(DevTask));
     L.counters = place(size_t(p.head.num_kv_heads) * 2 * 4);               // zero: nothing taken, nobody done
     L.arrive = place(size_t(p.head.num_kv_heads) * size_t(p.num_requests) * 4);   // zero: nothing arrived
-    if (p.fused == 2) p.fused = p.makespan < kAutoFusedMakespanNs ? 1 : 0;
+    // one workgroup may end up last for every request: more query rows than a workgroup reduces in a
+    // few rounds make the single launch slower than two (cfg2, 256 rows per KV head: 89 against 26 us)
+    if (p.fused == 2)
+        p.fused = p.makespan < kAutoFusedMakespanNs && int64_t(p.num_requests) * p.group <= kAutoFusedMaxRows ? 1 : 0;
     L.total = std::max<size_t>(off, 256);
     p.blob.assign(L.total, 0);
     // Streaming hint (kernels.hip): a task reads its slice with it when no other task reads that slice

@@ -31,6 +31,8 @@ constexpr int32_t kAutoQueueEntriesPerSlot = 6;
 // fused = 2 reduces inside the attention launch when the estimated makespan (ns) is below this: where a
 // second launch (about 5 us with the gap in front of it) is a large part of the step.
 constexpr int64_t kAutoFusedMakespanNs = 40000;
+// ... and when the batch has at most this many query rows per KV head (requests x group).
+constexpr int64_t kAutoFusedMaxRows = 64;
 
 // Task record as the kernels read it (32 bytes).  The device image holds the records twice: in the
 // order of the slots' lists and in the order of the run-time queue, so that a workgroup reads record
