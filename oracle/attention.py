@@ -38,7 +38,7 @@ def _load():
             ctypes.c_int32, i32p, i32p, ctypes.c_int32, i32p, i32p, i32p, ctypes.c_int32,
             ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, ctypes.c_double,
             u16p, u16p, u16p, ctypes.c_int64, ctypes.c_int64, ctypes.c_int64,
-            ctypes.c_int64, i32p, i32p, f64p, f64p, ctypes.c_int32]
+            ctypes.c_int64, i32p, i32p, i32p, ctypes.POINTER(ctypes.c_uint32), f64p, f64p, ctypes.c_int32]
         lib.codec_oracle_decode16.restype = ctypes.c_double
         lib.codec_oracle_decode16.argtypes = [ctypes.c_uint16, ctypes.c_int32]
         lib.codec_oracle_max_threads.restype = ctypes.c_int32
@@ -61,11 +61,13 @@ def max_threads() -> int:
 def decode_attention(parent, node_len, req_node, node_page_off, page_ids, page_size,
                      h_q, h_kv, d, dtype, scale, q_bits, k_bits, v_bits,
                      page_stride, token_stride, head_stride,
-                     sel=None, nthreads: int = 0):
+                     sel=None, nthreads: int = 0, req_mask_off=None, req_mask=None):
     """Returns (out [n, d] float64, lse [n] float64).
 
     ``sel``: optional list of (request, query head) pairs; default all pairs,
     request-major, reshaped by the caller as [B, h_q, d].
+    ``req_mask_off`` [B + 1], ``req_mask`` (uint32 words): per-request visibility over the tokens of the
+    request's last node (Sec. 4.1); a request without words sees everything.
     """
     lib = _load()
     parent = np.ascontiguousarray(parent, dtype=np.int32)
@@ -85,6 +87,12 @@ def decode_attention(parent, node_len, req_node, node_page_off, page_ids, page_s
         n = sel.shape[0]
         sr = np.ascontiguousarray(sel[:, 0])
         sh = np.ascontiguousarray(sel[:, 1])
+    mo = mw = None
+    if req_mask_off is not None:
+        mo = np.ascontiguousarray(req_mask_off, dtype=np.int32)
+        mw = np.ascontiguousarray(req_mask, dtype=np.uint32)
+        if mw.size == 0:
+            mw = np.zeros(1, dtype=np.uint32)
     out = np.zeros((n, d), dtype=np.float64)
     lse = np.zeros(n, dtype=np.float64)
     rc = lib.codec_oracle_decode_attention(
@@ -95,6 +103,8 @@ def decode_attention(parent, node_len, req_node, node_page_off, page_ids, page_s
         page_stride, token_stride, head_stride,
         n, _p(sr, ctypes.c_int32) if sr is not None else None,
         _p(sh, ctypes.c_int32) if sh is not None else None,
+        _p(mo, ctypes.c_int32) if mo is not None else None,
+        _p(mw, ctypes.c_uint32) if mw is not None else None,
         _p(out, ctypes.c_double), _p(lse, ctypes.c_double), nthreads)
     if rc != 0:
         raise ValueError(f"oracle rejected the forest (status {rc})")
@@ -107,7 +117,8 @@ def decode_attention_workload(w, sel=None, nthreads: int = 0):
     out, lse = decode_attention(f.parent, f.node_len, f.req_node, p.node_page_off, p.page_ids,
                                 p.page_size, h.num_q_heads, h.num_kv_heads, h.head_dim, h.dtype,
                                 h.scale, w.q_bits(), w.k_bits(), w.v_bits(),
-                                p.page_stride, p.token_stride, p.head_stride, sel, nthreads)
+                                p.page_stride, p.token_stride, p.head_stride, sel, nthreads,
+                                getattr(f, "req_mask_off", None), getattr(f, "req_mask", None))
     if sel is None:
         out = out.reshape(f.num_requests, h.num_q_heads, h.head_dim)
         lse = lse.reshape(f.num_requests, h.num_q_heads)

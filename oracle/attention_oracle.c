@@ -13,9 +13,17 @@
  * definition on its own, in double precision, on the exact values the 16-bit
  * inputs hold.
  *
+ * Visibility (Sec. 4.1, "Streaming softmax across nodes": a position (n, j)
+ * that is not visible to r gets the score -inf and contributes 0).  Here a
+ * request may carry a visibility mask over the tokens of the LAST node of its
+ * path (the drafted tokens of a multi-token decoding step, of which a query
+ * sees its ancestors and itself); every token of the other nodes on the path is
+ * visible.  An invisible token is left out of the request's context: that is
+ * what a score of -inf amounts to in Eq. 2.
+ *
  * Readings the paper leaves open: query head hq uses KV head hq / (h_q / h_kv)
- * (consecutive query heads share a KV head); every token of the path is
- * visible to the single decode query; each node owns whole pages and fills
+ * (consecutive query heads share a KV head); without a mask every token of the
+ * path is visible to the decode query; each node owns whole pages and fills
  * them in order, so logical token t of a node lives in the node's page
  * t / page_size at slot t % page_size.
  */
@@ -69,6 +77,12 @@ double codec_oracle_decode16(uint16_t bits, int32_t dtype)
  * to evaluate all B*h_q pairs in (request-major, head-minor) order.
  * out: [n][d] doubles, lse: [n] doubles (natural-log sum-exp of the scaled
  * scores), n = n_sel or B*h_q.  Strides are in elements.
+ *
+ * req_mask_off / req_mask: NULL, or per request r the 32-bit words
+ * req_mask[req_mask_off[r] .. req_mask_off[r+1]): none = everything visible,
+ * else bit (t % 32) of word t / 32 says whether token t of node req_node[r]
+ * is visible to r (there must be a word for every 32 tokens of that node).
+ * Returns -3 if a request with a mask sees no token at all.
  */
 int codec_oracle_decode_attention(
     int32_t num_nodes, const int32_t *parent, const int32_t *node_len,
@@ -79,6 +93,7 @@ int codec_oracle_decode_attention(
     const uint16_t *k_pool, const uint16_t *v_pool,
     int64_t page_stride, int64_t token_stride, int64_t head_stride,
     int64_t n_sel, const int32_t *sel_req, const int32_t *sel_head,
+    const int32_t *req_mask_off, const uint32_t *req_mask,
     double *out, double *lse, int32_t nthreads)
 {
     const int64_t total = sel_req ? n_sel : (int64_t)num_requests * h_q;
@@ -128,12 +143,17 @@ int codec_oracle_decode_attention(
         for (int c = 0; c < d; ++c)
             qv[c] = load16(q + ((int64_t)r * h_q + hq) * d + c, dtype);
 
-        /* scores over the concatenated context, root first */
+        /* the request's mask over its last node, if it has one */
+        const uint32_t *mask = NULL;
+        if (req_mask_off && req_mask_off[r + 1] > req_mask_off[r]) mask = req_mask + req_mask_off[r];
+
+        /* scores over the concatenated visible context, root first */
         int64_t pos = 0;
         double mx = -INFINITY;
         for (int lvl = depth - 1; lvl >= 0; --lvl) {
             const int n = path[lvl];
             for (int t = 0; t < node_len[n]; ++t) {
+                if (lvl == 0 && mask && !((mask[t / 32] >> (t % 32)) & 1u)) continue;
                 const int64_t page = page_ids[node_page_off[n] + t / page_size];
                 const uint16_t *krow = k_pool + page * page_stride
                                        + (int64_t)(t % page_size) * token_stride
@@ -146,9 +166,16 @@ int codec_oracle_decode_attention(
                 if (s > mx) mx = s;
             }
         }
+        const int64_t seen = pos;
+        if (seen == 0) {
+#pragma omp atomic write
+            status = -3;
+            free(path); free(score); free(qv);
+            continue;
+        }
         /* softmax with the maximum subtracted (Eq. 2) */
         double sum = 0.0;
-        for (int64_t i = 0; i < ctx; ++i) {
+        for (int64_t i = 0; i < seen; ++i) {
             score[i] = exp(score[i] - mx);
             sum += score[i];
         }
@@ -158,6 +185,7 @@ int codec_oracle_decode_attention(
         for (int lvl = depth - 1; lvl >= 0; --lvl) {
             const int n = path[lvl];
             for (int t = 0; t < node_len[n]; ++t) {
+                if (lvl == 0 && mask && !((mask[t / 32] >> (t % 32)) & 1u)) continue;
                 const int64_t page = page_ids[node_page_off[n] + t / page_size];
                 const uint16_t *vrow = v_pool + page * page_stride
                                        + (int64_t)(t % page_size) * token_stride

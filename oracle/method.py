@@ -32,9 +32,15 @@ def widen(bits: np.ndarray, dtype: int) -> np.ndarray:
         return (bits.astype(np.uint32) << np.uint32(16)).view(np.float32).astype(np.float64)
 
 
-def pac(Q: np.ndarray, K: np.ndarray, V: np.ndarray, scale: float):
-    """Alg. 2 on Q [n_q, d], K, V [n, d] -> (O [n_q, d], m [n_q], s [n_q])."""
+def pac(Q: np.ndarray, K: np.ndarray, V: np.ndarray, scale: float, visible=None):
+    """Alg. 2 on Q [n_q, d], K, V [n, d] -> (O [n_q, d], m [n_q], s [n_q]).
+
+    ``visible`` [n_q, n] bool: the visibility mask of Sec. 4.1 (an invisible position gets the score
+    -inf and contributes 0); every query must see at least one position.
+    """
     S = (Q @ K.T) * scale
+    if visible is not None:
+        S = np.where(visible, S, -np.inf)
     m = S.max(axis=1)
     P = np.exp(S - m[:, None])
     s = P.sum(axis=1)
@@ -89,6 +95,21 @@ def gather_node_kv(w, node: int, kvh: int, t0: int, t1: int):
     return widen(kb[idx], h.dtype), widen(vb[idx], h.dtype)
 
 
+def _visibility(f, node: int, reqs, g: int, t0: int, t1: int):
+    """Rows (request x head of the group) x tokens [t0, t1) of ``node``: which positions each row sees
+    (Sec. 4.1).  A request's mask covers its last node only; None when no row of the task is masked."""
+    if getattr(f, "req_mask_off", None) is None:
+        return None
+    rows = []
+    any_mask = False
+    for r in reqs:
+        vis = f.visible(int(r)) if int(f.req_node[int(r)]) == node else None
+        any_mask |= vis is not None
+        row = np.ones(t1 - t0, dtype=bool) if vis is None else vis[t0:t1]
+        rows += [row] * g
+    return np.stack(rows) if any_mask else None
+
+
 def codec(w):
     """Alg. 4 on a workload -> out [B, h_q, d] float64 (tree sharing, node-level partials)."""
     f, h = w.forest, w.head
@@ -105,7 +126,7 @@ def codec(w):
                 continue
             K, V = gather_node_kv(w, n, kvh, 0, int(f.node_len[n]))
             Qn = Q[node_q[n], kvh * g:(kvh + 1) * g, :].reshape(-1, h.head_dim)
-            tree[n] = pac(Qn, K, V, h.scale)
+            tree[n] = pac(Qn, K, V, h.scale, _visibility(f, n, node_q[n], g, 0, int(f.node_len[n])))
         for r in range(B):
             acc = None
             for n in paths[r]:
@@ -139,7 +160,7 @@ def replay_tasks(w, tasks, node_q_flat, req_part_off, req_part):
             reqs = node_q_flat[q_off:q_off + n_req]
             K, V = gather_node_kv(w, int(node), kvh, int(kv_begin), int(kv_begin + kv_len))
             Qt = Q[reqs, kvh * g:(kvh + 1) * g, :].reshape(-1, d)
-            O, m, s = pac(Qt, K, V, h.scale)
+            O, m, s = pac(Qt, K, V, h.scale, _visibility(f, int(node), reqs, g, int(kv_begin), int(kv_begin + kv_len)))
             rows = slice(int(base), int(base) + n_req * g)
             assert np.all(np.isnan(PM[rows])), "two tasks write the same partial rows"
             PO[rows], PM[rows], PS[rows] = O, m, s

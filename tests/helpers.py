@@ -16,10 +16,17 @@ def pool_row(pool, w, page, slot, kvh):
 
 
 def request_context(w, r, kvh):
-    """Concatenated (K, V) float64 [N_r, d] of request r for one KV head, root first."""
+    """Concatenated (K, V) float64 [N_r, d] of request r for one KV head, root first: the tokens of the
+    nodes on its path, without those of its last node that its visibility mask (if any) hides."""
     ks, vs = [], []
-    for node in w.forest.path(r):
-        for t in range(int(w.forest.node_len[node])):
+    f = w.forest
+    words = None
+    if getattr(f, "req_mask_off", None) is not None and f.req_mask_off[r + 1] > f.req_mask_off[r]:
+        words = [int(x) for x in f.req_mask[f.req_mask_off[r]:f.req_mask_off[r + 1]]]
+    for node in f.path(r):
+        for t in range(int(f.node_len[node])):
+            if words is not None and node == int(f.req_node[r]) and not (words[t // 32] >> (t % 32)) & 1:
+                continue
             page, slot = token_slot(w, node, t)
             ks.append(pool_row(w.k_pool, w, page, slot, kvh))
             vs.append(pool_row(w.v_pool, w, page, slot, kvh))

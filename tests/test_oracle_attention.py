@@ -14,7 +14,8 @@ from scipy.special import logsumexp
 
 from oracle import attention as A
 from workloads import (HeadConfig, make_workload, two_level_forest, three_level_forest,
-                       unshared_forest, random_forest, draft_tree_forest, DTYPE_FP16, DTYPE_BF16, Forest)
+                       unshared_forest, random_forest, draft_tree_forest, draft_masked_forest, concat_forests,
+                       DTYPE_FP16, DTYPE_BF16, Forest)
 from helpers import request_context, q_float64, set_token, token_slot, pool_row
 
 
@@ -107,6 +108,79 @@ def test_brute_force_drafted_token_trees():
     assert below and others
     assert np.array_equal(out2[others], out[others])
     assert all(np.max(np.abs(out2[r] - out[r])) > 1e-6 for r in below)
+
+
+def test_brute_force_with_visibility_masks():
+    """Sec. 4.1 visibility: a request with a mask over its last node attends to the visible tokens only
+    (brute-force loops over the materialised visible context); 40 drafted tokens need two mask words."""
+    f = concat_forests(draft_masked_forest(5, [7, 3], 6, seed=2), draft_masked_forest(0, [9], 40, seed=5))
+    w = make_workload("masked", f, HeadConfig(4, 2, 8, DTYPE_BF16, page_size=4), seed=9, poison=True)
+    out, lse = A.decode_attention_workload(w)
+    ref, ref_lse = brute_force(w)
+    assert np.max(np.abs(out - ref)) < 1e-13 and np.max(np.abs(lse - ref_lse)) < 1e-12
+    # masks really hide something: with every bit set the drafted requests give other results
+    full = Forest(f.parent, f.node_len, f.req_node, f.req_mask_off, np.full_like(f.req_mask, 0xFFFFFFFF))
+    w_all = make_workload("masked", full, w.head, seed=9, poison=True)
+    out_all, _ = A.decode_attention_workload(w_all)
+    unmasked = Forest(f.parent, f.node_len, f.req_node)
+    out_none, _ = A.decode_attention_workload(make_workload("masked", unmasked, w.head, seed=9, poison=True))
+    assert np.array_equal(out_all, out_none)                # all bits set = no mask at all
+    hidden = [r for r in range(f.num_requests) if f.visible(r) is not None and not f.visible(r).all()]
+    assert len(hidden) > 20 and all(np.max(np.abs(out[r] - out_none[r])) > 1e-9 for r in hidden)
+
+
+def test_masked_draft_node_equals_tree_of_one_token_nodes():
+    """Two statements of one verification step: every drafted token a node of its own (what a query sees
+    is its path: pinned by brute force above), or all drafted tokens of a sequence in one node with a
+    mask per query.  Same drafted trees, the same K/V rows copied token by token: identical outputs, the
+    visible tokens being summed in the same order."""
+    head = HeadConfig(4, 2, 16, DTYPE_FP16, page_size=4)
+    tree = draft_tree_forest(11, [19, 6, 33], 9, seed=12)
+    packed = draft_masked_forest(11, [19, 6, 33], 9, seed=12)
+    assert tree.num_requests == packed.num_requests == 3 * 10
+    a = make_workload("tree", tree, head, seed=4, poison=True)
+    b = make_workload("packed", packed, head, seed=5, poison=True)
+    b.q[:] = a.q
+    # node numbering: tree = prompt, then per sequence context + 9 one-token nodes; packed = prompt, then
+    # per sequence context + one 9-token node
+    pairs = [((0, t), (0, t)) for t in range(11)]
+    for i, n in enumerate([19, 6, 33]):
+        ta, tb = 1 + i * 10, 1 + i * 2
+        pairs += [((ta, t), (tb, t)) for t in range(n)]
+        pairs += [((ta + 1 + k, 0), (tb + 1, k)) for k in range(9)]
+    _copy_logical(a, b, pairs)
+    out_a, lse_a = A.decode_attention_workload(a)
+    out_b, lse_b = A.decode_attention_workload(b)
+    assert np.array_equal(out_a, out_b) and np.array_equal(lse_a, lse_b)
+
+
+def test_planted_key_is_seen_through_the_mask_only():
+    """A key with a huge logit planted in drafted token k: the requests whose mask has bit k answer with
+    (almost exactly) that token's V row, every other request's output does not move by one bit."""
+    f = draft_masked_forest(4, [10, 5], 7, seed=21)
+    head = HeadConfig(2, 2, 8, DTYPE_FP16, page_size=4)
+    w = make_workload("planted", f, head, seed=6, poison=True)
+    w.q[:] = torch.ones_like(w.q)
+    base, _ = A.decode_attention_workload(w)
+    draft_node, k = 2, 3                                   # first sequence's draft node, its fourth token
+    marker = torch.arange(8, dtype=torch.float32) - 3.0
+    for kvh in range(2):
+        set_token(w, draft_node, k, kvh, k_row=torch.full((8,), 30.0), v_row=marker)
+    out, _ = A.decode_attention_workload(w)
+    sees = [r for r in range(f.num_requests) if f.req_node[r] == draft_node and f.visible(r)[k]]
+    blind = [r for r in range(f.num_requests) if r not in sees]
+    assert sees and len(blind) > len(sees)
+    assert np.array_equal(out[blind], base[blind])
+    for r in sees:
+        assert np.max(np.abs(out[r] - marker.double().numpy())) < 1e-9
+
+
+def test_request_that_sees_nothing_is_rejected():
+    """A mask that hides every token of a request whose path is its last node alone: no context at all."""
+    g = Forest(np.array([-1]), np.array([5]), np.array([0]), np.array([0, 1]), np.array([0], dtype=np.uint32))
+    w = make_workload("blind", g, HeadConfig(2, 2, 8, DTYPE_FP16, page_size=4), seed=1)
+    with pytest.raises(ValueError):
+        A.decode_attention_workload(w)
 
 
 def test_single_sequence_equals_torch_softmax():

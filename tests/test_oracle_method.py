@@ -129,3 +129,28 @@ def test_tree_merged_equals_definition_on_shrunken_config():
     ref, _ = A.decode_attention_workload(w)
     got = M.codec(w)
     assert np.max(np.abs(got - ref)) < 1e-13
+
+
+def test_masked_pac_is_attention_over_the_visible_positions():
+    """Alg. 2 with the visibility mask of Sec. 4.1: a row's result equals plain softmax attention (scipy)
+    over the positions it sees."""
+    from scipy.special import softmax
+    rng = np.random.default_rng(11)
+    Q, K, V = rng.standard_normal((6, 16)), rng.standard_normal((21, 16)), rng.standard_normal((21, 16))
+    vis = rng.random((6, 21)) < 0.4
+    vis[np.arange(6), rng.integers(0, 21, size=6)] = True           # everybody sees something
+    O, m, s = M.pac(Q, K, V, 0.25, vis)
+    for i in range(6):
+        idx = np.nonzero(vis[i])[0]
+        sc = (K[idx] @ Q[i]) * 0.25
+        assert np.allclose(O[i], softmax(sc) @ V[idx], atol=1e-14)
+        assert np.isclose(m[i], sc.max()) and np.isclose(s[i], np.exp(sc - sc.max()).sum())
+
+
+def test_tree_merged_result_with_masks_equals_definition():
+    """Alg. 4 with masked drafted-token nodes (node-level partials, per-query reduction) = the definition."""
+    from workloads import draft_masked_forest, DTYPE_BF16
+    f = draft_masked_forest(20, [33, 9, 70], 37, seed=8)
+    w = make_workload("masked-codec", f, HeadConfig(4, 2, 16, DTYPE_BF16, page_size=8), seed=3, poison=True)
+    ref, _ = A.decode_attention_workload(w)
+    assert np.max(np.abs(M.codec(w) - ref)) < 1e-13

@@ -6,7 +6,7 @@ no planning), so both the CPU oracle's tests and the HIP path's tests can draw
 their inputs from it without sharing any code of the method itself.
 """
 from .trees import (Forest, two_level_forest, three_level_forest, random_forest,
-                    unshared_forest, full_kary_forest, degenerate_forest, draft_tree_forest,
+                    unshared_forest, full_kary_forest, degenerate_forest, draft_tree_forest, draft_masked_forest,
                     concat_forests, forest_stats)
 from .tensors import (HeadConfig, PagedKV, Workload, build_paged_kv, make_workload,
                       bits_to_float64, float_to_bits, DTYPE_FP16, DTYPE_BF16)
@@ -14,7 +14,7 @@ from .configs import CONFIG_NAMES, make_config, make_small_config
 
 __all__ = [
     "Forest", "two_level_forest", "three_level_forest", "random_forest", "unshared_forest",
-    "full_kary_forest", "degenerate_forest", "draft_tree_forest", "concat_forests", "forest_stats",
+    "full_kary_forest", "degenerate_forest", "draft_tree_forest", "draft_masked_forest", "concat_forests", "forest_stats",
     "HeadConfig", "PagedKV", "Workload", "build_paged_kv", "make_workload",
     "bits_to_float64", "float_to_bits", "DTYPE_FP16", "DTYPE_BF16",
     "CONFIG_NAMES", "make_config", "make_small_config",

@@ -11,7 +11,7 @@ and the configurations this build is measured on.
 from __future__ import annotations
 
 from dataclasses import dataclass
-from typing import List, Sequence
+from typing import List, Optional, Sequence
 
 import numpy as np
 
@@ -21,12 +21,30 @@ class Forest:
     parent: np.ndarray      # int32 [N]
     node_len: np.ndarray    # int32 [N]
     req_node: np.ndarray    # int32 [B]
+    # optional visibility masks over the tokens of each request's LAST node: request r owns the 32-bit
+    # words req_mask[req_mask_off[r] : req_mask_off[r + 1]] (none: it sees every token); bit t % 32 of
+    # word t // 32 says whether it sees token t of node req_node[r]
+    req_mask_off: Optional[np.ndarray] = None   # int32 [B + 1]
+    req_mask: Optional[np.ndarray] = None       # uint32
 
     def __post_init__(self):
         self.parent = np.ascontiguousarray(self.parent, dtype=np.int32)
         self.node_len = np.ascontiguousarray(self.node_len, dtype=np.int32)
         self.req_node = np.ascontiguousarray(self.req_node, dtype=np.int32)
         assert self.parent.shape == self.node_len.shape
+        if self.req_mask_off is not None:
+            self.req_mask_off = np.ascontiguousarray(self.req_mask_off, dtype=np.int32)
+            self.req_mask = np.ascontiguousarray(self.req_mask, dtype=np.uint32)
+            assert self.req_mask_off.shape == (self.req_node.shape[0] + 1,)
+
+    def visible(self, r: int) -> Optional[np.ndarray]:
+        """bool [node_len of r's last node], or None when request r carries no mask."""
+        if self.req_mask_off is None or self.req_mask_off[r + 1] == self.req_mask_off[r]:
+            return None
+        words = self.req_mask[self.req_mask_off[r]:self.req_mask_off[r + 1]]
+        n = int(self.node_len[self.req_node[r]])
+        t = np.arange(n)
+        return ((words[t // 32] >> (t % 32).astype(np.uint32)) & 1).astype(bool)
 
     @property
     def num_nodes(self) -> int:
@@ -187,14 +205,71 @@ def draft_tree_forest(prompt_len: int, context_lens: Sequence[int], draft_tokens
     return Forest(np.array(parent), np.array(node_len), np.array(req_node))
 
 
+def draft_masked_forest(prompt_len: int, context_lens: Sequence[int], draft_tokens: int, seed: int) -> Forest:
+    """The verification step of ``draft_tree_forest`` with the drafted tokens of a sequence packed into
+    ONE node and visibility masks in place of one-token nodes.
+
+    Same seeded draft trees and the same request order as ``draft_tree_forest`` (a request for the
+    sequence's context, then one per drafted token in the order they were drafted).  The drafted tokens
+    of a sequence form a node of ``draft_tokens`` tokens below the sequence's context, token k being the
+    k-th drafted one; the request of drafted token k ends at that node and sees, of its tokens, token k
+    and the drafted tokens k was drafted after (its ancestors in the draft tree): bit j of its mask.
+    A token is always drafted after an earlier one, so a request's visible tokens come in the order of
+    its path in the one-token-node formulation.
+    """
+    rng = np.random.Generator(np.random.PCG64(seed))
+    parent: List[int] = []
+    node_len: List[int] = []
+    req_node: List[int] = []
+    masks: List[List[int]] = []
+    words = (draft_tokens + 31) // 32
+    top = -1
+    if prompt_len > 0:
+        parent.append(-1); node_len.append(prompt_len); top = 0
+    for ctx_len in context_lens:
+        parent.append(top); node_len.append(int(ctx_len))
+        ctx = len(parent) - 1
+        req_node.append(ctx)
+        masks.append([])
+        if draft_tokens == 0:
+            continue
+        parent.append(ctx); node_len.append(draft_tokens)
+        draft = len(parent) - 1
+        after_of: List[int] = []                  # per drafted token: the drafted token before it, -1 = the context
+        order = [-1]                              # the tokens drafted so far, the context first (as in draft_tree_forest)
+        for k in range(draft_tokens):
+            after = order[-1] if rng.random() < 0.5 else order[int(rng.integers(len(order)))]
+            after_of.append(after)
+            order.append(k)
+            bits = [0] * words
+            t = k
+            while t != -1:
+                bits[t // 32] |= 1 << (t % 32)
+                t = after_of[t]
+            req_node.append(draft)
+            masks.append(bits)
+    off = np.zeros(len(req_node) + 1, dtype=np.int32)
+    np.cumsum([len(m) for m in masks], out=off[1:])
+    flat = np.array([w for m in masks for w in m], dtype=np.uint32)
+    return Forest(np.array(parent), np.array(node_len), np.array(req_node), off, flat)
+
+
 def concat_forests(a: Forest, b: Forest) -> Forest:
     """Both forests under one virtual root; b's node ids are shifted by a.num_nodes."""
     shift = a.num_nodes
     pb = b.parent.copy()
     pb[pb >= 0] += shift
+    off = words = None
+    if a.req_mask_off is not None or b.req_mask_off is not None:
+        ao = a.req_mask_off if a.req_mask_off is not None else np.zeros(a.num_requests + 1, dtype=np.int32)
+        bo = b.req_mask_off if b.req_mask_off is not None else np.zeros(b.num_requests + 1, dtype=np.int32)
+        aw = a.req_mask if a.req_mask is not None else np.zeros(0, dtype=np.uint32)
+        bw = b.req_mask if b.req_mask is not None else np.zeros(0, dtype=np.uint32)
+        off = np.concatenate([ao, bo[1:] + ao[-1]])
+        words = np.concatenate([aw, bw])
     return Forest(np.concatenate([a.parent, pb]),
                   np.concatenate([a.node_len, b.node_len]),
-                  np.concatenate([a.req_node, b.req_node + shift]))
+                  np.concatenate([a.req_node, b.req_node + shift]), off, words)
 
 
 def forest_stats(f: Forest) -> dict:
