@@ -64,6 +64,21 @@ typedef struct {
  * req_node[r] (a leaf or an internal node).  Node i owns the whole pages
  * page_ids[node_page_off[i] .. node_page_off[i+1]) and fills them in order, so
  * only its last page may be partly used.  All arrays are host memory.
+ *
+ * Visibility masks (Sec. 4.1: a position that is not visible to a query scores
+ * -inf and contributes nothing; multi-token decoding, e.g. the verification of
+ * tree-structured drafts).  A request is one query token.  It may carry a mask
+ * over the tokens of the LAST node of its path: with the drafted tokens of a
+ * sequence stored in one node, the query of a drafted token ends at that node
+ * and sees, of its tokens, itself and the drafted tokens before it on its
+ * branch; every token of the other nodes on its path is visible.
+ * req_mask_off == NULL: no masks.  Else request r owns the 32-bit words
+ * req_mask[req_mask_off[r] .. req_mask_off[r+1]): none (it sees everything), or
+ * exactly one word per 32 tokens of node req_node[r], bit t % 32 of word t / 32
+ * saying whether it sees token t; it must see at least one token of that node
+ * (CODEC_ERR_INVALID_TREE otherwise).  A node that ends a masked request is not
+ * divided along KV, and its queries are tiled 16 rows at a time; masks need
+ * num_q_heads / num_kv_heads <= 16 (CODEC_ERR_UNSUPPORTED otherwise).
  */
 typedef struct {
     int32_t        num_nodes;
@@ -73,6 +88,8 @@ typedef struct {
     const int32_t *req_node;        /* [num_requests]   */
     const int32_t *node_page_off;   /* [num_nodes + 1]  */
     const int32_t *page_ids;        /* [node_page_off[num_nodes]] */
+    const int32_t  *req_mask_off;   /* NULL, or [num_requests + 1], ascending from 0 */
+    const uint32_t *req_mask;       /* [req_mask_off[num_requests]] */
 } codec_tree;
 
 /*
@@ -251,7 +268,8 @@ int codec_plan_export(const codec_plan_t *plan, codec_plan_view *view);
  * recomputed.  The forest itself (parents, requests) must be the one the plan
  * was created for; node_len[num_nodes], node_page_off[num_nodes + 1] and
  * page_ids[node_page_off[num_nodes]] are host arrays with the meaning they have
- * in codec_tree and are copied.  Host only.
+ * in codec_tree and are copied.  Host only.  Visibility masks are kept as they
+ * are: a node that ends a masked request must keep its length.
  *
  * The device copy of the metadata becomes stale: codec_plan_device_bytes may
  * have grown (longer page lists) and codec_plan_upload must be called again

@@ -120,7 +120,11 @@ def build_index(parent, node_len, req_node):
 
 def plan(parent, node_len, req_node, group: int, num_slots: int, align: int,
          max_rows: int, share: bool, table: Dict, fixed_slices: int = 0,
-         slack: bool = False, diagonal: bool = False) -> Dict:
+         slack: bool = False, diagonal: bool = False, masked_nodes=()) -> Dict:
+    """``masked_nodes``: nodes that end a request with a visibility mask (Sec. 4.1).  The library runs
+    masks in its 16-row task shape only, so such a node gets row tiles of at most 16 rows and is not
+    divided along KV (its bound and slice count are 1)."""
+    masked_nodes = set(int(n) for n in masked_nodes)
     parent = [int(x) for x in parent]
     node_len = [int(x) for x in node_len]
     req_node = [int(x) for x in req_node]
@@ -135,19 +139,21 @@ def plan(parent, node_len, req_node, group: int, num_slots: int, align: int,
         node_q_off.append(len(node_q_flat))
 
     # work items: (node, request range); a flat plan gives every request its own item
-    qpt = max(1, max_rows // group) if share else 1
+    qpt_all = max(1, max_rows // group) if share else 1
+    qpt_of = [min(qpt_all, max(1, 16 // group)) if n in masked_nodes else qpt_all for n in range(n_nodes)]
     items = []
     first_item_of_node = [0] * n_nodes
     for n in range(n_nodes):
         first_item_of_node[n] = len(items)
         nq = len(node_q[n])
+        qpt = qpt_of[n]
         for a in range(0, nq, qpt):
             cnt = min(qpt, nq - a)
             items.append({"node": n, "q_off": node_q_off[n] + a, "n_req": cnt,
                           "rows": cnt * group, "len": node_len[n]})
     for it in items:
         it["cost"] = c_est(table, it["rows"], it["len"])
-        it["max_b"] = _ceil_div(it["len"], align)
+        it["max_b"] = 1 if it["node"] in masked_nodes else _ceil_div(it["len"], align)
 
     def b_of(it, T):
         return min(_ceil_div(it["cost"], T), it["max_b"])
@@ -247,6 +253,7 @@ def plan(parent, node_len, req_node, group: int, num_slots: int, align: int,
     for r, p in enumerate(paths):
         for n in p:
             qi = node_q[n].index(r)
+            qpt = qpt_of[n]
             j = first_item_of_node[n] + qi // qpt
             it = items[j]
             t0 = first_task_of_item[j]
@@ -298,7 +305,7 @@ def refresh(plan_out: Dict, table: Dict, new_node_len) -> Dict:
 
 
 def plan_best(parent, node_len, req_node, group: int, align: int, max_rows: int, tables: Dict,
-              num_slots_of, slack: bool = False, diagonal: bool = False) -> Dict:
+              num_slots_of, slack: bool = False, diagonal: bool = False, masked_nodes=()) -> Dict:
     """share = 2 of the library: the candidate with the lowest estimated makespan, ties to the earlier.
 
     Candidates: the prefix-shared plan with row tiles of ``max_rows``; with row tiles of half that (if
@@ -318,11 +325,13 @@ def plan_best(parent, node_len, req_node, group: int, align: int, max_rows: int,
     best = None
     for share, rows in cands:
         paths, node_q = build_index([int(x) for x in parent], [int(x) for x in node_len], [int(x) for x in req_node])
-        qpt = max(1, rows // group) if share else 1
-        widest = max((min(qpt, len(q) - a) * group for q in node_q for a in range(0, len(q), qpt)), default=0)
+        qpt_all = max(1, rows // group) if share else 1
+        tile = [min(qpt_all, max(1, 16 // group)) if n in set(masked_nodes) else qpt_all for n in range(len(node_q))]
+        widest = max((min(tile[n], len(q) - a) * group for n, q in enumerate(node_q)
+                      for a in range(0, len(q), tile[n])), default=0)
         wide = widest > 16
         p = plan(parent, node_len, req_node, group, num_slots_of(wide), align, rows, share,
-                 tables["wide" if wide else "narrow"], slack=slack, diagonal=diagonal)
+                 tables["wide" if wide else "narrow"], slack=slack, diagonal=diagonal, masked_nodes=masked_nodes)
         p["share"], p["max_rows"] = share, rows
         if best is None or p["makespan"] < best["makespan"]:
             best = p

@@ -51,7 +51,8 @@ class codec_head_config(Structure):
 class codec_tree(Structure):
     _fields_ = [("num_nodes", c_int32), ("parent", _i32p), ("node_len", _i32p),
                 ("num_requests", c_int32), ("req_node", _i32p),
-                ("node_page_off", _i32p), ("page_ids", _i32p)]
+                ("node_page_off", _i32p), ("page_ids", _i32p),
+                ("req_mask_off", _i32p), ("req_mask", POINTER(ctypes.c_uint32))]
 
 
 class codec_cost_table(Structure):
@@ -181,12 +182,19 @@ def codec_last_error_message() -> str:
 def codec_plan_create(parent, node_len, req_node, node_page_off, page_ids,
                       num_q_heads, num_kv_heads, head_dim, dtype, page_size, scale,
                       num_slots=0, split_align=0, max_rows=0, share=1, cost_table=None, fixed_slices=0,
-                      schedule=0, extensions=0, fused=0):
-    """Returns (status, plan handle or None).  ``cost_table``: (row_grid, len_grid, cost) or None."""
+                      schedule=0, extensions=0, fused=0, req_mask_off=None, req_mask=None):
+    """Returns (status, plan handle or None).  ``cost_table``: (row_grid, len_grid, cost) or None;
+    ``req_mask_off`` / ``req_mask``: per-request visibility masks (see codec_tree) or None."""
     parent, node_len, req_node = _i32(parent), _i32(node_len), _i32(req_node)
     node_page_off, page_ids = _i32(node_page_off), _i32(page_ids)
+    mask_off = mask_words = None
+    if req_mask_off is not None:
+        mask_off = _i32(req_mask_off)
+        mask_words = np.ascontiguousarray(req_mask if req_mask is not None else [], dtype=np.uint32)
     tree = codec_tree(len(parent), _ptr(parent), _ptr(node_len), len(req_node), _ptr(req_node),
-                      _ptr(node_page_off), _ptr(page_ids))
+                      _ptr(node_page_off), _ptr(page_ids),
+                      _ptr(mask_off) if mask_off is not None else None,
+                      _ptr(mask_words, ctypes.c_uint32) if mask_words is not None else None)
     head = codec_head_config(num_q_heads, num_kv_heads, head_dim, dtype, page_size, scale)
     keep = None
     ct_ptr = None

@@ -268,6 +268,10 @@ int partial_attention(const codec_plan_t *plan, const void *q, const void *k_pag
         pp.counters = reinterpret_cast<int32_t *>(const_cast<char *>(meta) + L.counters);
         pp.num_entries = int32_t(d.queue_off.size()) - 1;
     }
+    if (!d.req_mask_off.empty()) {
+        pp.nodeq_mask = reinterpret_cast<const int32_t *>(meta + L.nodeq_mask);
+        pp.mask_words = reinterpret_cast<const uint32_t *>(meta + L.mask_words);
+    }
     if (fused_out) {
         pp.merge = merge_params(plan, workspace, fused_out);
         pp.arrive = reinterpret_cast<int32_t *>(const_cast<char *>(meta) + L.arrive);

@@ -179,13 +179,18 @@ __device__ __forceinline__ int64_t page_offset(const SliceCtx &c, int pg, int sl
 struct BlockRegs {
     u32x4 k[2][4];      // [tile][k-step]: token = tile*16 + lane%16, channels 32*ks + 8*(lane/16)..+7
     u32x4 v[8];         // [e]: token = (e/4)*16 + 4*(lane/16) + e%4, channels 8*(lane%16)..+7
+    uint32_t visible;   // masked tasks: bit t = the lane's row sees token t of the block
 };
 
 // Issue the loads of block `tb`.  A tile that starts beyond the slice is redirected to tile 0 so that
 // no address leaves the slice's pages; its scores are masked later.  ONCE: with the streaming hint.
 template <bool ONCE>
-__device__ __forceinline__ void load_block(const SliceCtx &c, int tb, uint32_t koff, uint32_t voff, BlockRegs &r)
+__device__ __forceinline__ void load_block(const SliceCtx &c, int tb, uint32_t koff, uint32_t voff, BlockRegs &r,
+                                           bool masked, const uint32_t *mask_row)
 {
+    // the word of the row's visibility mask for this block (a slice with masks starts at token 0 of its
+    // node; a row without a mask sees everything)
+    if (masked) r.visible = mask_row ? mask_row[tb] : 0xFFFFFFFFu;
     int tok[2], pg[2];
 #pragma unroll
     for (int j = 0; j < 2; ++j) {
@@ -208,19 +213,24 @@ __device__ __forceinline__ void load_block(const SliceCtx &c, int tb, uint32_t k
     }
 }
 
+// Initial reference of a row.  Finite, so that a block in which a row sees no token at all (every score
+// -inf under its visibility mask) yields exp2(-inf - m) = 0 and not exp2(-inf + inf); so low that the
+// first finite score raises the reference and wipes (multiplies by exp2 of -1e30) whatever it scaled.
+constexpr float kNoReference = -1e30f;
+
 template <int NT>
 struct RowState {
     f32x4 o[NT][8];     // [row tile][dt]: row = 16*nt + lane%16; channel of component e is
                         // 32*(lane/16) + 8*e + dt
     float m[NT];        // reference subtracted before exponentiation, log2 units (same in the 4 lanes
-                        // that share a row)
+                        // that share a row); kNoReference until the row has seen a score above -inf
     float l[NT];        // the lane's share of the row sum; the row sum after finish()
 
     __device__ __forceinline__ void clear()
     {
 #pragma unroll
         for (int nt = 0; nt < NT; ++nt) {
-            m[nt] = -INFINITY;
+            m[nt] = kNoReference;
             l[nt] = 0.f;
 #pragma unroll
             for (int dt = 0; dt < 8; ++dt) o[nt][dt] = f32x4{0.f, 0.f, 0.f, 0.f};
@@ -258,6 +268,21 @@ __device__ __forceinline__ void mask_scores(f32x4 (&s)[2][NT], int valid, int gr
             const bool dead = j * 16 + grp * 4 + e >= valid;
 #pragma unroll
             for (int nt = 0; nt < NT; ++nt) s[j][nt][e] = dead ? -INFINITY : s[j][nt][e];
+        }
+}
+
+// Scores of tokens the row does not see become -inf (visibility mask, Sec. 4.1): bit t of `visible` is
+// token t of the block.
+template <int NT>
+__device__ __forceinline__ void mask_invisible(f32x4 (&s)[2][NT], uint32_t visible, int grp)
+{
+    static_assert(NT == 1, "one mask word per lane: one row per lane");
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const bool seen = (visible >> (j * 16 + grp * 4 + e)) & 1u;
+            s[j][0][e] = seen ? s[j][0][e] : -INFINITY;
         }
 }
 
@@ -419,7 +444,7 @@ __device__ __forceinline__ SliceCtx make_ctx(const PacParams &P, const DevTask &
     c.kv_len = t.kv_len;
     c.page_shift = P.page_shift;
     c.page_mask = (1 << P.page_shift) - 1;
-    c.read_once = t.read_once;
+    c.read_once = t.flags & kTaskReadOnce;
     return c;
 }
 
@@ -443,6 +468,15 @@ __device__ void run_stream(const PacParams &P, const DevTask &t, int head, char 
     const uint32_t koff = uint32_t(l16) * c.token_bytes + grp * 16;
     const uint32_t voff = uint32_t(grp * 4) * c.token_bytes + l16 * 16;
 
+    // visibility mask of the lane's row, if the task has any (masked tasks hold at most 16 rows and are
+    // never slices of a node: block tb of the task is word tb of the mask)
+    const bool masked = (t.flags & kTaskMasked) != 0;
+    const uint32_t *mask_row = nullptr;
+    if (masked && l16 < rows) {
+        const int off = P.nodeq_mask[t.q_off + l16 / P.group];
+        if (off >= 0) mask_row = P.mask_words + off;
+    }
+
     RowState<NT> st;
     st.clear();
 
@@ -462,6 +496,7 @@ __device__ void run_stream(const PacParams &P, const DevTask &t, int head, char 
             mask_scores<NT>(s, valid, grp);
             mask_values(r.v, valid, grp);
         }
+        if (masked) mask_invisible<NT>(s, r.visible, grp);
         float lm[NT];
         lane_maxima<NT>(s, P.scale_log2e, lm);
         if (__any(outgrown<NT>(lm, st))) raise_reference<NT>(lm, st);
@@ -474,15 +509,15 @@ __device__ void run_stream(const PacParams &P, const DevTask &t, int head, char 
     const int nblk = (t.kv_len + 31) >> 5;
     BlockRegs ra, rb;
     int tb = wave;
-    if (tb < nblk) load_block<ONCE>(c, tb, koff, voff, ra);
+    if (tb < nblk) load_block<ONCE>(c, tb, koff, voff, ra, masked, mask_row);
     while (tb < nblk) {
         int nb = tb + W;
-        if (nb < nblk) load_block<ONCE>(c, nb, koff, voff, rb);
+        if (nb < nblk) load_block<ONCE>(c, nb, koff, voff, rb, masked, mask_row);
         compute(tb, ra);
         tb = nb;
         if (tb >= nblk) break;
         nb = tb + W;
-        if (nb < nblk) load_block<ONCE>(c, nb, koff, voff, ra);
+        if (nb < nblk) load_block<ONCE>(c, nb, koff, voff, ra, masked, mask_row);
         compute(tb, rb);
         tb = nb;
     }
@@ -1248,7 +1283,7 @@ __global__ void __launch_bounds__(WIDE ? kWideWaves * 64 : kNarrowWaves * 64, 2)
                     k = __builtin_amdgcn_readfirstlane(k);
                     if (k >= n) break;
                     const DevTask mine = recs[i + k];
-                    if (mine.read_once) run_stream<DT, true, 1, 1>(P, mine, head, lds, 0);
+                    if (mine.flags & kTaskReadOnce) run_stream<DT, true, 1, 1>(P, mine, head, lds, 0);
                     else                run_stream<DT, false, 1, 1>(P, mine, head, lds, 0);
                     if (P.arrive) task_delivered_by_wave<DT>(P, mine, head);
                 }
@@ -1256,7 +1291,7 @@ __global__ void __launch_bounds__(WIDE ? kWideWaves * 64 : kNarrowWaves * 64, 2)
                 i += n;
             } else {
                 if (t.n_req * P.group <= 16) {
-                    if (t.read_once) run_stream<DT, true, 1, W>(P, t, head, lds, wave);
+                    if (t.flags & kTaskReadOnce) run_stream<DT, true, 1, W>(P, t, head, lds, wave);
                     else             run_stream<DT, false, 1, W>(P, t, head, lds, wave);
                 }
                 else if constexpr (WIDE != 0) run_dense32<DT>(P, t, head, lds);

@@ -45,6 +45,10 @@ struct PacParams {
     // the request's rows of that head into merge.out and puts the counter back to zero.
     int32_t *arrive;
     MergeParams merge;
+    // Visibility masks (nullptr: none).  nodeq_mask[e], e an index into node_q: first word in mask_words
+    // of that request's mask over the node, or -1 (the node does not end the request, or no mask).
+    const int32_t *nodeq_mask;
+    const uint32_t *mask_words;
 };
 
 

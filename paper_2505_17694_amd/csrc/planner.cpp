@@ -156,6 +156,9 @@ void build_device_image(PlanData &p)
     L.queue_recs = place(p.queue_tasks.size() * sizeof(DevTask));
     L.counters = place(size_t(p.head.num_kv_heads) * 2 * 4);               // zero: nothing taken, nobody done
     L.arrive = place(size_t(p.head.num_kv_heads) * size_t(p.num_requests) * 4);   // zero: nothing arrived
+    const bool masks = !p.req_mask_off.empty();
+    L.nodeq_mask = place(masks ? p.node_q.size() * 4 : 0);
+    L.mask_words = place(masks ? p.req_mask.size() * 4 : 0);
     // one workgroup may end up last for every request: more query rows than a workgroup reduces in a
     // few rounds make the single launch slower than two (cfg2, 256 rows per KV head: 89 against 26 us)
     if (p.fused == 2)
@@ -173,6 +176,16 @@ void build_device_image(PlanData &p)
     for (const codec_task &t : p.tasks) tokens_read += t.kv_len;
     for (int32_t len : p.node_len) tokens_held += len;
     const bool streaming_plan = 4 * tokens_read <= 5 * tokens_held;
+    // visibility masks: which (node, request) entries carry one (the node ends the request)
+    std::vector<int32_t> nodeq_mask;
+    if (masks) {
+        nodeq_mask.assign(p.node_q.size(), -1);
+        for (int32_t n = 0; n < p.num_nodes; ++n)
+            for (int32_t e = p.node_q_off[n]; e < p.node_q_off[n + 1]; ++e) {
+                const int32_t r = p.node_q[e];
+                if (p.req_node[r] == n && p.req_mask_off[r + 1] > p.req_mask_off[r]) nodeq_mask[e] = p.req_mask_off[r];
+            }
+    }
     auto record = [&](int32_t i) {
         const codec_task &t = p.tasks[i];
         DevTask r{};
@@ -182,7 +195,10 @@ void build_device_image(PlanData &p)
         r.n_req = t.n_req;
         r.part_row_base = t.part_row_base;
         r.solo_run = 0;
-        r.read_once = streaming_plan && readers[t.node] == 1;
+        r.flags = streaming_plan && readers[t.node] == 1 ? kTaskReadOnce : 0;
+        if (masks)
+            for (int32_t e = t.q_off; e < t.q_off + t.n_req; ++e)
+                if (nodeq_mask[e] >= 0) r.flags |= kTaskMasked;
         r.single_req = t.n_req == 1 ? p.node_q[t.q_off] : -1;
         return r;
     };
@@ -215,6 +231,10 @@ void build_device_image(PlanData &p)
         }
     }
     put(L.queue_off, p.queue_off);
+    if (masks) {
+        put(L.nodeq_mask, nodeq_mask);
+        if (!p.req_mask.empty()) std::memcpy(p.blob.data() + L.mask_words, p.req_mask.data(), p.req_mask.size() * 4);
+    }
 }
 
 }  // namespace
@@ -339,6 +359,26 @@ int build_plan(const codec_tree &tree, const codec_head_config &head,
     }
     for (int32_t r = 0; r < B; ++r)
         if (tree.req_node[r] < 0 || tree.req_node[r] >= N) return CODEC_ERR_INVALID_TREE;
+    // visibility masks over the requests' last nodes (Sec. 4.1)
+    std::vector<uint8_t> ends_masked(N, 0);         // the node is the last node of a masked request
+    if (tree.req_mask_off) {
+        if (group > kSoloMaxRows) return CODEC_ERR_UNSUPPORTED;
+        if (tree.req_mask_off[0] != 0) return CODEC_ERR_INVALID_TREE;
+        for (int32_t r = 0; r < B; ++r) {
+            const int64_t words = int64_t(tree.req_mask_off[r + 1]) - tree.req_mask_off[r];
+            if (words == 0) continue;
+            const int32_t len = tree.node_len[tree.req_node[r]];
+            if (words != ceil_div(len, 32) || !tree.req_mask) return CODEC_ERR_INVALID_TREE;
+            bool sees = false;
+            for (int32_t t = 0; t < len && !sees; ++t)
+                sees = (tree.req_mask[tree.req_mask_off[r] + t / 32] >> (t % 32)) & 1u;
+            if (!sees) return CODEC_ERR_INVALID_TREE;
+            ends_masked[tree.req_node[r]] = 1;
+        }
+        p.req_mask_off.assign(tree.req_mask_off, tree.req_mask_off + B + 1);
+        if (tree.req_mask_off[B] > 0) p.req_mask.assign(tree.req_mask, tree.req_mask + tree.req_mask_off[B]);
+    }
+    p.req_node.assign(tree.req_node, tree.req_node + B);
 
     p.head = head;
     p.group = group;
@@ -371,10 +411,15 @@ int build_plan(const codec_tree &tree, const codec_head_config &head,
     }
 
     // ---- work items: a node with (a row tile of) its queries -------------------------------
-    const int32_t qpt = p.share ? std::max(1, max_rows / group) : 1;
+    // requests per work item: row tiles of max_rows; a node that ends a masked request takes tiles of at
+    // most 16 rows (the task shape that applies masks) and is not divided along KV
+    std::vector<int32_t> qpt_of(N, p.share ? std::max(1, max_rows / group) : 1);
+    for (int32_t n = 0; n < N; ++n)
+        if (ends_masked[n]) qpt_of[n] = std::min(qpt_of[n], std::max(1, kSoloMaxRows / group));
     std::vector<int32_t> first_item(N, 0);
     for (int32_t n = 0; n < N; ++n) {
         first_item[n] = int32_t(p.items.size());
+        const int32_t qpt = qpt_of[n];
         for (int32_t a = 0; a < n_q[n]; a += qpt) {
             codec_item it{};
             it.node = n;
@@ -397,7 +442,7 @@ int build_plan(const codec_tree &tree, const codec_head_config &head,
     p.table = *table;
     for (codec_item &it : p.items) it.cost = table->estimate(it.rows, it.len);       // a2: Eq. 6
     std::vector<int64_t> max_b(J);
-    for (size_t j = 0; j < J; ++j) max_b[j] = ceil_div(p.items[j].len, align);
+    for (size_t j = 0; j < J; ++j) max_b[j] = ends_masked[p.items[j].node] ? 1 : ceil_div(p.items[j].len, align);
 
     auto slices_at = [&](size_t j, int64_t T) {
         return std::min(ceil_div(p.items[j].cost, T), max_b[j]);
@@ -558,6 +603,7 @@ int build_plan(const codec_tree &tree, const codec_head_config &head,
             const int32_t *lo = p.node_q.data() + p.node_q_off[n];
             const int32_t *hi = p.node_q.data() + p.node_q_off[n + 1];
             const int32_t qi = int32_t(std::lower_bound(lo, hi, r) - lo);
+            const int32_t qpt = qpt_of[n];
             const int32_t j = first_item[n] + qi / qpt;
             for (int32_t c = 0; c < p.items[j].b; ++c)
                 p.req_part.push_back(p.tasks[first_task[j] + c].part_row_base + (qi % qpt) * group);
@@ -624,6 +670,9 @@ int refresh_plan(PlanData &p, const int32_t *node_len, const int32_t *node_page_
     if (node_page_off[N] > 0 && !page_ids) return CODEC_ERR_INVALID_ARGUMENT;
     for (int32_t i = node_page_off[0]; i < node_page_off[N]; ++i)
         if (page_ids[i] < 0) return CODEC_ERR_INVALID_TREE;
+    for (int32_t r = 0; r < p.num_requests && !p.req_mask_off.empty(); ++r)
+        if (p.req_mask_off[r + 1] > p.req_mask_off[r] && node_len[p.req_node[r]] != p.node_len[p.req_node[r]])
+            return CODEC_ERR_INVALID_ARGUMENT;          // a mask covers the tokens the node had at plan time
     std::vector<int32_t> first_task(p.items.size(), -1);
     for (size_t i = 0; i < p.tasks.size(); ++i)
         if (first_task[p.tasks[i].item] < 0) first_task[p.tasks[i].item] = int32_t(i);

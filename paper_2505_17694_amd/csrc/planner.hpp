@@ -45,9 +45,12 @@ struct DevTask {
     int32_t n_req;          // requests in the task
     int32_t part_row_base;  // first partial row
     int32_t solo_run;       // number of consecutive single-wave tasks in the slot's list from this one on
-    int32_t read_once;      // 1 = no other task reads this KV slice (its node has a single row tile)
+    int32_t flags;          // kTaskReadOnce: no other task reads this KV slice (its node has a single row
+                            // tile); kTaskMasked: some request of the task has a visibility mask over this node
     int32_t single_req;     // n_req == 1: the request itself (saves the read of node_q); else -1
 };
+
+enum : int32_t { kTaskReadOnce = 1, kTaskMasked = 2 };
 
 // Per request, the reduction kernel reads one 64-byte line: the number of partial rows on the request's
 // path and, if there are at most kInlineParts of them, the rows themselves; longer lists are read
@@ -59,6 +62,8 @@ struct DevLayout {
     size_t slot_recs = 0, slot_off = 0, node_q = 0, page_ids = 0,
            req_part_off = 0, req_part = 0, req_inline = 0, queue_off = 0, queue_recs = 0, counters = 0,
            arrive = 0,      // [h_kv][num_requests] partial results arrived (single-launch mode), zero between launches
+           nodeq_mask = 0,  // per entry of node_q: first word of that request's mask if the node ends the request, else -1
+           mask_words = 0,
            total = 0;
 };
 
@@ -70,6 +75,9 @@ struct PlanData {
 
     std::vector<int32_t> node_len, node_page_off, page_ids;
     std::vector<int32_t> node_q_off, node_q;
+    std::vector<int32_t> req_node;                  // last node of every request
+    std::vector<int32_t> req_mask_off;              // empty: no visibility masks
+    std::vector<uint32_t> req_mask;
     std::vector<codec_item> items;
     std::vector<codec_task> tasks;
     std::vector<int32_t> slot_off, slot_tasks;

@@ -10,7 +10,8 @@ class PlannedAttention:
     """Owns a codec plan plus its device metadata and workspace tensors.
 
     ``forest``/``paged``/``head`` are plain attribute bags (see ``workloads``):
-    forest.parent, forest.node_len, forest.req_node; paged.node_page_off,
+    forest.parent, forest.node_len, forest.req_node (and, optionally, forest.req_mask_off and
+    forest.req_mask: per-request visibility masks); paged.node_page_off,
     paged.page_ids, paged.num_pages and the three strides; head.num_q_heads,
     num_kv_heads, head_dim, dtype, page_size, scale.
     """
@@ -23,7 +24,8 @@ class PlannedAttention:
                                        head.num_q_heads, head.num_kv_heads, head.head_dim,
                                        head.dtype, head.page_size, head.scale,
                                        num_slots, split_align, max_rows, share, cost_table, fixed_slices, schedule,
-                                       extensions, fused)
+                                       extensions, fused,
+                                       getattr(forest, "req_mask_off", None), getattr(forest, "req_mask", None))
         if st != B.CODEC_OK:
             raise B.CodecError(st, "codec_plan_create")
         self.plan = plan
@@ -80,9 +82,10 @@ class PlannedAttention:
         """q and out are dense [num_requests][num_q_heads][head_dim] tensors of the plan's dtype on its device."""
         h = self.head
         want = (self.num_requests, h.num_q_heads, h.head_dim)
-        if (tuple(t.shape) != want or t.dtype != h.torch_dtype or t.device != self.device
+        dtype = torch.float16 if h.dtype == B.CODEC_DTYPE_FP16 else torch.bfloat16
+        if (tuple(t.shape) != want or t.dtype != dtype or t.device != self.device
                 or not t.is_contiguous()):
-            raise ValueError(f"{what}: need a contiguous {h.torch_dtype} tensor of shape {want} on {self.device}, "
+            raise ValueError(f"{what}: need a contiguous {dtype} tensor of shape {want} on {self.device}, "
                              f"got {t.dtype} {tuple(t.shape)} on {t.device}, contiguous={t.is_contiguous()}")
 
     def decode(self, q: torch.Tensor, k_pool: torch.Tensor, v_pool: torch.Tensor,

@@ -14,7 +14,8 @@ import torch
 from oracle import attention as A
 from workloads import (HeadConfig, Forest, make_workload, make_small_config, make_config,
                        two_level_forest, three_level_forest, unshared_forest, random_forest,
-                       concat_forests, degenerate_forest, draft_tree_forest, DTYPE_FP16, DTYPE_BF16)
+                       concat_forests, degenerate_forest, draft_tree_forest, draft_masked_forest,
+                       DTYPE_FP16, DTYPE_BF16)
 
 pytestmark = pytest.mark.gpu
 
@@ -354,6 +355,47 @@ def test_drafted_token_trees(drafted, hq, hkv, share, schedule):
     assert f.num_requests == 4 * (drafted + 1)
     w = make_workload(f"drafted{drafted}", f, HeadConfig(hq, hkv, 128, DTYPE_BF16), seed=71 + drafted, poison=True)
     check(w, share=share, schedule=schedule)
+
+
+@pytest.mark.parametrize("drafted,hq,hkv,opts", [
+    (1, 8, 2, {}), (7, 32, 8, {}), (24, 32, 8, {"schedule": 1}), (24, 8, 8, {"share": 2}),
+    (40, 16, 1, {"fused": 1}), (33, 32, 8, {"share": 0}), (64, 32, 8, {"extensions": 3}),
+    (70, 12, 4, {"num_slots": 3, "split_align": 32}), (100, 16, 4, {"schedule": 1, "fused": 1})])
+def test_masked_draft_nodes(drafted, hq, hkv, opts):
+    """Multi-token decoding with visibility masks (Sec. 4.1): the drafted tokens of a sequence sit in one
+    node, every drafted token's query ends there and sees itself and the drafted tokens before it on
+    its branch.  1 .. 100 drafted tokens: one to four mask words per query, partly filled last words,
+    row tiles of one to sixteen requests, tasks run by a wave alone and by the workgroup."""
+    f = draft_masked_forest(300, [900, 33, 2100, 260], drafted, seed=170 + drafted)
+    assert f.num_requests == 4 * (drafted + 1)
+    dtype = DTYPE_BF16 if drafted % 2 else DTYPE_FP16
+    w = make_workload(f"masked{drafted}", f, HeadConfig(hq, hkv, 128, dtype), seed=171 + drafted, poison=True)
+    _, view = check(w, **opts)
+    ends = {int(f.req_node[r]) for r in range(f.num_requests) if f.visible(r) is not None}
+    assert all(it["rows"] <= 16 and it["b"] == 1 for it in view["items"] if it["node"] in ends)
+
+
+def test_masks_that_hide_whole_blocks_and_long_masked_nodes():
+    """A masked node of 700 tokens (22 blocks), queries that see a single token each, at the front, in the
+    middle, at the very end: whole 32-token blocks with nothing visible, before and after the first
+    visible one; a query whose mask is all ones; a request without a mask ending at the same node."""
+    n = 700
+    words = (n + 31) // 32
+    picks = [[0], [699], [350], [31, 32], [5, 690], list(range(n)), [64 + i for i in range(40)]]
+    masks = []
+    for vis in picks:
+        m = [0] * words
+        for t in vis:
+            m[t // 32] |= 1 << (t % 32)
+        masks.append(m)
+    masks.append([])                                        # the last request sees the whole node
+    off = np.zeros(len(masks) + 1, dtype=np.int32)
+    np.cumsum([len(m) for m in masks], out=off[1:])
+    f = Forest(np.array([-1, 0]), np.array([90, n]), np.full(len(masks), 1), off,
+               np.array([x for m in masks for x in m], dtype=np.uint32))
+    w = make_workload("sparse-masks", f, HeadConfig(8, 4, 128, DTYPE_BF16), seed=77, poison=True)
+    check(w)
+    check(w, num_slots=1, schedule=1)
 
 
 @pytest.mark.parametrize("slices", [1, 6, 7, 8, 14, 15, 16, 23, 40])

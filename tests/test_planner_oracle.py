@@ -431,3 +431,27 @@ def test_diagonal_of_the_grid_hand_worked():
     assert p["makespan"] == 300 and len(p["tasks"]) == 8
     assert sorted(t["kv_len"] for t in p["tasks"]) == [300] * 8
 
+
+
+def test_cpu_replay_with_visibility_masks_equals_the_definition():
+    """Plan a forest whose drafted-token nodes carry masks, run the emitted tasks on the CPU (Alg. 2 with
+    the mask of Sec. 4.1 per task, Alg. 3 per request): the definition oracle's output.  Masked nodes get
+    row tiles of at most 16 rows and are never divided."""
+    from workloads import draft_masked_forest
+    f = draft_masked_forest(90, [130, 40, 333], 21, seed=6)
+    head = HeadConfig(8, 2, 16, DTYPE_BF16, page_size=16)
+    w = make_workload("replay-masked", f, head, seed=78, poison=True)
+    table = {"row_grid": [1, 64], "len_grid": [16, 256], "cost": [[20, 100], [40, 300]]}
+    masked = {int(f.req_node[r]) for r in range(f.num_requests) if f.visible(r) is not None}
+    p = P.plan(f.parent, f.node_len, f.req_node, head.group, 40, 16, 64, True, table, masked_nodes=masked)
+    assert any(it["b"] > 1 for it in p["items"])
+    for it in p["items"]:
+        if it["node"] in masked:
+            assert it["rows"] <= 16 and it["b"] == 1 and it["ub"] == 1
+    tasks = [(t["node"], t["kv_begin"], t["kv_len"], t["q_off"], t["n_req"], t["part_row_base"])
+             for t in p["tasks"]]
+    got = M.replay_tasks(w, tasks, p["node_q"], p["req_part_off"], p["req_part"])
+    ref, _ = A.decode_attention_workload(w)
+    assert np.max(np.abs(got - ref)) < 1e-13
+    p["table"] = table
+    _check_invariants(f, p, head.group, 40, 16)

@@ -13,7 +13,7 @@ import paper_2505_17694_amd as C
 from oracle import planner as P
 from golden_tables import load_table2
 from workloads import (two_level_forest, three_level_forest, random_forest, unshared_forest,
-                       concat_forests, degenerate_forest, full_kary_forest, draft_tree_forest, Forest,
+                       concat_forests, degenerate_forest, full_kary_forest, draft_tree_forest, draft_masked_forest, Forest,
                        HeadConfig, build_paged_kv)
 from workloads.configs import config_forest, config_head, CONFIG_NAMES
 
@@ -404,3 +404,77 @@ def test_single_launch_option():
                                        head.num_q_heads, head.num_kv_heads, head.head_dim, head.dtype,
                                        head.page_size, head.scale, fused=bad)
         assert st == C.CODEC_ERR_INVALID_ARGUMENT and plan is None
+
+
+# ---- visibility masks (multi-token decoding) ------------------------------------------------------
+
+def _masked_nodes(f):
+    return {int(f.req_node[r]) for r in range(f.num_requests) if f.req_mask_off[r + 1] > f.req_mask_off[r]}
+
+
+@pytest.mark.parametrize("share", [1, 0])
+@pytest.mark.parametrize("hq,hkv,drafted", [(32, 8, 64), (8, 8, 5), (16, 1, 33), (12, 4, 40)])
+def test_plans_with_visibility_masks_match_oracle(share, hq, hkv, drafted):
+    """A node that ends masked requests gets row tiles of at most 16 rows and stays whole; everything
+    else is planned as ever.  Bit-exact against the re-derivation, for the printed solver and both extensions."""
+    f = draft_masked_forest(700, [3000, 45, 1200, 9000], drafted, seed=4)
+    head = HeadConfig(hq, hkv, 128)
+    paged = build_paged_kv(f, head, seed=1)
+    for ext in (0, 3):
+        st, plan = C.codec_plan_create(f.parent, f.node_len, f.req_node, paged.node_page_off, paged.page_ids,
+                                       hq, hkv, 128, head.dtype, head.page_size, head.scale, 16, 64, 0, share,
+                                       extensions=ext, req_mask_off=f.req_mask_off, req_mask=f.req_mask)
+        assert st == C.CODEC_OK, C.codec_status_string(st)
+        st, view = C.codec_plan_export(plan)
+        C.codec_plan_destroy(plan)
+        wide = max(it["rows"] for it in view["items"]) > 16
+        ref = P.plan(f.parent, f.node_len, f.req_node, head.group, 16, 64, 256, bool(share), _default_table(wide),
+                     slack=bool(ext & 1), diagonal=bool(ext & 2), masked_nodes=_masked_nodes(f))
+        _compare(view, ref)
+        for it in view["items"]:
+            if it["node"] in _masked_nodes(f):
+                assert it["rows"] <= 16 and it["b"] == 1
+
+
+def test_malformed_masks_are_rejected():
+    f = draft_masked_forest(0, [100], 40, seed=2)          # two words per drafted request
+    head = HeadConfig(8, 2, 128)
+    paged = build_paged_kv(f, head, seed=1)
+
+    def create(off, words, hq=8, hkv=2):
+        return C.codec_plan_create(f.parent, f.node_len, f.req_node, paged.node_page_off, paged.page_ids,
+                                   hq, hkv, 128, head.dtype, head.page_size, head.scale,
+                                   req_mask_off=off, req_mask=words)[0]
+    assert create(f.req_mask_off, f.req_mask) == C.CODEC_OK
+    short = f.req_mask_off.copy()
+    short[2:] -= 1                                           # request 1 is left with one word for 40 tokens
+    assert create(short, f.req_mask[1:]) == C.CODEC_ERR_INVALID_TREE
+    blind = f.req_mask.copy()
+    blind[0:2] = 0                                           # request 1 sees none of its node's tokens
+    assert create(f.req_mask_off, blind) == C.CODEC_ERR_INVALID_TREE
+    beyond = f.req_mask.copy()
+    beyond[0:2] = [0, 1 << 20]                               # only a bit past the node's 40 tokens is set
+    assert create(f.req_mask_off, beyond) == C.CODEC_ERR_INVALID_TREE
+    shifted = f.req_mask_off + 1
+    assert create(shifted, np.concatenate([[0], f.req_mask])) == C.CODEC_ERR_INVALID_TREE
+    assert create(f.req_mask_off, f.req_mask, hq=64, hkv=2) == C.CODEC_ERR_UNSUPPORTED      # group 32 > 16
+
+
+def test_refresh_keeps_masked_nodes_as_they_are():
+    f = draft_masked_forest(0, [100, 60], 8, seed=2)
+    head = HeadConfig(8, 2, 128)
+    paged = build_paged_kv(f, head, seed=1)
+    st, plan = C.codec_plan_create(f.parent, f.node_len, f.req_node, paged.node_page_off, paged.page_ids,
+                                   8, 2, 128, head.dtype, head.page_size, head.scale,
+                                   req_mask_off=f.req_mask_off, req_mask=f.req_mask)
+    assert st == C.CODEC_OK
+    grown = f.node_len.copy()
+    grown[0] += 5                                            # a context grows: fine
+    g = Forest(f.parent, grown, f.req_node)
+    gp = build_paged_kv(g, head, seed=1)
+    assert C.codec_plan_refresh_lengths(plan, grown, gp.node_page_off, gp.page_ids) == C.CODEC_OK
+    grown[1] += 1                                            # a drafted-token node grows: its masks no longer fit
+    g = Forest(f.parent, grown, f.req_node)
+    gp = build_paged_kv(g, head, seed=1)
+    assert C.codec_plan_refresh_lengths(plan, grown, gp.node_page_off, gp.page_ids) == C.CODEC_ERR_INVALID_ARGUMENT
+    C.codec_plan_destroy(plan)

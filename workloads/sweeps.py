@@ -16,16 +16,18 @@ Forests only; tensors come from ``make_workload`` like every other input.  Each 
                under a shared 2048-token prompt, each with a random tree of 0 .. 64 one-token draft nodes
                and one request per draft token; not one of the paper's sweeps, its motivation names the
                use case
+* ``draft_masked``  the same verification steps with the drafted tokens of a sequence packed into one
+               node and a visibility mask per query (Sec. 4.1) in place of the one-token nodes
 """
 from __future__ import annotations
 
 from typing import List, Tuple
 
 from .trees import (Forest, two_level_forest, full_kary_forest, degenerate_forest, unshared_forest,
-                    draft_tree_forest)
+                    draft_tree_forest, draft_masked_forest)
 from .tensors import HeadConfig, DTYPE_BF16
 
-SWEEP_NAMES = ["seqlen", "batch", "depth", "ratio", "shape", "ablation", "draft"]
+SWEEP_NAMES = ["seqlen", "batch", "depth", "ratio", "shape", "ablation", "draft", "draft_masked"]
 SWEEP_SEED = 2000
 
 
@@ -66,4 +68,6 @@ def sweep_points(name: str) -> List[Tuple[str, Forest]]:
         # verification of drafted token trees (the speculative-decoding use of prefix sharing named
         # in the motivation): 16 sequences of 8192 tokens under a prompt of 2048
         return [(f"drafted={t}", draft_tree_forest(2048, [8192] * 16, t, SWEEP_SEED + t)) for t in (0, 4, 16, 64)]
+    if name == "draft_masked":
+        return [(f"drafted={t}", draft_masked_forest(2048, [8192] * 16, t, SWEEP_SEED + t)) for t in (0, 4, 16, 64)]
     raise KeyError(name)
