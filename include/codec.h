@@ -36,7 +36,7 @@ enum {
     CODEC_OK = 0,
     CODEC_ERR_INVALID_ARGUMENT = -1,    /* null pointer, non-positive count, bad option        */
     CODEC_ERR_INVALID_TREE = -2,        /* bad parent/req_node index, cycle, empty node, short page list */
-    CODEC_ERR_UNSUPPORTED = -3,         /* head_dim != 128, unknown dtype, page size, group size */
+    CODEC_ERR_UNSUPPORTED = -3,         /* head_dim not 64/128/256, unknown dtype, page size, group size */
     CODEC_ERR_WORKSPACE_TOO_SMALL = -4,
     CODEC_ERR_HIP = -5,                 /* a HIP runtime call failed                           */
     CODEC_ERR_NOT_UPLOADED = -6,        /* decode called before codec_plan_upload              */
@@ -51,7 +51,10 @@ typedef struct codec_plan codec_plan_t;         /* opaque, library-owned, immuta
 typedef struct {
     int32_t num_q_heads;
     int32_t num_kv_heads;       /* must divide num_q_heads; group = ratio, 1..64        */
-    int32_t head_dim;           /* 128                                                  */
+    int32_t head_dim;           /* 128; or 64 or 256, which run in the 16-row task shape
+                                   only: group <= 16, query sets are tiled 16 rows at a
+                                   time (max_rows is capped), so a shared node is read once
+                                   per 16 rows, the repeats from cache                  */
     int32_t dtype;              /* CODEC_DTYPE_*: type of q, K, V and out               */
     int32_t page_size;          /* tokens per KV page, a power of two, 16..4096         */
     float   scale;              /* softmax scale, 1/sqrt(head_dim) in Eq. 1             */
@@ -231,7 +234,7 @@ typedef struct {
 
 /*
  * Layout of the K and V page pools (both pools share it): element (page, slot, kv head, c)
- * lives at page * page_stride + slot * token_stride + kv head * head_stride + c.  The 128
+ * lives at page * page_stride + slot * token_stride + kv head * head_stride + c.  The head_dim
  * elements of a head are contiguous; strides are multiples of 8 elements.  num_pages is
  * the pool size; every page id of the plan must be below it.
  */
@@ -320,9 +323,9 @@ size_t codec_plan_workspace_bytes(const codec_plan_t *plan);
  * One decode-attention step (Alg. 4): partial attention for every scheduled
  * task, then per-query reduction, enqueued on `stream`; returns without
  * synchronising.
- *   q        device [num_requests][num_q_heads][128], dtype of the plan, 16-byte aligned
+ *   q        device [num_requests][num_q_heads][head_dim], dtype of the plan, 16-byte aligned
  *   k_pages, v_pages   device page pools, laid out by `layout`, 16-byte aligned
- *   out      device [num_requests][num_q_heads][128], same dtype
+ *   out      device [num_requests][num_q_heads][head_dim], same dtype
  *   workspace  device scratch, >= codec_plan_workspace_bytes, 256-byte aligned;
  *              contents are overwritten; calls sharing a workspace must not overlap
  */

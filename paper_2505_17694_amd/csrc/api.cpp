@@ -34,7 +34,7 @@ size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
 size_t part_o_bytes(const codec::PlanData &d)
 {
-    return align_up(size_t(d.head.num_kv_heads) * size_t(d.part_rows) * 128 * sizeof(float), 256);
+    return align_up(size_t(d.head.num_kv_heads) * size_t(d.part_rows) * size_t(d.head.head_dim) * sizeof(float), 256);
 }
 
 size_t part_ml_bytes(const codec::PlanData &d)
@@ -229,7 +229,7 @@ int partial_attention(const codec_plan_t *plan, const void *q, const void *k_pag
     if (!aligned16(q) || !aligned16(k_pages) || !aligned16(v_pages)) return CODEC_ERR_INVALID_ARGUMENT;
     if (reinterpret_cast<uintptr_t>(workspace) & 255u) return CODEC_ERR_INVALID_ARGUMENT;
     if (layout->num_pages <= plan->max_page_id) return CODEC_ERR_INVALID_ARGUMENT;
-    if (layout->page_stride < 1 || layout->token_stride < 128 || layout->head_stride < 128 ||
+    if (layout->page_stride < 1 || layout->token_stride < d.head.head_dim || layout->head_stride < d.head.head_dim ||
         layout->page_stride % 8 || layout->token_stride % 8 || layout->head_stride % 8)
         return CODEC_ERR_INVALID_ARGUMENT;
     // the kernels keep a page's size in bytes, and every byte offset of a token inside its page, in 32 bits
@@ -276,7 +276,7 @@ int partial_attention(const codec_plan_t *plan, const void *q, const void *k_pag
         pp.merge = merge_params(plan, workspace, fused_out);
         pp.arrive = reinterpret_cast<int32_t *>(const_cast<char *>(meta) + L.arrive);
     }
-    if (int e = codec::launch_pac(pp, d.head.dtype, d.num_slots, plan->max_task_rows, stream))
+    if (int e = codec::launch_pac(pp, d.head.dtype, d.head.head_dim, d.num_slots, plan->max_task_rows, stream))
         return hip_failure("partial attention launch", e);
     return CODEC_OK;
 }
@@ -304,7 +304,7 @@ int codec_partial_reduction(const codec_plan_t *plan, const void *workspace, siz
     if (!aligned16(out) || (reinterpret_cast<uintptr_t>(workspace) & 255u)) return CODEC_ERR_INVALID_ARGUMENT;
 
     const codec::MergeParams mp = merge_params(plan, workspace, out);
-    if (int e = codec::launch_merge(mp, d.head.dtype, stream)) return hip_failure("partial reduction launch", e);
+    if (int e = codec::launch_merge(mp, d.head.dtype, d.head.head_dim, stream)) return hip_failure("partial reduction launch", e);
     return CODEC_OK;
 }
 

@@ -48,12 +48,16 @@ typedef __attribute__((ext_vector_type(8))) _Float16 f16x8;
 typedef __attribute__((ext_vector_type(4))) float f32x4;
 typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;
 
-constexpr int kHeadDim = 128;
+constexpr int kHeadDim = 128;       // the dense path; the stream path and the reduction take the head
+                                    // dimension D (64, 128 or 256) as a template parameter
 constexpr int kNarrowWaves = 4;     // stream-only kernel variant: 4 waves, two workgroups per CU
 constexpr int kWideWaves = 8;       // all task shapes: 8 waves (two per SIMD), one workgroup per CU
 constexpr int kMergeWaves = 4;      // reduction kernel
+// Channel tiles of 16 that a stream task accumulates: 8 per 128 channels (with 64 channels half of each
+// tile's rows are idle, see BlockRegs).
+constexpr int channel_tiles(int d) { return d <= 128 ? 8 : d / 16; }
 // LDS for merging the waves' states at the end of a stream task: W/2 states of NT row tiles
-constexpr int merge_bytes(int waves, int nt) { return (waves / 2) * (nt * 8 * 64 * 4 + nt * 64 * 2) * 4; }
+constexpr int merge_bytes(int waves, int nt, int d) { return (waves / 2) * (nt * channel_tiles(d) * 64 * 4 + nt * 64 * 2) * 4; }
 
 template <int DT>
 __device__ __forceinline__ f32x4 mfma16(u32x4 a, u32x4 b, f32x4 c)
@@ -175,17 +179,22 @@ __device__ __forceinline__ int64_t page_offset(const SliceCtx &c, int pg, int sl
     return int64_t(uint64_t(uint32_t(pg)) * c.page_bytes + uint64_t(uint32_t(slot) * c.token_bytes));
 }
 
-// K and V registers of one 32-token block (stream path).
+// K and V registers of one 32-token block (stream path), head dimension D.
+template <int D>
 struct BlockRegs {
-    u32x4 k[2][4];      // [tile][k-step]: token = tile*16 + lane%16, channels 32*ks + 8*(lane/16)..+7
-    u32x4 v[8];         // [e]: token = (e/4)*16 + 4*(lane/16) + e%4, channels 8*(lane%16)..+7
+    static constexpr int KS = D / 32;                   // k-steps of the scores
+    static constexpr int VU = D <= 128 ? 1 : D / 128;   // 16-byte V pieces per token and lane
+    u32x4 k[2][KS];     // [tile][k-step]: token = tile*16 + lane%16, channels 32*ks + 8*(lane/16)..+7
+    u32x4 v[8][VU];     // [e][u]: token = (e/4)*16 + 4*(lane/16) + e%4, channels 128*u + 8*(lane%16)..+7;
+                        // D = 64: lanes 8..15 repeat the pieces of lanes 0..7 (their rows of the
+                        // accumulated tiles stand for channels that do not exist and are never stored)
     uint32_t visible;   // masked tasks: bit t = the lane's row sees token t of the block
 };
 
 // Issue the loads of block `tb`.  A tile that starts beyond the slice is redirected to tile 0 so that
 // no address leaves the slice's pages; its scores are masked later.  ONCE: with the streaming hint.
-template <bool ONCE>
-__device__ __forceinline__ void load_block(const SliceCtx &c, int tb, uint32_t koff, uint32_t voff, BlockRegs &r,
+template <bool ONCE, int D>
+__device__ __forceinline__ void load_block(const SliceCtx &c, int tb, uint32_t koff, uint32_t voff, BlockRegs<D> &r,
                                            bool masked, const uint32_t *mask_row)
 {
     // the word of the row's visibility mask for this block (a slice with masks starts at token 0 of its
@@ -204,12 +213,15 @@ __device__ __forceinline__ void load_block(const SliceCtx &c, int tb, uint32_t k
         const char *kt = c.k_head + off;
         const char *vt = c.v_head + off;
 #pragma unroll
-        for (int ks = 0; ks < 4; ++ks) r.k[j][ks] = ONCE ? ld16_once(kt + koff + ks * 64) : ld16(kt + koff + ks * 64);
+        for (int ks = 0; ks < BlockRegs<D>::KS; ++ks)
+            r.k[j][ks] = ONCE ? ld16_once(kt + koff + ks * 64) : ld16(kt + koff + ks * 64);
 #pragma unroll
-        for (int e = 0; e < 4; ++e) {
-            const char *p = vt + size_t(e) * c.token_bytes + voff;
-            r.v[j * 4 + e] = ONCE ? ld16_once(p) : ld16(p);
-        }
+        for (int e = 0; e < 4; ++e)
+#pragma unroll
+            for (int u = 0; u < BlockRegs<D>::VU; ++u) {
+                const char *p = vt + size_t(e) * c.token_bytes + voff + u * 256;
+                r.v[j * 4 + e][u] = ONCE ? ld16_once(p) : ld16(p);
+            }
     }
 }
 
@@ -218,10 +230,11 @@ __device__ __forceinline__ void load_block(const SliceCtx &c, int tb, uint32_t k
 // first finite score raises the reference and wipes (multiplies by exp2 of -1e30) whatever it scaled.
 constexpr float kNoReference = -1e30f;
 
-template <int NT>
+template <int NT, int D>
 struct RowState {
-    f32x4 o[NT][8];     // [row tile][dt]: row = 16*nt + lane%16; channel of component e is
-                        // 32*(lane/16) + 8*e + dt
+    static constexpr int CT = channel_tiles(D);
+    f32x4 o[NT][CT];    // [row tile][dt]: row = 16*nt + lane%16; channel of component e is
+                        // 128*(dt/8) + 32*(lane/16) + 8*e + dt%8
     float m[NT];        // reference subtracted before exponentiation, log2 units (same in the 4 lanes
                         // that share a row); kNoReference until the row has seen a score above -inf
     float l[NT];        // the lane's share of the row sum; the row sum after finish()
@@ -233,7 +246,7 @@ struct RowState {
             m[nt] = kNoReference;
             l[nt] = 0.f;
 #pragma unroll
-            for (int dt = 0; dt < 8; ++dt) o[nt][dt] = f32x4{0.f, 0.f, 0.f, 0.f};
+            for (int dt = 0; dt < CT; ++dt) o[nt][dt] = f32x4{0.f, 0.f, 0.f, 0.f};
         }
     }
     // each lane summed its own 8 tokens per block: the four lanes of a row are added up
@@ -287,13 +300,16 @@ __device__ __forceinline__ void mask_invisible(f32x4 (&s)[2][NT], uint32_t visib
 }
 
 // V rows of tokens past `valid` count as zero (their memory may hold anything).
-__device__ __forceinline__ void mask_values(u32x4 (&v)[8], int valid, int grp)
+template <int VU>
+__device__ __forceinline__ void mask_values(u32x4 (&v)[8][VU], int valid, int grp)
 {
 #pragma unroll
     for (int e = 0; e < 8; ++e) {
         const bool dead = (e >> 2) * 16 + grp * 4 + (e & 3) >= valid;
 #pragma unroll
-        for (int c = 0; c < 4; ++c) v[e][c] = dead ? 0u : v[e][c];
+        for (int u = 0; u < VU; ++u)
+#pragma unroll
+            for (int c = 0; c < 4; ++c) v[e][u][c] = dead ? 0u : v[e][u][c];
     }
 }
 
@@ -310,8 +326,8 @@ __device__ __forceinline__ void lane_maxima(const f32x4 (&s)[2][NT], float scale
     }
 }
 
-template <int NT>
-__device__ __forceinline__ bool outgrown(const float (&lm)[NT], const RowState<NT> &st)
+template <int NT, int D>
+__device__ __forceinline__ bool outgrown(const float (&lm)[NT], const RowState<NT, D> &st)
 {
     bool any = false;
 #pragma unroll
@@ -320,8 +336,8 @@ __device__ __forceinline__ bool outgrown(const float (&lm)[NT], const RowState<N
 }
 
 // Move every row's reference up to its true running maximum and rescale its accumulators.
-template <int NT>
-__device__ __forceinline__ void raise_reference(const float (&lm)[NT], RowState<NT> &st)
+template <int NT, int D>
+__device__ __forceinline__ void raise_reference(const float (&lm)[NT], RowState<NT, D> &st)
 {
 #pragma unroll
     for (int nt = 0; nt < NT; ++nt) {
@@ -332,15 +348,15 @@ __device__ __forceinline__ void raise_reference(const float (&lm)[NT], RowState<
         const float alpha = fast_exp2(st.m[nt] - m_new);       // 0 on the first block (m = -inf)
         st.l[nt] *= alpha;
 #pragma unroll
-        for (int dt = 0; dt < 8; ++dt) st.o[nt][dt] *= alpha;
+        for (int dt = 0; dt < RowState<NT, D>::CT; ++dt) st.o[nt][dt] *= alpha;
         st.m[nt] = m_new;
     }
 }
 
 // P = exp2(scale * S - m), rounded to 16 bits in B-operand layout; the lane adds its 8 exponentials to
 // its share of the row sum.
-template <int DT, int NT>
-__device__ __forceinline__ void probabilities(const f32x4 (&s)[2][NT], RowState<NT> &st,
+template <int DT, int NT, int D>
+__device__ __forceinline__ void probabilities(const f32x4 (&s)[2][NT], RowState<NT, D> &st,
                                               float scale_log2e, u32x4 (&pb)[NT])
 {
 #pragma unroll
@@ -357,16 +373,16 @@ __device__ __forceinline__ void probabilities(const f32x4 (&s)[2][NT], RowState<
     }
 }
 
-// O^T += V^T P^T for the channel tiles dt = 4*HALF .. 4*HALF+3.  `vh[e]` holds dwords 2*HALF and
-// 2*HALF+1 (channels 4*HALF .. 4*HALF+3 of the lane's 8) of token e's V row piece; the 16-bit
+// O^T += V^T P^T for the channel tiles dt = 8*U + 4*HALF .. +3.  `vh[e]` holds dwords 2*HALF and
+// 2*HALF+1 (channels 4*HALF .. 4*HALF+3 of the lane's 8) of token e's V row piece U; the 16-bit
 // transpose inside each lane turns them into A operands.
-template <int DT, int NT, int HALF>
+template <int DT, int NT, int D, int U, int HALF>
 __device__ __forceinline__ void accumulate_half(const unsigned int (&vh)[8][2], const u32x4 (&pb)[NT],
-                                                RowState<NT> &st)
+                                                RowState<NT, D> &st)
 {
 #pragma unroll
     for (int d = 0; d < 4; ++d) {
-        const int dt = 4 * HALF + d;
+        const int dt = 8 * U + 4 * HALF + d;
         const unsigned int sel = (d & 1) ? 0x07060302u : 0x05040100u;
         u32x4 va;
 #pragma unroll
@@ -377,24 +393,33 @@ __device__ __forceinline__ void accumulate_half(const unsigned int (&vh)[8][2], 
     }
 }
 
-// Same for a whole V row piece per token (16 bytes each) held in registers.
-template <int DT, int NT>
-__device__ __forceinline__ void accumulate(const u32x4 (&v)[8], const u32x4 (&pb)[NT], RowState<NT> &st)
+// Same for V row piece U of every token (16 bytes each) held in registers.
+template <int DT, int NT, int D, int U>
+__device__ __forceinline__ void accumulate_piece(const u32x4 (&v)[8][BlockRegs<D>::VU], const u32x4 (&pb)[NT],
+                                                 RowState<NT, D> &st)
 {
     unsigned int lo[8][2], hi[8][2];
 #pragma unroll
     for (int e = 0; e < 8; ++e) {
-        lo[e][0] = v[e][0]; lo[e][1] = v[e][1];
-        hi[e][0] = v[e][2]; hi[e][1] = v[e][3];
+        lo[e][0] = v[e][U][0]; lo[e][1] = v[e][U][1];
+        hi[e][0] = v[e][U][2]; hi[e][1] = v[e][U][3];
     }
-    accumulate_half<DT, NT, 0>(lo, pb, st);
-    accumulate_half<DT, NT, 1>(hi, pb, st);
+    accumulate_half<DT, NT, D, U, 0>(lo, pb, st);
+    accumulate_half<DT, NT, D, U, 1>(hi, pb, st);
+}
+template <int DT, int NT, int D>
+__device__ __forceinline__ void accumulate(const u32x4 (&v)[8][BlockRegs<D>::VU], const u32x4 (&pb)[NT],
+                                           RowState<NT, D> &st)
+{
+    accumulate_piece<DT, NT, D, 0>(v, pb, st);
+    if constexpr (BlockRegs<D>::VU > 1) accumulate_piece<DT, NT, D, 1>(v, pb, st);
+    static_assert(BlockRegs<D>::VU <= 2, "head dimensions up to 256");
 }
 
 // Gather the wave's query rows (task rows row0 .. row0 + 16*NT) into B-operand registers.
-template <int NT>
+template <int NT, int D>
 __device__ __forceinline__ void gather_q(const PacParams &P, const DevTask &t, int head, int row0, int rows,
-                                         int l16, int grp, u32x4 (&qb)[NT][4])
+                                         int l16, int grp, u32x4 (&qb)[NT][D / 32])
 {
 #pragma unroll
     for (int nt = 0; nt < NT; ++nt) {
@@ -404,30 +429,33 @@ __device__ __forceinline__ void gather_q(const PacParams &P, const DevTask &t, i
         const int hj = live ? row - qi * P.group : 0;
         const int req = t.single_req >= 0 ? t.single_req : P.node_q[t.q_off + qi];
         const char *qp = static_cast<const char *>(P.q)
-                         + (int64_t(req) * P.h_q + int64_t(head) * P.group + hj) * (kHeadDim * 2) + grp * 16;
+                         + (int64_t(req) * P.h_q + int64_t(head) * P.group + hj) * (D * 2) + grp * 16;
 #pragma unroll
-        for (int ks = 0; ks < 4; ++ks) qb[nt][ks] = live ? ld16(qp + ks * 64) : u32x4{0u, 0u, 0u, 0u};
+        for (int ks = 0; ks < D / 32; ++ks) qb[nt][ks] = live ? ld16(qp + ks * 64) : u32x4{0u, 0u, 0u, 0u};
     }
 }
 
 // Write one wave's rows of the partial result: unnormalised output, (reference, sum) per row.
-template <int NT>
+template <int NT, int D>
 __device__ __forceinline__ void store_partial(const PacParams &P, const DevTask &t, int head, int row0, int rows,
-                                              int l16, int grp, const RowState<NT> &st)
+                                              int l16, int grp, const RowState<NT, D> &st)
 {
 #pragma unroll
     for (int nt = 0; nt < NT; ++nt) {
         const int row = row0 + nt * 16 + l16;
         if (row < rows) {
             const int64_t prow = int64_t(head) * P.part_rows + t.part_row_base + row;
-            float *po = P.part_o + prow * kHeadDim + grp * 32;
+            float *po = P.part_o + prow * D + grp * 32;
 #pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                f32x4 lo = {st.o[nt][0][e], st.o[nt][1][e], st.o[nt][2][e], st.o[nt][3][e]};
-                f32x4 hi = {st.o[nt][4][e], st.o[nt][5][e], st.o[nt][6][e], st.o[nt][7][e]};
-                st16_partial(po + e * 8, lo, P.arrive != nullptr);
-                st16_partial(po + e * 8 + 4, hi, P.arrive != nullptr);
-            }
+            for (int u = 0; u < BlockRegs<D>::VU; ++u)
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    if (D < 128 && grp * 32 + e * 8 >= D) continue;     // channels the head does not have
+                    const f32x4 lo = {st.o[nt][8 * u + 0][e], st.o[nt][8 * u + 1][e], st.o[nt][8 * u + 2][e], st.o[nt][8 * u + 3][e]};
+                    const f32x4 hi = {st.o[nt][8 * u + 4][e], st.o[nt][8 * u + 5][e], st.o[nt][8 * u + 6][e], st.o[nt][8 * u + 7][e]};
+                    st16_partial(po + u * 128 + e * 8, lo, P.arrive != nullptr);
+                    st16_partial(po + u * 128 + e * 8 + 4, hi, P.arrive != nullptr);
+                }
             if (grp == 0) st8_partial(P.part_ml + prow * 2, st.m[nt], st.l[nt], P.arrive != nullptr);
         }
     }
@@ -455,18 +483,19 @@ __device__ __forceinline__ float weight(float a, float m) { return a == m ? 1.f 
 // ---- stream path: rows <= 16*NT (NT = 1 in use), a team of W waves splits the tokens ---------------
 // `wave` is the wave's index in its team.  A team of one wave (W = 1) uses no LDS and no barrier, so
 // several such waves may work on different tasks at the same time.
-template <int DT, bool ONCE, int NT, int W>
+template <int DT, bool ONCE, int NT, int W, int D>
 __device__ void run_stream(const PacParams &P, const DevTask &t, int head, char *lds_raw, int wave)
 {
+    constexpr int KS = D / 32, CT = channel_tiles(D);
     const int lane = opaque_lane();
     const int l16 = lane & 15, grp = lane >> 4;
     const int rows = t.n_req * P.group;
 
-    u32x4 qb[NT][4];
-    gather_q<NT>(P, t, head, 0, rows, l16, grp, qb);
+    u32x4 qb[NT][KS];
+    gather_q<NT, D>(P, t, head, 0, rows, l16, grp, qb);
     const SliceCtx c = make_ctx(P, t, head);
     const uint32_t koff = uint32_t(l16) * c.token_bytes + grp * 16;
-    const uint32_t voff = uint32_t(grp * 4) * c.token_bytes + l16 * 16;
+    const uint32_t voff = uint32_t(grp * 4) * c.token_bytes + (D < 128 ? (l16 & (D / 8 - 1)) : l16) * 16;
 
     // visibility mask of the lane's row, if the task has any (masked tasks hold at most 16 rows and are
     // never slices of a node: block tb of the task is word tb of the mask)
@@ -477,10 +506,10 @@ __device__ void run_stream(const PacParams &P, const DevTask &t, int head, char 
         if (off >= 0) mask_row = P.mask_words + off;
     }
 
-    RowState<NT> st;
+    RowState<NT, D> st;
     st.clear();
 
-    auto compute = [&](int tb, BlockRegs &r) {
+    auto compute = [&](int tb, BlockRegs<D> &r) {
         f32x4 s[2][NT];
 #pragma unroll
         for (int j = 0; j < 2; ++j)
@@ -488,36 +517,36 @@ __device__ void run_stream(const PacParams &P, const DevTask &t, int head, char 
             for (int nt = 0; nt < NT; ++nt) {
                 f32x4 acc = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-                for (int ks = 0; ks < 4; ++ks) acc = mfma16<DT>(r.k[j][ks], qb[nt][ks], acc);
+                for (int ks = 0; ks < KS; ++ks) acc = mfma16<DT>(r.k[j][ks], qb[nt][ks], acc);
                 s[j][nt] = acc;
             }
         const int valid = c.kv_len - tb * 32;
         if (valid < 32) {
             mask_scores<NT>(s, valid, grp);
-            mask_values(r.v, valid, grp);
+            mask_values<BlockRegs<D>::VU>(r.v, valid, grp);
         }
         if (masked) mask_invisible<NT>(s, r.visible, grp);
         float lm[NT];
         lane_maxima<NT>(s, P.scale_log2e, lm);
-        if (__any(outgrown<NT>(lm, st))) raise_reference<NT>(lm, st);
+        if (__any(outgrown<NT, D>(lm, st))) raise_reference<NT, D>(lm, st);
         u32x4 pb[NT];
-        probabilities<DT, NT>(s, st, P.scale_log2e, pb);
-        accumulate<DT, NT>(r.v, pb, st);
+        probabilities<DT, NT, D>(s, st, P.scale_log2e, pb);
+        accumulate<DT, NT, D>(r.v, pb, st);
     };
 
     // software pipeline: the loads of the wave's next block are in flight while it computes this one
     const int nblk = (t.kv_len + 31) >> 5;
-    BlockRegs ra, rb;
+    BlockRegs<D> ra, rb;
     int tb = wave;
-    if (tb < nblk) load_block<ONCE>(c, tb, koff, voff, ra, masked, mask_row);
+    if (tb < nblk) load_block<ONCE, D>(c, tb, koff, voff, ra, masked, mask_row);
     while (tb < nblk) {
         int nb = tb + W;
-        if (nb < nblk) load_block<ONCE>(c, nb, koff, voff, rb, masked, mask_row);
+        if (nb < nblk) load_block<ONCE, D>(c, nb, koff, voff, rb, masked, mask_row);
         compute(tb, ra);
         tb = nb;
         if (tb >= nblk) break;
         nb = tb + W;
-        if (nb < nblk) load_block<ONCE>(c, nb, koff, voff, ra, masked, mask_row);
+        if (nb < nblk) load_block<ONCE, D>(c, nb, koff, voff, ra, masked, mask_row);
         compute(tb, rb);
         tb = nb;
     }
@@ -525,19 +554,19 @@ __device__ void run_stream(const PacParams &P, const DevTask &t, int head, char 
     st.finish();
 
     // merge the waves' states pairwise through LDS: waves [h, 2h) hand theirs to waves [0, h), h = W/2 .. 1
-    constexpr int kState = NT * 8 * 64 * 4 + NT * 64 * 2;              // floats per handed-over state
+    constexpr int kState = NT * CT * 64 * 4 + NT * 64 * 2;             // floats per handed-over state
     float *lds = reinterpret_cast<float *>(lds_raw);
 #pragma unroll 1
     for (int h = W / 2; h >= 1; h >>= 1) {
         if (wave >= h && wave < 2 * h) {
             float *base = lds + (wave - h) * kState;
-            f32x4 *lo = reinterpret_cast<f32x4 *>(base);                // [NT][8][64]
+            f32x4 *lo = reinterpret_cast<f32x4 *>(base);                // [NT][CT][64]
 #pragma unroll
             for (int nt = 0; nt < NT; ++nt) {
 #pragma unroll
-                for (int dt = 0; dt < 8; ++dt) lo[(nt * 8 + dt) * 64 + lane] = st.o[nt][dt];
-                base[NT * 8 * 64 * 4 + nt * 64 + lane] = st.m[nt];
-                base[NT * 8 * 64 * 4 + NT * 64 + nt * 64 + lane] = st.l[nt];
+                for (int dt = 0; dt < CT; ++dt) lo[(nt * CT + dt) * 64 + lane] = st.o[nt][dt];
+                base[NT * CT * 64 * 4 + nt * 64 + lane] = st.m[nt];
+                base[NT * CT * 64 * 4 + NT * 64 + nt * 64 + lane] = st.l[nt];
             }
         }
         __syncthreads();
@@ -546,20 +575,20 @@ __device__ void run_stream(const PacParams &P, const DevTask &t, int head, char 
             const f32x4 *lo = reinterpret_cast<const f32x4 *>(base);
 #pragma unroll
             for (int nt = 0; nt < NT; ++nt) {
-                const float m2 = base[NT * 8 * 64 * 4 + nt * 64 + lane];
-                const float l2 = base[NT * 8 * 64 * 4 + NT * 64 + nt * 64 + lane];
+                const float m2 = base[NT * CT * 64 * 4 + nt * 64 + lane];
+                const float l2 = base[NT * CT * 64 * 4 + NT * 64 + nt * 64 + lane];
                 const float mm = fmaxf(st.m[nt], m2);
                 const float a = weight(st.m[nt], mm), b = weight(m2, mm);
                 st.l[nt] = st.l[nt] * a + l2 * b;
                 st.m[nt] = mm;
 #pragma unroll
-                for (int dt = 0; dt < 8; ++dt)
-                    st.o[nt][dt] = st.o[nt][dt] * a + lo[(nt * 8 + dt) * 64 + lane] * b;
+                for (int dt = 0; dt < CT; ++dt)
+                    st.o[nt][dt] = st.o[nt][dt] * a + lo[(nt * CT + dt) * 64 + lane] * b;
             }
         }
         __syncthreads();
     }
-    if (wave == 0) store_partial<NT>(P, t, head, 0, rows, l16, grp, st);
+    if (wave == 0) store_partial<NT, D>(P, t, head, 0, rows, l16, grp, st);
 }
 
 // ---- dense path: 1..256 rows, the 8 waves split the rows (32 each) and share each block ------------
@@ -1095,10 +1124,11 @@ __device__ void run_dense32(const PacParams &P, const DevTask &t, int head, char
 // in list order; each lane owns two channels.  Partials are taken eight or fifteen at a time: their
 // loads are issued together, then they are folded against their common maximum (by associativity of
 // the reduction this equals any binary bracketing).
-template <int DT, bool COHERENT>
+template <int DT, bool COHERENT, int D>
 __device__ __forceinline__ void merge_one(const MergeParams &P, int r, int hq, int lane)
 {
     constexpr int kChunk = 8;
+    constexpr int CPL = D / 64;         // channels per lane: 1, 2 or 4
     const int head = hq / P.group, hj = hq - head * P.group;
     // The request's line: its number of partial rows and the first kInlineParts of them, read together
     // (no address waits for another read).  Lists of up to eight rows, and of up to kInlineParts, are
@@ -1109,19 +1139,43 @@ __device__ __forceinline__ void merge_one(const MergeParams &P, int r, int hq, i
 #pragma unroll
     for (int j = 0; j < kInlineParts; ++j) first[j] = line[1 + j];  // zero behind the end: a valid row
     const int64_t head_base = int64_t(head) * P.part_rows + hj;
-    float M = -INFINITY, L = 0.f, a0 = 0.f, a1 = 0.f;
+    float M = -INFINITY, L = 0.f, acc[CPL];
+#pragma unroll
+    for (int c = 0; c < CPL; ++c) acc[c] = 0.f;
     auto fold = [&](const int *rows, int cnt, auto width) {
         constexpr int N = decltype(width)::value;
-        float2 ml[N], o[N];
+        float2 ml[N];
+        float o[N][CPL];
 #pragma unroll
         for (int j = 0; j < N; ++j) {
             const int64_t prow = head_base + rows[j];
+            const float *src = P.part_o + prow * D + lane * CPL;
             if constexpr (COHERENT) {       // rows written by other workgroups of this launch
                 ml[j] = ld8_device(P.part_ml + prow * 2);
-                o[j] = ld8_device(P.part_o + prow * kHeadDim + lane * 2);
+                if constexpr (CPL == 1) {
+                    o[j][0] = __builtin_bit_cast(float, __hip_atomic_load(reinterpret_cast<const unsigned int *>(src),
+                                                                          __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
+                } else {
+#pragma unroll
+                    for (int c = 0; c < CPL; c += 2) {
+                        const float2 x = ld8_device(src + c);
+                        o[j][c] = x.x;
+                        o[j][c + 1] = x.y;
+                    }
+                }
             } else {
                 ml[j] = *reinterpret_cast<const float2 *>(P.part_ml + prow * 2);
-                o[j] = *reinterpret_cast<const float2 *>(P.part_o + prow * kHeadDim + lane * 2);
+                if constexpr (CPL == 1) {
+                    o[j][0] = *src;
+                } else if constexpr (CPL == 2) {
+                    const float2 x = *reinterpret_cast<const float2 *>(src);
+                    o[j][0] = x.x;
+                    o[j][1] = x.y;
+                } else {
+                    const f32x4 x = *reinterpret_cast<const f32x4 *>(src);
+#pragma unroll
+                    for (int c = 0; c < 4; ++c) o[j][c] = x[c];
+                }
             }
         }
         float mm = M;
@@ -1130,15 +1184,15 @@ __device__ __forceinline__ void merge_one(const MergeParams &P, int r, int hq, i
             if (j < cnt) mm = fmaxf(mm, ml[j].x);
         const float wa = weight(M, mm);
         L *= wa;
-        a0 *= wa;
-        a1 *= wa;
+#pragma unroll
+        for (int c = 0; c < CPL; ++c) acc[c] *= wa;
 #pragma unroll
         for (int j = 0; j < N; ++j)
             if (j < cnt) {
                 const float wb = weight(ml[j].x, mm);
                 L += ml[j].y * wb;
-                a0 += o[j].x * wb;
-                a1 += o[j].y * wb;
+#pragma unroll
+                for (int c = 0; c < CPL; ++c) acc[c] += o[j][c] * wb;
             }
         M = mm;
     };
@@ -1159,17 +1213,23 @@ __device__ __forceinline__ void merge_one(const MergeParams &P, int r, int hq, i
         }
     }
     const float inv = 1.f / L;
-    unsigned int *out = static_cast<unsigned int *>(P.out) + (int64_t(r) * P.h_q + hq) * (kHeadDim / 2) + lane;
-    *out = pack2<DT>(a0 * inv, a1 * inv);
+    char *out = static_cast<char *>(P.out) + ((int64_t(r) * P.h_q + hq) * D + lane * CPL) * 2;
+    if constexpr (CPL == 1) {
+        *reinterpret_cast<unsigned short *>(out) = static_cast<unsigned short>(pack2<DT>(acc[0] * inv, 0.f) & 0xFFFFu);
+    } else {
+#pragma unroll
+        for (int c = 0; c < CPL; c += 2)
+            *reinterpret_cast<unsigned int *>(out + c * 2) = pack2<DT>(acc[c] * inv, acc[c + 1] * inv);
+    }
 }
 
-template <int DT>
+template <int DT, int D>
 __global__ void __launch_bounds__(kMergeWaves * 64) merge_kernel(const MergeParams P)
 {
     const int row = blockIdx.x * kMergeWaves + (threadIdx.x >> 6);
     if (row >= P.num_requests * P.h_q) return;
     const int r = row / P.h_q;
-    merge_one<DT, false>(P, r, row - r * P.h_q, threadIdx.x & 63);
+    merge_one<DT, false, D>(P, r, row - r * P.h_q, threadIdx.x & 63);
 }
 
 // ---- single-launch mode: the reduction inside the attention launch (Sec. 4.3, parallel reduction) ----
@@ -1195,7 +1255,7 @@ __device__ __forceinline__ bool deliver(const PacParams &P, const DevTask &t, in
 }
 
 // A task that the whole workgroup ran (every thread calls this after the task).
-template <int DT>
+template <int DT, int D>
 __device__ void task_delivered_by_workgroup(const PacParams &P, const DevTask &t, int head, char *lds_raw, int waves)
 {
     int *count = reinterpret_cast<int *>(lds_raw), *ready = count + 1;
@@ -1214,14 +1274,14 @@ __device__ void task_delivered_by_workgroup(const PacParams &P, const DevTask &t
 #pragma unroll 1
         for (int i = wave; i < n; i += waves) {
             const int k = i / P.group;
-            merge_one<DT, true>(P.merge, ready[k], head * P.group + (i - k * P.group), threadIdx.x & 63);
+            merge_one<DT, true, D>(P.merge, ready[k], head * P.group + (i - k * P.group), threadIdx.x & 63);
         }
     }
     __syncthreads();                    // the list is done with before LDS is used again
 }
 
 // A task that one wave ran on its own (no barrier: the other waves are inside other tasks).
-template <int DT>
+template <int DT, int D>
 __device__ void task_delivered_by_wave(const PacParams &P, const DevTask &t, int head)
 {
     const int lane = threadIdx.x & 63;
@@ -1237,7 +1297,7 @@ __device__ void task_delivered_by_wave(const PacParams &P, const DevTask &t, int
         ready &= ready - 1;
         const int r = __shfl(req, src);
 #pragma unroll 1
-        for (int hj = 0; hj < P.group; ++hj) merge_one<DT, true>(P.merge, r, head * P.group + hj, lane);
+        for (int hj = 0; hj < P.group; ++hj) merge_one<DT, true, D>(P.merge, r, head * P.group + hj, lane);
     }
 }
 
@@ -1245,15 +1305,17 @@ __device__ void task_delivered_by_wave(const PacParams &P, const DevTask &t, int
 // the ring must start on a 256-byte boundary (no static LDS in that variant).
 extern __shared__ __attribute__((aligned(1024))) char dyn_lds[];
 
-template <int DT, int WIDE>
-__global__ void __launch_bounds__(WIDE ? kWideWaves * 64 : kNarrowWaves * 64, 2) pac_kernel(const PacParams P)
+template <int DT, int WIDE, int D>
+__global__ void __launch_bounds__(WIDE ? kWideWaves * 64 : kNarrowWaves * 64, D > 128 ? 1 : 2)
+pac_kernel(const PacParams P)     // 256 channels: two blocks of K and V in registers need a wave per SIMD
 {
+    static_assert(WIDE == 0 || D == kHeadDim, "the dense path exists for 128 channels only");
     constexpr int W = WIDE ? kWideWaves : kNarrowWaves;
     char *lds;
     if constexpr (WIDE != 0) {
         lds = dyn_lds;
     } else {
-        __shared__ __attribute__((aligned(16))) char static_lds[merge_bytes(kNarrowWaves, 1)];
+        __shared__ __attribute__((aligned(16))) char static_lds[merge_bytes(kNarrowWaves, 1, D)];
         lds = static_lds;
     }
     const int head = blockIdx.x % P.h_kv;
@@ -1283,19 +1345,19 @@ __global__ void __launch_bounds__(WIDE ? kWideWaves * 64 : kNarrowWaves * 64, 2)
                     k = __builtin_amdgcn_readfirstlane(k);
                     if (k >= n) break;
                     const DevTask mine = recs[i + k];
-                    if (mine.flags & kTaskReadOnce) run_stream<DT, true, 1, 1>(P, mine, head, lds, 0);
-                    else                run_stream<DT, false, 1, 1>(P, mine, head, lds, 0);
-                    if (P.arrive) task_delivered_by_wave<DT>(P, mine, head);
+                    if (mine.flags & kTaskReadOnce) run_stream<DT, true, 1, 1, D>(P, mine, head, lds, 0);
+                    else                run_stream<DT, false, 1, 1, D>(P, mine, head, lds, 0);
+                    if (P.arrive) task_delivered_by_wave<DT, D>(P, mine, head);
                 }
                 __syncthreads();                // the counter is done with before LDS is used again
                 i += n;
             } else {
                 if (t.n_req * P.group <= 16) {
-                    if (t.flags & kTaskReadOnce) run_stream<DT, true, 1, W>(P, t, head, lds, wave);
-                    else             run_stream<DT, false, 1, W>(P, t, head, lds, wave);
+                    if (t.flags & kTaskReadOnce) run_stream<DT, true, 1, W, D>(P, t, head, lds, wave);
+                    else             run_stream<DT, false, 1, W, D>(P, t, head, lds, wave);
                 }
                 else if constexpr (WIDE != 0) run_dense32<DT>(P, t, head, lds);
-                if (P.arrive) task_delivered_by_workgroup<DT>(P, t, head, lds, W);
+                if (P.arrive) task_delivered_by_workgroup<DT, D>(P, t, head, lds, W);
                 ++i;
             }
         }
@@ -1389,27 +1451,40 @@ int prepare_kernels()
     if (dev < 0 || dev >= kMaxDevices) return int(hipErrorInvalidDevice);
     std::lock_guard<std::mutex> guard(lock);
     if (done[dev]) return 0;
-    if (hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(pac_kernel<CODEC_DTYPE_FP16, 1>),
+    if (hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(pac_kernel<CODEC_DTYPE_FP16, 1, 128>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, kRingBytes))
         return int(e);
-    if (hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(pac_kernel<CODEC_DTYPE_BF16, 1>),
+    if (hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(pac_kernel<CODEC_DTYPE_BF16, 1, 128>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, kRingBytes))
         return int(e);
     done[dev] = true;
     return 0;
 }
 
-int launch_pac(const PacParams &p, int dtype, int num_slots, int max_rows_in_plan, void *stream)
+template <int DT, int D>
+void launch_narrow(const PacParams &p, dim3 grid, hipStream_t s)
+{
+    hipLaunchKernelGGL((pac_kernel<DT, 0, D>), grid, dim3(kNarrowWaves * 64), 0, s, p);
+}
+
+int launch_pac(const PacParams &p, int dtype, int head_dim, int num_slots, int max_rows_in_plan, void *stream)
 {
     const bool wide = max_rows_in_plan > 16;
+    if (wide && head_dim != kHeadDim) return int(hipErrorInvalidValue);     // the planner never builds such a plan
     const dim3 grid(unsigned(num_slots) * unsigned(p.h_kv)), block((wide ? kWideWaves : kNarrowWaves) * 64);
     hipStream_t s = static_cast<hipStream_t>(stream);
+    const bool f16 = dtype == CODEC_DTYPE_FP16;
     if (wide) {
-        if (dtype == CODEC_DTYPE_FP16) hipLaunchKernelGGL((pac_kernel<CODEC_DTYPE_FP16, 1>), grid, block, kRingBytes, s, p);
-        else                           hipLaunchKernelGGL((pac_kernel<CODEC_DTYPE_BF16, 1>), grid, block, kRingBytes, s, p);
+        if (f16) hipLaunchKernelGGL((pac_kernel<CODEC_DTYPE_FP16, 1, 128>), grid, block, kRingBytes, s, p);
+        else     hipLaunchKernelGGL((pac_kernel<CODEC_DTYPE_BF16, 1, 128>), grid, block, kRingBytes, s, p);
+    } else if (head_dim == 64) {
+        if (f16) launch_narrow<CODEC_DTYPE_FP16, 64>(p, grid, s); else launch_narrow<CODEC_DTYPE_BF16, 64>(p, grid, s);
+    } else if (head_dim == 128) {
+        if (f16) launch_narrow<CODEC_DTYPE_FP16, 128>(p, grid, s); else launch_narrow<CODEC_DTYPE_BF16, 128>(p, grid, s);
+    } else if (head_dim == 256) {
+        if (f16) launch_narrow<CODEC_DTYPE_FP16, 256>(p, grid, s); else launch_narrow<CODEC_DTYPE_BF16, 256>(p, grid, s);
     } else {
-        if (dtype == CODEC_DTYPE_FP16) hipLaunchKernelGGL((pac_kernel<CODEC_DTYPE_FP16, 0>), grid, block, 0, s, p);
-        else                           hipLaunchKernelGGL((pac_kernel<CODEC_DTYPE_BF16, 0>), grid, block, 0, s, p);
+        return int(hipErrorInvalidValue);
     }
     return int(hipGetLastError());
 }
@@ -1424,13 +1499,23 @@ int launch_stream_read(const void *buf, uint64_t chunks, uint64_t mult, int once
     return int(hipGetLastError());
 }
 
-int launch_merge(const MergeParams &p, int dtype, void *stream)
+template <int DT>
+void launch_merge_of(const MergeParams &p, int head_dim, dim3 grid, hipStream_t s)
 {
+    const dim3 block(kMergeWaves * 64);
+    if (head_dim == 64)       hipLaunchKernelGGL((merge_kernel<DT, 64>), grid, block, 0, s, p);
+    else if (head_dim == 128) hipLaunchKernelGGL((merge_kernel<DT, 128>), grid, block, 0, s, p);
+    else                      hipLaunchKernelGGL((merge_kernel<DT, 256>), grid, block, 0, s, p);
+}
+
+int launch_merge(const MergeParams &p, int dtype, int head_dim, void *stream)
+{
+    if (head_dim != 64 && head_dim != 128 && head_dim != 256) return int(hipErrorInvalidValue);
     const int rows = p.num_requests * p.h_q;
-    const dim3 grid(unsigned((rows + kMergeWaves - 1) / kMergeWaves)), block(kMergeWaves * 64);
+    const dim3 grid(unsigned((rows + kMergeWaves - 1) / kMergeWaves));
     hipStream_t s = static_cast<hipStream_t>(stream);
-    if (dtype == CODEC_DTYPE_FP16) hipLaunchKernelGGL((merge_kernel<CODEC_DTYPE_FP16>), grid, block, 0, s, p);
-    else                           hipLaunchKernelGGL((merge_kernel<CODEC_DTYPE_BF16>), grid, block, 0, s, p);
+    if (dtype == CODEC_DTYPE_FP16) launch_merge_of<CODEC_DTYPE_FP16>(p, head_dim, grid, s);
+    else                           launch_merge_of<CODEC_DTYPE_BF16>(p, head_dim, grid, s);
     return int(hipGetLastError());
 }
 

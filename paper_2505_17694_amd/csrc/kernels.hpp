@@ -14,12 +14,12 @@ struct MergeParams {
     const int32_t *req_part_off;
     const int32_t *req_part;
     const int32_t *req_inline;      // [B][1 + kInlineParts]: count, then the first rows of the list
-    void *out;                      // [B][h_q][128], 16-bit
+    void *out;                      // [B][h_q][head_dim], 16-bit
     int32_t num_requests, h_q, group, part_rows;
 };
 
 struct PacParams {
-    const void *q;                  // [B][h_q][128], 16-bit
+    const void *q;                  // [B][h_q][head_dim], 16-bit
     const void *k_pages;
     const void *v_pages;
     int64_t page_stride, token_stride, head_stride;     // elements
@@ -27,7 +27,7 @@ struct PacParams {
     const int32_t *slot_off;
     const int32_t *node_q;
     const int32_t *page_ids;
-    float *part_o;                  // [h_kv][part_rows][128] unnormalised partial outputs
+    float *part_o;                  // [h_kv][part_rows][head_dim] unnormalised partial outputs
     float *part_ml;                 // [h_kv][part_rows][2]   (max in log2 units, sum of exponentials)
     int32_t h_q, h_kv, group, page_shift, part_rows;    // page_shift = log2(tokens per page)
     float scale_log2e;              // scale * log2(e): scores are kept in log2 units
@@ -68,7 +68,8 @@ int launch_stream_read(const void *buf, uint64_t chunks, uint64_t mult, int once
 
 // Both return a hipError_t value (0 = success) without synchronising.
 // `max_rows_in_plan` selects the register-budget variant of the attention kernel.
-int launch_pac(const PacParams &p, int dtype, int num_slots, int max_rows_in_plan, void *stream);
-int launch_merge(const MergeParams &p, int dtype, void *stream);
+// `head_dim`: 64, 128 or 256 (plans for 64 and 256 hold tasks of at most 16 rows).
+int launch_pac(const PacParams &p, int dtype, int head_dim, int num_slots, int max_rows_in_plan, void *stream);
+int launch_merge(const MergeParams &p, int dtype, int head_dim, void *stream);
 
 }  // namespace codec

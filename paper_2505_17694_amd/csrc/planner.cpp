@@ -289,7 +289,7 @@ int build_plan(const codec_tree &tree, const codec_head_config &head,
     if (tree.num_requests > 0 && !tree.req_node) return CODEC_ERR_INVALID_ARGUMENT;
     if (head.num_q_heads < 1 || head.num_kv_heads < 1) return CODEC_ERR_INVALID_ARGUMENT;
     if (head.num_q_heads % head.num_kv_heads != 0) return CODEC_ERR_INVALID_ARGUMENT;
-    if (head.head_dim != 128) return CODEC_ERR_UNSUPPORTED;
+    if (head.head_dim != 64 && head.head_dim != 128 && head.head_dim != 256) return CODEC_ERR_UNSUPPORTED;
     if (head.dtype != CODEC_DTYPE_FP16 && head.dtype != CODEC_DTYPE_BF16) return CODEC_ERR_UNSUPPORTED;
     if (head.page_size < 16 || head.page_size > 4096 || (head.page_size & (head.page_size - 1)) != 0)
         return CODEC_ERR_UNSUPPORTED;
@@ -298,7 +298,12 @@ int build_plan(const codec_tree &tree, const codec_head_config &head,
     if (group > 64) return CODEC_ERR_UNSUPPORTED;
 
     const int32_t align = opt.split_align > 0 ? opt.split_align : std::max(256, head.page_size);
-    const int32_t max_rows = opt.max_rows > 0 ? opt.max_rows : std::max(256, group);
+    int32_t max_rows = opt.max_rows > 0 ? opt.max_rows : std::max(256, group);
+    if (head.head_dim != 128) {
+        // 64 and 256 channels run in the 16-row task shape only: row tiles of at most 16 rows
+        if (group > kSoloMaxRows) return CODEC_ERR_UNSUPPORTED;
+        max_rows = std::min(max_rows, std::max(group, kSoloMaxRows / group * group));
+    }
     if (opt.num_slots < 0 || opt.split_align < 0 || opt.max_rows < 0) return CODEC_ERR_INVALID_ARGUMENT;
     if (opt.num_slots > (1 << 20)) return CODEC_ERR_INVALID_ARGUMENT;
     if (align % 32 != 0 || align % head.page_size != 0) return CODEC_ERR_INVALID_ARGUMENT;

@@ -47,7 +47,10 @@ def test_create_ok_and_sizes():
 
 
 @pytest.mark.parametrize("head,status", [
-    (HeadConfig(8, 2, 64), C.CODEC_ERR_UNSUPPORTED),
+    (HeadConfig(8, 2, 96), C.CODEC_ERR_UNSUPPORTED),           # head dimensions: 64, 128, 256
+    (HeadConfig(8, 2, 512), C.CODEC_ERR_UNSUPPORTED),
+    (HeadConfig(64, 2, 64), C.CODEC_ERR_UNSUPPORTED),           # 64 and 256 channels: groups of at most 16
+    (HeadConfig(34, 2, 256), C.CODEC_ERR_UNSUPPORTED),
     (HeadConfig(8, 2, 128, dtype=2), C.CODEC_ERR_UNSUPPORTED),
     (HeadConfig(8, 2, 128, page_size=24), C.CODEC_ERR_UNSUPPORTED),
     (HeadConfig(8, 2, 128, page_size=48), C.CODEC_ERR_UNSUPPORTED),

@@ -82,6 +82,34 @@ def test_head_layouts(hq, hkv):
     check(w, share=0)
 
 
+@pytest.mark.parametrize("d", [64, 256])
+@pytest.mark.parametrize("case", ["cfg2", "cfg3", "ragged", "mha-drafted-masked", "mqa", "queue-fused", "flat-fp16"])
+def test_other_head_dimensions(d, case):
+    """64 and 256 channels per head: the 16-row task shape only (row tiles of at most 16 rows, whatever
+    max_rows asks for), every plan option, masks, the single-launch mode and the reduction kernel."""
+    if case == "cfg2":
+        f, hq, hkv, dtype, opts = make_small_config("cfg2", 8, 2).forest, 32, 8, DTYPE_BF16, {}
+    elif case == "cfg3":
+        f, hq, hkv, dtype, opts = make_small_config("cfg3", 16, 2).forest, 32, 8, DTYPE_BF16, {"extensions": 3}
+    elif case == "ragged":
+        f, hq, hkv, dtype, opts = unshared_forest([1, 15, 16, 17, 31, 33, 63, 65, 127, 129, 1030]), 8, 2, DTYPE_FP16, \
+            {"num_slots": 3, "split_align": 32}
+    elif case == "mha-drafted-masked":
+        f, hq, hkv, dtype, opts = draft_masked_forest(300, [900, 33, 260], 40, seed=5), 8, 8, DTYPE_BF16, {"fused": 1}
+    elif case == "mqa":
+        f, hq, hkv, dtype, opts = three_level_forest(70, [130, 45], 3, [5, 33, 64, 1, 17, 48]), 16, 1, DTYPE_BF16, \
+            {"max_rows": 200}
+    elif case == "queue-fused":
+        f, hq, hkv, dtype, opts = random_forest(30, 4, 2.0, 200, 1.0, 1, 3000, seed=7), 12, 4, DTYPE_BF16, \
+            {"schedule": 1, "fused": 1, "num_slots": 2, "split_align": 64}
+    else:
+        f, hq, hkv, dtype, opts = two_level_forest(2100, [40, 90, 33, 7]), 8, 2, DTYPE_FP16, {"share": 0}
+    w = make_workload(f"d{d}-{case}", f, HeadConfig(hq, hkv, d, dtype), seed=600 + d, poison=True,
+                      layout="htd" if d == 64 else "thd")
+    _, view = check(w, **opts)
+    assert max(t["n_req"] * (hq // hkv) for t in view["tasks"]) <= 16
+
+
 @pytest.mark.parametrize("max_rows", [8, 16, 32, 48, 64, 100, 128, 200, 256])
 def test_row_tiles(max_rows):
     """70 requests x group 4 = 280 rows under the root: stream and dense task shapes, row tiling."""
