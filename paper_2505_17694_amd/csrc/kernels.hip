@@ -130,14 +130,6 @@ __device__ __forceinline__ void st8_partial(float *p, float a, float b, bool coh
     else          *reinterpret_cast<float2 *>(p) = float2{a, b};
 }
 
-// A 16-byte load the compiler does not know is pending: the caller waits for it itself (a vector-memory
-// wait that names dst, see wait_pending) and must not touch dst before.  Used where loads are queued
-// between asynchronous copies: a wait placed by the compiler would count those copies as its own.
-__device__ __forceinline__ void ld16_pending(u32x4 &dst, const char *p)
-{
-    asm volatile("global_load_dwordx4 %0, %1, off" : "=v"(dst) : "v"(p) : "memory");
-}
-
 // The lane index as a value the optimiser cannot trace back to the thread id.  Each task path derives
 // its lane constants (operand addresses, row and channel positions) from it, which keeps them inside
 // the path: hoisted out of the task loop they would stay live across all paths and cost the dense
@@ -645,6 +637,25 @@ __device__ __forceinline__ void dma16_pair(uint32_t lds_addr, uint32_t voff_k, u
     }
 }
 
+// One 16-byte piece per lane from a per-lane address: lane i's piece lands at lds_addr + 16 * i.  Used for
+// the query rows of a dense task, which are queued between the copies of K/V blocks: a load into
+// registers there would have to be waited for by the compiler, which counts the copies as its own loads
+// and would wait for all of them; through LDS the rows take the same asynchronous path as the blocks,
+// no register is written behind the compiler's back, and the rows are read from LDS by ordinary loads
+// once the hand-placed wait has passed.
+__device__ __forceinline__ void dma16_rows(uint32_t lds_addr, const char *gp)
+{
+    uint32_t m0_saved;
+    asm volatile("s_mov_b32 %0, m0\n\t"
+                 "s_mov_b32 m0, %1\n\t"
+                 "s_nop 0\n\t"
+                 "global_load_lds_dwordx4 %2, off\n\t"
+                 "s_mov_b32 m0, %0\n"
+                 : "=&s"(m0_saved)
+                 : "s"(lds_addr), "v"(gp)
+                 : "memory", "scc");
+}
+
 // ---- dense path with 32 query rows per wave ---------------------------------------------------------
 //
 // v_mfma_f32_32x32x16: A operand lane = (row lane%32, k-group lane/32), 8 k-values per lane; B operand
@@ -891,8 +902,13 @@ __device__ __forceinline__ void dense32_wave(const PacParams &P, const DevTask &
     // Start of the task.  What the first matrix instruction waits for is a chain of dependent reads:
     // page ids and the rows' requests, then the first blocks and the query rows.  The two reads of a
     // stage are issued together; the query rows (32 rows of 32 bytes per instruction, the slowest
-    // requests to issue) are queued behind the copies of the first 2S blocks only, the other copies
-    // of the ring behind them.
+    // requests to issue) are queued behind the copies of the first 2S blocks only.  They travel through
+    // LDS like the blocks (dma16_rows): each wave parks its 8 KB in the last four slots of the ring,
+    // whose blocks are requested once every wave has taken its rows into registers, behind the barrier
+    // that ends this start-up; the other blocks of the ring are requested right behind the rows.
+    constexpr int EARLY = RING - 4;                                     // blocks requested ahead of that barrier
+    static_assert(EARLY >= 2 * STRIDE && 8 * 8192 == 4 * kBlockBytes, "the rows' parking space is the last four slots");
+    int pg_late[4];
     {
         int pg[RING];
 #pragma unroll
@@ -910,32 +926,42 @@ __device__ __forceinline__ void dense32_wave(const PacParams &P, const DevTask &
                  + (int64_t(req) * P.h_q + int64_t(head) * P.group + hj) * (kHeadDim * 2) + kg * 16;
         }
 #pragma unroll
+        for (int d = 0; d < 4; ++d) pg_late[d] = pg[EARLY + d];
+#pragma unroll
         for (int d = 0; d < 2 * STRIDE; ++d)
             if (d < nblk) dma_block(d, pg[d]);
+        const uint32_t park = lds_base + uint32_t(EARLY) * kBlockBytes + uint32_t(wave) * 8192;   // wave-uniform
+        const uint32_t parked = park + uint32_t(lane) * 16;
         if constexpr (LIVE) {
 #pragma unroll
-            for (int ks = 0; ks < 8; ++ks) ld16_pending(qb[ks], qp + ks * 32);
+            for (int ks = 0; ks < 8; ++ks) dma16_rows(park + ks * 1024, qp + ks * 32);
         }
 #pragma unroll
-        for (int d = 2 * STRIDE; d < RING; ++d)
+        for (int d = 2 * STRIDE; d < EARLY; ++d)
             if (d < nblk) dma_block(d, pg[d]);
-        // loads complete in order: with at most the copies of blocks 2S .. RING-1 outstanding, blocks
-        // 0 .. 2S-1 have landed and the query rows are in their registers
-        if (nblk >= RING) __builtin_amdgcn_s_waitcnt(vmcnt_imm(2 * (RING - 2 * STRIDE)));
-        else               __builtin_amdgcn_s_waitcnt(0x0F70);
+        // loads complete in order: with at most the copies of blocks 2S .. EARLY-1 outstanding, blocks
+        // 0 .. 2S-1 and the query rows have landed
+        if (nblk >= EARLY) __builtin_amdgcn_s_waitcnt(vmcnt_imm(2 * (EARLY - 2 * STRIDE)));
+        else                __builtin_amdgcn_s_waitcnt(0x0F70);
         if constexpr (LIVE) {
-            // from here on the query registers may be read; one statement on every path, so that no
-            // copy of a register still being loaded is made where paths join
-            asm volatile("; query rows ready" : "+v"(qb[0]), "+v"(qb[1]), "+v"(qb[2]), "+v"(qb[3]), "+v"(qb[4]), "+v"(qb[5]),
-                              "+v"(qb[6]), "+v"(qb[7]));
+            typedef const u32x4 __attribute__((address_space(3))) *lds_u32x4_ptr;
 #pragma unroll
-            for (int ks = 0; ks < 8; ++ks) qb[ks] = live ? qb[ks] : u32x4{0u, 0u, 0u, 0u};
+            for (int ks = 0; ks < 8; ++ks) {
+                const u32x4 x = *reinterpret_cast<lds_u32x4_ptr>(uintptr_t(parked + ks * 1024));   // the piece this lane sent
+                qb[ks] = live ? x : u32x4{0u, 0u, 0u, 0u};
+            }
+            // the rows are in registers before this wave passes the barrier below, behind which the
+            // parking space is overwritten
+            __builtin_amdgcn_s_waitcnt(0xC07F);
         }
     }
     int pg_next[STRIDE];                                                // pages of the blocks interval 0 requests
 #pragma unroll
     for (int u = 0; u < STRIDE; ++u) pg_next[u] = page_issue(RING + u);
     __syncthreads();
+#pragma unroll
+    for (int d = 0; d < 4; ++d)
+        if (EARLY + d < nblk) dma_block(EARLY + d, pg_late[d]);
 
     // more: blocks S*j+8 .. S*j+8+S-1 all exist
     auto wait_and_sync = [&](auto more) {
