@@ -87,6 +87,23 @@ __device__ __forceinline__ unsigned int pack2(float lo, float hi)
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
+// acc + lo + hi of a dword of two 16-bit values (a two-element dot product with ones, exact products,
+// fp32 sum).  Row sums are taken over the probabilities as rounded for the second product: the
+// normaliser then matches the numerator, and a pair costs one instruction.
+template <int DT>
+__device__ __forceinline__ float add_pair(unsigned int packed, float acc)
+{
+    if constexpr (DT == CODEC_DTYPE_FP16) {
+        typedef __attribute__((ext_vector_type(2))) _Float16 h2;
+        const h2 ones = {(_Float16)1.0f, (_Float16)1.0f};
+        return __builtin_amdgcn_fdot2(__builtin_bit_cast(h2, packed), ones, acc, false);
+    } else {
+        typedef __attribute__((ext_vector_type(2))) __bf16 b2;
+        const b2 ones = {(__bf16)1.0f, (__bf16)1.0f};
+        return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(b2, packed), ones, acc, false);
+    }
+}
+
 __device__ __forceinline__ u32x4 ld16(const char *p) { return *reinterpret_cast<const u32x4 *>(p); }
 // The same load with the streaming hint (the `nt` bit).  K and V slices that one task alone reads are
 // fetched this way: bytes on their way through then do not displace each other, nor the slices that
@@ -359,9 +376,10 @@ __device__ __forceinline__ void probabilities(const f32x4 (&s)[2][NT], RowState<
 #pragma unroll
             for (int e = 0; e < 4; ++e)
                 p[j][e] = fast_exp2(__builtin_fmaf(s[j][nt][e], scale_log2e, -st.m[nt]));
-        st.l[nt] += ((p[0][0] + p[0][1]) + (p[0][2] + p[0][3])) + ((p[1][0] + p[1][1]) + (p[1][2] + p[1][3]));
         pb[nt] = u32x4{pack2<DT>(p[0][0], p[0][1]), pack2<DT>(p[0][2], p[0][3]),
                        pack2<DT>(p[1][0], p[1][1]), pack2<DT>(p[1][2], p[1][3])};
+#pragma unroll
+        for (int d = 0; d < 4; ++d) st.l[nt] = add_pair<DT>(pb[nt][d], st.l[nt]);
     }
 }
 
@@ -715,7 +733,7 @@ __device__ __forceinline__ void dense32_wave(const PacParams &P, const DevTask &
     u32x4 qb[8];            // B operand of the scores: row l32, channels 16*ks + 8*kg .. +7
     f32x16 o[4];            // O^T: row l32, channel 32*ct + 8*(r/4) + 4*kg + r%4
     float m = -INFINITY;    // reference, log2 units, integer-valued (same in the two lanes of a row)
-    float l = 0.f;          // this lane's share of the row sum
+    float l4[4] = {0.f, 0.f, 0.f, 0.f};     // this lane's share of the row sum, in four partial sums
     if constexpr (LIVE) {
 #pragma unroll
         for (int ct = 0; ct < 4; ++ct)
@@ -871,7 +889,8 @@ __device__ __forceinline__ void dense32_wave(const PacParams &P, const DevTask &
             const float mx = fmaxf(lm, __shfl_xor(lm, 32));
             const float m_new = __builtin_ceilf(fmaxf(m, mx));
             const float alpha = fast_exp2(m - m_new);                   // 0 on the first block (m = -inf)
-            l *= alpha;
+#pragma unroll
+            for (int d = 0; d < 4; ++d) l4[d] *= alpha;
 #pragma unroll
             for (int ct = 0; ct < 4; ++ct)
 #pragma unroll
@@ -883,11 +902,12 @@ __device__ __forceinline__ void dense32_wave(const PacParams &P, const DevTask &
         float e[8];
 #pragma unroll
         for (int i = 0; i < 8; ++i) e[i] = fast_exp2(__builtin_fmaf(s[8 * tt + i], P.scale_log2e, -m));
-        l += ((e[0] + e[1]) + (e[2] + e[3])) + ((e[4] + e[5]) + (e[6] + e[7]));
 #pragma unroll
-        for (int d = 0; d < 4; ++d) p[tt][d] = pack2<DT>(e[2 * d], e[2 * d + 1]);
+        for (int d = 0; d < 4; ++d) {
+            p[tt][d] = pack2<DT>(e[2 * d], e[2 * d + 1]);
+            l4[d] = add_pair<DT>(p[tt][d], l4[d]);
+        }
         pin(p[tt]);
-        pin(l);
     };
 
     // Common to all roles.  Blocks 0 .. 7 are requested up front; interval j (j = 0 .. nint-1) starts
@@ -1060,6 +1080,7 @@ __device__ __forceinline__ void dense32_wave(const PacParams &P, const DevTask &
     }
 
     __syncthreads();                        // every block has been read: the ring is free
+    float l = (l4[0] + l4[1]) + (l4[2] + l4[3]);
     if constexpr (STRIDE == 2) {
         // The odd-block wave hands its state to the even-block wave of its row group: 64 accumulator
         // registers, reference and sum share per lane, register-major so that a wave's store or load
