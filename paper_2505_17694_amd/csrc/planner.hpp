@@ -22,7 +22,7 @@ struct CostTable {
 // A task of at most kSoloMaxRows rows and kSoloMaxLen tokens may be run by a single wave; the kernels
 // take runs of such tasks in a slot's list one wave each (see solo_run below).
 constexpr int32_t kSoloMaxRows = 16;
-constexpr int32_t kSoloMaxLen = 1024;
+constexpr int32_t kSoloMaxLen = 2048;
 // Most short tasks in one entry of the run-time queue (measured on cfg3/cfg4: 2 costs fetches, 8 and
 // more make the last entries long).
 constexpr int32_t kQueueBundle = 4;

@@ -29,6 +29,7 @@ import sys
 
 import numpy as np
 
+FLOOR_NS = 200.0
 DEFAULT_OUT = os.path.join(os.path.dirname(os.path.abspath(__file__)), "cost_table_mi355x.json")
 
 
@@ -45,72 +46,85 @@ def _forest(num_tasks, rows, length, force_wide):
     return np.array(parent, np.int32), np.array(node_len, np.int32), np.array(req_node, np.int32)
 
 
-def launch_time(rows: int, length: int, wide: bool, per_slot: int, iters: int = 8,
-                device: str = "cuda:0") -> float:
-    """Median duration (ns) of the partial-attention launch with `per_slot` (rows, length) tasks per slot."""
-    import torch
-    from . import binding as B
-    from .runtime import PlannedAttention
+class _Case:
+    """One profiling launch shape: every slot of every KV head runs `per_slot` (rows, length) tasks."""
 
-    class Bag:
-        pass
+    def __init__(self, rows: int, length: int, wide: bool, per_slot: int, device: str = "cuda:0"):
+        import torch
+        from . import binding as B
+        from .runtime import PlannedAttention
 
-    h_kv, d, ps = 8, 128, 16
-    slots = 32 if wide else 64
-    force = wide and rows <= 16
-    parent, node_len, req_node = _forest(slots * per_slot, rows, length, force)
-    forest, paged, head = Bag(), Bag(), Bag()
-    forest.parent, forest.node_len, forest.req_node = parent, node_len, req_node
-    pages_per = (node_len.astype(np.int64) + ps - 1) // ps
-    off = np.zeros(len(parent) + 1, np.int64)
-    np.cumsum(pages_per, out=off[1:])
-    paged.node_page_off = off.astype(np.int32)
-    paged.num_pages = int(off[-1])
-    rng = np.random.Generator(np.random.PCG64(rows * 1000003 + length))
-    paged.page_ids = rng.permutation(paged.num_pages).astype(np.int32)
-    paged.page_stride, paged.token_stride, paged.head_stride = ps * h_kv * d, d, ps * d
-    head.num_q_heads = head.num_kv_heads = h_kv
-    head.head_dim, head.dtype, head.page_size, head.scale = d, B.CODEC_DTYPE_BF16, ps, 1.0 / math.sqrt(d)
+        class Bag:
+            pass
 
-    pool_elems = paged.num_pages * ps * h_kv * d
-    copies = max(1, min(16, int((2 << 30) // max(1, 4 * pool_elems))))
-    gen = torch.Generator(device=device)
-    gen.manual_seed(1)
-    q = torch.randn((len(req_node), h_kv, d), device=device, generator=gen).to(torch.bfloat16)
-    pools = [(torch.randn(pool_elems, device=device, generator=gen).to(torch.bfloat16),
-              torch.randn(pool_elems, device=device, generator=gen).to(torch.bfloat16)) for _ in range(copies)]
-    # a flat table keeps the planner from dividing: one task per node, one node per slot
-    flat = ([1], [1], [[1000]])
-    pa = PlannedAttention(forest, paged, head, device=device, num_slots=slots,
-                          split_align=32, max_rows=256, share=1, cost_table=flat)
-    view = pa.export()
-    assert len(view["tasks"]) == len(parent), "the profiling plan must not divide nodes"
-    per = np.bincount([t["slot"] for t in view["tasks"]][:slots * per_slot], minlength=slots)
-    assert per.max() == per_slot, "every slot must get the same number of tasks"
-    stream = torch.cuda.current_stream()
-    for i in range(2):
-        pa.partial_attention(q, *pools[i % copies])
-    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(iters)]
-    for i, (a, b) in enumerate(ev):
-        k, v = pools[(i + 2) % copies]
-        a.record(stream)
-        pa.partial_attention(q, k, v)
-        b.record(stream)
-    torch.cuda.synchronize()
-    pa.close()
-    times = sorted(a.elapsed_time(b) for a, b in ev)
-    return times[len(times) // 2] * 1e6
+        h_kv, d, ps = 8, 128, 16
+        slots = 32 if wide else 64
+        force = wide and rows <= 16
+        parent, node_len, req_node = _forest(slots * per_slot, rows, length, force)
+        forest, paged, head = Bag(), Bag(), Bag()
+        forest.parent, forest.node_len, forest.req_node = parent, node_len, req_node
+        pages_per = (node_len.astype(np.int64) + ps - 1) // ps
+        off = np.zeros(len(parent) + 1, np.int64)
+        np.cumsum(pages_per, out=off[1:])
+        paged.node_page_off = off.astype(np.int32)
+        paged.num_pages = int(off[-1])
+        rng = np.random.Generator(np.random.PCG64(rows * 1000003 + length))
+        paged.page_ids = rng.permutation(paged.num_pages).astype(np.int32)
+        # [page][kv_head][token][d]: a (page, head) is one contiguous 4 KB run
+        paged.page_stride, paged.token_stride, paged.head_stride = ps * h_kv * d, d, ps * d
+        head.num_q_heads = head.num_kv_heads = h_kv
+        head.head_dim, head.dtype, head.page_size, head.scale = d, B.CODEC_DTYPE_BF16, ps, 1.0 / math.sqrt(d)
+
+        pool_elems = paged.num_pages * ps * h_kv * d
+        copies = max(1, min(16, int((2 << 30) // max(1, 4 * pool_elems))))
+        gen = torch.Generator(device=device)
+        gen.manual_seed(1)
+        self.q = torch.randn((len(req_node), h_kv, d), device=device, generator=gen).to(torch.bfloat16)
+        self.pools = [(torch.randn(pool_elems, device=device, generator=gen).to(torch.bfloat16),
+                       torch.randn(pool_elems, device=device, generator=gen).to(torch.bfloat16)) for _ in range(copies)]
+        # a flat table keeps the planner from dividing: one task per node, one node per slot
+        flat = ([1], [1], [[1000]])
+        self.pa = PlannedAttention(forest, paged, head, device=device, num_slots=slots,
+                                   split_align=32, max_rows=256, share=1, cost_table=flat)
+        view = self.pa.export()
+        assert len(view["tasks"]) == len(parent), "the profiling plan must not divide nodes"
+        per = np.bincount([t["slot"] for t in view["tasks"]][:slots * per_slot], minlength=slots)
+        assert per.max() == per_slot, "every slot must get the same number of tasks"
+        self.turn = 0
+        self.stream = torch.cuda.current_stream()
+        for _ in range(2):
+            self.launch()
+
+    def launch(self):
+        """One launch of the partial-attention kernel on the next pool copy -> (start, end) events."""
+        import torch
+        k, v = self.pools[self.turn % len(self.pools)]
+        self.turn += 1
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record(self.stream)
+        self.pa.partial_attention(self.q, k, v)
+        b.record(self.stream)
+        return a, b
+
+    def close(self):
+        self.pa.close()
 
 
-def measure(rows: int, length: int, wide: bool) -> float:
+def measure(rows: int, length: int, wide: bool, pairs: int = 12) -> float:
     """Cost (ns) of one (rows, length) task inside a busy persistent workgroup.
 
-    The difference between launches with three tasks and with one task per slot, halved: launch
-    latency and the ramp at both ends of a launch drop out.
+    The difference between a launch with three tasks per slot and one with one task per slot, halved:
+    launch latency and the ramp at both ends of a launch drop out.  The two launches alternate (`pairs`
+    times) so that clock and temperature drift hits both alike; the median difference is returned.
     """
-    t1 = launch_time(rows, length, wide, 1)
-    t3 = launch_time(rows, length, wide, 3)
-    return max((t3 - t1) / 2.0, 1.0)
+    import torch
+    one, three = _Case(rows, length, wide, 1), _Case(rows, length, wide, 3)
+    ev = [(one.launch(), three.launch()) for _ in range(pairs)]
+    torch.cuda.synchronize()
+    diffs = sorted(c[0].elapsed_time(c[1]) - a[0].elapsed_time(a[1]) for a, c in ev)
+    one.close()
+    three.close()
+    return max(diffs[len(diffs) // 2] * 1e6 / 2.0, 1.0)
 
 
 def profile(row_grid, len_grid, wide: bool, verbose: bool = True):
@@ -118,7 +132,9 @@ def profile(row_grid, len_grid, wide: bool, verbose: bool = True):
     for r in row_grid:
         row = []
         for n in len_grid:
-            ns = measure(r, n, wide)
+            # the difference of two launches cannot resolve a task that a wave runs in the shadow of the
+            # others: no task is priced below FLOOR_NS (a record read and a partial row written)
+            ns = max(measure(r, n, wide), FLOOR_NS)
             row.append(int(round(ns)))
             if verbose:
                 print(f"[profile] {'wide' if wide else 'narrow'} rows={r:4d} len={n:6d}: {ns / 1e3:9.2f} us",

@@ -273,10 +273,10 @@ def test_many_short_tasks_per_slot(slots, upside_down):
     """Long runs of single-wave tasks in a slot's list, before, between and behind team and dense tasks.
 
     With the upside-down cost table short tasks count as the most expensive, so longest-first
-    scheduling puts them in front of the long ones; lengths around the single-wave limit (1024) and
+    scheduling puts them in front of the long ones; lengths around the single-wave limit (2048) and
     request counts around the 16-row limit mix the three task shapes in every slot.
     """
-    lens = [7, 40, 1024, 33, 1025, 64, 300, 5, 2000, 96, 17, 1000, 31, 640, 1, 129] * 3
+    lens = [7, 40, 2048, 33, 2049, 64, 300, 5, 3000, 96, 17, 1000, 31, 640, 1, 129] * 3
     f = concat_forests(two_level_forest(1500, lens), two_level_forest(200, [50, 60, 70, 80, 90]))
     head = HeadConfig(8, 2, 128, DTYPE_BF16)                    # group 4: the 5-request root has 20 rows
     w = make_workload(f"short{slots}", f, head, seed=23, poison=True)
@@ -440,7 +440,7 @@ def test_reduction_lists_of_every_length(slices):
 
 
 def _queue_cases():
-    short = [7, 40, 1024, 33, 1025, 64, 300, 5, 2000, 96, 17, 1000, 31, 640, 1, 129] * 3
+    short = [7, 40, 2048, 33, 2049, 64, 300, 5, 3000, 96, 17, 1000, 31, 640, 1, 129] * 3
     dense = two_level_forest(1, [43] * 17)
     for n in [33, 300, 545, 1024, 1090, 2210]:
         dense = concat_forests(dense, two_level_forest(n, [40 + n % 4] * 17))

@@ -279,7 +279,7 @@ def test_best_candidate_plan_matches_oracle(name, table):
 @pytest.mark.parametrize("slots", [0, 4])
 def test_run_time_queue_entries(name, slots):
     """The queue holds every task once; an entry of several tasks holds short ones only (at most 16 rows
-    and 1024 tokens, at most 4 of them); entries come in order of decreasing cost (a bundle counts as the
+    and 2048 tokens, at most 4 of them); entries come in order of decreasing cost (a bundle counts as the
     sum of its tasks); when the tasks that are not short leave workgroups free, the bundles are just
     large enough for every entry to have a workgroup of its own."""
     make, head = BEST_CASES[name]
@@ -295,7 +295,7 @@ def test_run_time_queue_entries(name, slots):
     assert v["schedule"] == 1
     off, q, tasks = list(v["queue_off"]), list(v["queue_tasks"]), v["tasks"]
     assert sorted(q) == list(range(len(tasks))) and off[0] == 0 and off[-1] == len(tasks)
-    short = [t["n_req"] * group <= 16 and t["kv_len"] <= 1024 for t in tasks]
+    short = [t["n_req"] * group <= 16 and t["kv_len"] <= 2048 for t in tasks]
     costs = []
     for e in range(len(off) - 1):
         members = q[off[e]:off[e + 1]]
