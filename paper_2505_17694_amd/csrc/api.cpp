@@ -325,6 +325,8 @@ int codec_decode_attention_static(const codec_plan_t *plan, const void *q, const
                                   const void *v_pages, const codec_kv_layout *layout, void *out, void *stream)
 {
     if (!plan) return CODEC_ERR_INVALID_ARGUMENT;
+    if (plan->d.num_requests == 0) return layout ? CODEC_OK : CODEC_ERR_INVALID_ARGUMENT;
+    if (!plan->device_meta) return CODEC_ERR_NOT_UPLOADED;      // before the first HIP call of this entry point
     const size_t need = codec_plan_workspace_bytes(plan);
     if (need > codec::kStaticScratchBytes) {
         std::snprintf(g_last_error, sizeof g_last_error,

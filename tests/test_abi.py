@@ -142,3 +142,20 @@ def test_runtime_refuses_pools_smaller_than_the_strides_reach():
     with pytest.raises(ValueError):
         pa._check_pool(two.k_pool, "k_pool")                         # the other layout's pool: half the stride
     pa.close()
+
+
+def test_entry_points_added_for_measurement_and_for_callers_without_a_workspace_check_their_arguments():
+    """Argument errors that are caught before any HIP call."""
+    assert C.codec_static_scratch_bytes() == 64 << 20
+    assert C.codec_decode_attention_static(None, 16, 16, 16, 1, 2048, 128, 128, 16) == C.CODEC_ERR_INVALID_ARGUMENT
+    ok = dict(buffer_ptr=4096, nbytes=1 << 20, pattern=1, nontemporal=1, workgroups=64, sink_ptr=4096)
+    for bad in (dict(buffer_ptr=0), dict(sink_ptr=0), dict(nbytes=3 << 20), dict(nbytes=2048), dict(pattern=2),
+                dict(workgroups=0), dict(buffer_ptr=4100)):
+        args = dict(ok)
+        args.update(bad)
+        assert C.codec_stream_read_probe(**args) == C.CODEC_ERR_INVALID_ARGUMENT, bad
+    # a plan that was never uploaded: the static entry point refuses like the workspace one
+    st, plan = _create()
+    assert st == C.CODEC_OK
+    assert C.codec_decode_attention_static(plan, 16, 16, 16, 64, 2048, 128, 128, 16) == C.CODEC_ERR_NOT_UPLOADED
+    C.codec_plan_destroy(plan)
