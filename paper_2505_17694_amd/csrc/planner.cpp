@@ -202,14 +202,23 @@ void build_device_image(PlanData &p)
         r.single_req = t.n_req == 1 ? p.node_q[t.q_off] : -1;
         return r;
     };
+    // A slot's records in the order the workgroup runs them: the tasks that need the whole workgroup
+    // first, then the single-wave tasks as one run (both in the order of the slot's list, which is by
+    // decreasing cost).  Every run ends with waves waiting for the last one; one run per slot pays that
+    // once, at the end of the launch, where the short tasks also even out what the long ones left.
     DevTask *by_slot = reinterpret_cast<DevTask *>(p.blob.data() + L.slot_recs);
-    for (int32_t sl = 0; sl < p.num_slots; ++sl) {                      // runs of single-wave tasks, back to front
+    auto is_short = [&](int32_t i) {
+        return p.tasks[i].n_req * p.group <= kSoloMaxRows && p.tasks[i].kv_len <= kSoloMaxLen;
+    };
+    for (int32_t sl = 0; sl < p.num_slots; ++sl) {
+        std::vector<int32_t> order(p.slot_tasks.begin() + p.slot_off[sl], p.slot_tasks.begin() + p.slot_off[sl + 1]);
+        std::stable_partition(order.begin(), order.end(), [&](int32_t i) { return !is_short(i); });
         int32_t run = 0;
-        for (int32_t i = p.slot_off[sl + 1] - 1; i >= p.slot_off[sl]; --i) {
-            by_slot[i] = record(p.slot_tasks[i]);
-            const bool is_short = by_slot[i].n_req * p.group <= kSoloMaxRows && by_slot[i].kv_len <= kSoloMaxLen;
-            run = is_short ? run + 1 : 0;
-            by_slot[i].solo_run = run;
+        for (int32_t k = int32_t(order.size()) - 1; k >= 0; --k) {       // runs of single-wave tasks, back to front
+            DevTask &r = by_slot[p.slot_off[sl] + k];
+            r = record(order[k]);
+            run = is_short(order[k]) ? run + 1 : 0;
+            r.solo_run = run;
         }
     }
     DevTask *by_entry = reinterpret_cast<DevTask *>(p.blob.data() + L.queue_recs);
