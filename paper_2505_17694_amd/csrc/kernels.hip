@@ -200,8 +200,11 @@ struct BlockRegs {
     uint32_t visible;   // masked tasks: bit t = the lane's row sees token t of the block
 };
 
-// Issue the loads of block `tb`.  A tile that starts beyond the slice is redirected to tile 0 so that
-// no address leaves the slice's pages; its scores are masked later.  ONCE: with the streaming hint.
+// Issue the loads of block `tb`.  A tile that starts beyond the slice is not loaded (its registers are
+// cleared; its scores are masked later): no address leaves the slice's pages, and the sixteen load
+// instructions of a block, each of which holds a place in the CU's queue of memory instructions in
+// flight whatever it fetches, become eight for the last tile of a ragged slice and for one-token
+// nodes.  ONCE: with the streaming hint.
 template <bool ONCE, int D>
 __device__ __forceinline__ void load_block(const SliceCtx &c, int tb, uint32_t koff, uint32_t voff, BlockRegs<D> &r,
                                            bool masked, const uint32_t *mask_row)
@@ -213,11 +216,19 @@ __device__ __forceinline__ void load_block(const SliceCtx &c, int tb, uint32_t k
 #pragma unroll
     for (int j = 0; j < 2; ++j) {
         tok[j] = tb * 32 + j * 16;
-        if (tok[j] >= c.kv_len) tok[j] = 0;
-        pg[j] = uniform_load(c.pages, tok[j] >> c.page_shift);
+        pg[j] = tok[j] < c.kv_len ? uniform_load(c.pages, tok[j] >> c.page_shift) : 0;
     }
 #pragma unroll
     for (int j = 0; j < 2; ++j) {
+        if (j == 1 && tok[j] >= c.kv_len) {     // wave-uniform: the slice ends inside the first tile
+#pragma unroll
+            for (int ks = 0; ks < BlockRegs<D>::KS; ++ks) r.k[j][ks] = u32x4{0u, 0u, 0u, 0u};
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+#pragma unroll
+                for (int u = 0; u < BlockRegs<D>::VU; ++u) r.v[j * 4 + e][u] = u32x4{0u, 0u, 0u, 0u};
+            continue;
+        }
         const int64_t off = page_offset(c, pg[j], tok[j] & c.page_mask);
         const char *kt = c.k_head + off;
         const char *vt = c.v_head + off;
@@ -1382,19 +1393,24 @@ pac_kernel(const PacParams P)     // 256 channels: two blocks of K and V in regi
             const DevTask t = recs[i];
             const int n = marked ? t.solo_run : t1 - i;
             if (n >= 2) {
+                // Wave w starts with task w of the run, every further task is the next one nobody has
+                // taken.  The run is in order of decreasing cost and the first waves are the older ones
+                // of the pairs that share a SIMD, which the hardware serves first (measured: in a run
+                // they move two to three times the tokens of their partners), so the longest tasks start
+                // on the fastest waves.
                 int *next = reinterpret_cast<int *>(lds);
-                if (threadIdx.x == 0) *next = 0;
+                if (threadIdx.x == 0) *next = W;
                 __syncthreads();
+                int k = wave;
 #pragma unroll 1
-                for (;;) {
-                    int k = 0;
-                    if ((threadIdx.x & 63) == 0) k = atomicAdd(next, 1);
-                    k = __builtin_amdgcn_readfirstlane(k);
-                    if (k >= n) break;
+                while (k < n) {
                     const DevTask mine = recs[i + k];
                     if (mine.flags & kTaskReadOnce) run_stream<DT, true, 1, 1, D>(P, mine, head, lds, 0);
                     else                run_stream<DT, false, 1, 1, D>(P, mine, head, lds, 0);
                     if (P.arrive) task_delivered_by_wave<DT, D>(P, mine, head);
+                    k = 0;
+                    if ((threadIdx.x & 63) == 0) k = atomicAdd(next, 1);
+                    k = __builtin_amdgcn_readfirstlane(k);
                 }
                 __syncthreads();                // the counter is done with before LDS is used again
                 i += n;
