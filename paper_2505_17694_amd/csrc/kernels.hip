@@ -52,7 +52,8 @@ constexpr int kHeadDim = 128;       // the dense path; the stream path and the r
                                     // dimension D (64, 128 or 256) as a template parameter
 constexpr int kNarrowWaves = 4;     // stream-only kernel variant: 4 waves, two workgroups per CU
 constexpr int kWideWaves = 8;       // all task shapes: 8 waves (two per SIMD), one workgroup per CU
-constexpr int kMergeWaves = 4;      // reduction kernel
+constexpr int kMergeWaves = 2;      // reduction kernel (workgroups of two waves: measured against one and four, the
+                                    // launch that follows a reduction starts up to 3 us sooner)
 // Channel tiles of 16 that a stream task accumulates: 8 per 128 channels (with 64 channels half of each
 // tile's rows are idle, see BlockRegs).
 constexpr int channel_tiles(int d) { return d <= 128 ? 8 : d / 16; }
@@ -1178,15 +1179,28 @@ __device__ void run_dense32(const PacParams &P, const DevTask &t, int head, char
     }
 }
 
-// Partial output reduction (Alg. 3), n-ary: one wave folds the partials of one (request, query head)
-// in list order; each lane owns two channels.  Partials are taken eight or fifteen at a time: their
-// loads are issued together, then they are folded against their common maximum (by associativity of
-// the reduction this equals any binary bracketing).
-template <int DT, bool COHERENT, int D>
-__device__ __forceinline__ void merge_one(const MergeParams &P, int r, int hq, int lane)
+// Partial output reduction (Alg. 3), n-ary: one wave folds the partials of RPW consecutive query heads
+// of one request (hq .. hq + RPW - 1, all of one KV head) in list order.  Partials are taken eight or
+// fifteen at a time: their loads are issued together, then they are folded against their common maximum
+// (by associativity of the reduction this equals any binary bracketing).
+//
+// RPW = 1: each lane owns D / 64 channels of the one row.  RPW = 256 / D (the reduction kernel, when
+// the group size allows it): each lane owns four channels of one of the rows; the rows of consecutive
+// heads are neighbours in the partial arrays and in the output, so every load of partial rows is one
+// full 1 KB instruction and a reduction costs half (a quarter for 64 channels) the memory instructions
+// per row.  The kernel is bound by those: each takes a place in the CU's queue of memory instructions
+// in flight whatever it moves.  For the same reason it loads only the partials that exist (inside the
+// attention kernel, single-launch mode, every slot of a round is loaded: rows behind the end of a list
+// read as row 0, which is valid memory, and the straight-line code keeps that kernel as it is).
+template <int DT, bool COHERENT, int D, int RPW = 1>
+__device__ __forceinline__ void merge_one(const MergeParams &P, int r, int hq, int wave_lane)
 {
     constexpr int kChunk = 8;
-    constexpr int CPL = D / 64;         // channels per lane: 1, 2 or 4
+    constexpr int LPR = 64 / RPW;       // lanes per row
+    constexpr int CPL = D / LPR;        // channels per lane: 1, 2 or 4
+    static_assert(CPL == 1 || CPL == 2 || CPL == 4, "channels per lane");
+    const int lane = wave_lane % LPR;   // the lane's place in its row
+    hq += wave_lane / LPR;              // the lane's row
     const int head = hq / P.group, hj = hq - head * P.group;
     // The request's line: its number of partial rows and the first kInlineParts of them, read together
     // (no address waits for another read).  Lists of up to eight rows, and of up to kInlineParts, are
@@ -1206,6 +1220,13 @@ __device__ __forceinline__ void merge_one(const MergeParams &P, int r, int hq, i
         float o[N][CPL];
 #pragma unroll
         for (int j = 0; j < N; ++j) {
+            if constexpr (!COHERENT)        // the reduction kernel: no load for a partial that does not exist
+                if (j >= cnt) {             // (wave-uniform)
+                    ml[j] = float2{0.f, 0.f};
+#pragma unroll
+                    for (int c = 0; c < CPL; ++c) o[j][c] = 0.f;
+                    continue;
+                }
             const int64_t prow = head_base + rows[j];
             const float *src = P.part_o + prow * D + lane * CPL;
             if constexpr (COHERENT) {       // rows written by other workgroups of this launch
@@ -1281,13 +1302,14 @@ __device__ __forceinline__ void merge_one(const MergeParams &P, int r, int hq, i
     }
 }
 
-template <int DT, int D>
+template <int DT, int D, int RPW>
 __global__ void __launch_bounds__(kMergeWaves * 64) merge_kernel(const MergeParams P)
 {
-    const int row = blockIdx.x * kMergeWaves + (threadIdx.x >> 6);
-    if (row >= P.num_requests * P.h_q) return;
-    const int r = row / P.h_q;
-    merge_one<DT, false, D>(P, r, row - r * P.h_q, threadIdx.x & 63);
+    const int per_req = P.h_q / RPW;            // the launch has checked that RPW divides the group size
+    const int unit = blockIdx.x * kMergeWaves + (threadIdx.x >> 6);
+    if (unit >= P.num_requests * per_req) return;
+    const int r = unit / per_req;
+    merge_one<DT, false, D, RPW>(P, r, (unit - r * per_req) * RPW, threadIdx.x & 63);
 }
 
 // ---- single-launch mode: the reduction inside the attention launch (Sec. 4.3, parallel reduction) ----
@@ -1562,23 +1584,26 @@ int launch_stream_read(const void *buf, uint64_t chunks, uint64_t mult, int once
     return int(hipGetLastError());
 }
 
-template <int DT>
-void launch_merge_of(const MergeParams &p, int head_dim, dim3 grid, hipStream_t s)
+template <int DT, int D>
+void launch_merge_of(const MergeParams &p, hipStream_t s)
 {
-    const dim3 block(kMergeWaves * 64);
-    if (head_dim == 64)       hipLaunchKernelGGL((merge_kernel<DT, 64>), grid, block, 0, s, p);
-    else if (head_dim == 128) hipLaunchKernelGGL((merge_kernel<DT, 128>), grid, block, 0, s, p);
-    else                      hipLaunchKernelGGL((merge_kernel<DT, 256>), grid, block, 0, s, p);
+    // a wave reduces 256 / D rows at a time where the rows of a KV head's group divide that evenly
+    constexpr int kWide = 256 / D;
+    const bool wide = kWide > 1 && p.group % kWide == 0;
+    const int units = p.num_requests * (p.h_q / (wide ? kWide : 1));
+    const dim3 grid(unsigned((units + kMergeWaves - 1) / kMergeWaves)), block(kMergeWaves * 64);
+    if (wide) hipLaunchKernelGGL((merge_kernel<DT, D, kWide>), grid, block, 0, s, p);
+    else      hipLaunchKernelGGL((merge_kernel<DT, D, 1>), grid, block, 0, s, p);
 }
 
 int launch_merge(const MergeParams &p, int dtype, int head_dim, void *stream)
 {
     if (head_dim != 64 && head_dim != 128 && head_dim != 256) return int(hipErrorInvalidValue);
-    const int rows = p.num_requests * p.h_q;
-    const dim3 grid(unsigned((rows + kMergeWaves - 1) / kMergeWaves));
     hipStream_t s = static_cast<hipStream_t>(stream);
-    if (dtype == CODEC_DTYPE_FP16) launch_merge_of<CODEC_DTYPE_FP16>(p, head_dim, grid, s);
-    else                           launch_merge_of<CODEC_DTYPE_BF16>(p, head_dim, grid, s);
+    const bool half = dtype == CODEC_DTYPE_FP16;
+    if (head_dim == 64)       half ? launch_merge_of<CODEC_DTYPE_FP16, 64>(p, s) : launch_merge_of<CODEC_DTYPE_BF16, 64>(p, s);
+    else if (head_dim == 128) half ? launch_merge_of<CODEC_DTYPE_FP16, 128>(p, s) : launch_merge_of<CODEC_DTYPE_BF16, 128>(p, s);
+    else                      half ? launch_merge_of<CODEC_DTYPE_FP16, 256>(p, s) : launch_merge_of<CODEC_DTYPE_BF16, 256>(p, s);
     return int(hipGetLastError());
 }
 
