@@ -59,6 +59,10 @@ constexpr int kMergeWaves = 2;      // reduction kernel (workgroups of two waves
 constexpr int channel_tiles(int d) { return d <= 128 ? 8 : d / 16; }
 // LDS for merging the waves' states at the end of a stream task: W/2 states of NT row tiles
 constexpr int merge_bytes(int waves, int nt, int d) { return (waves / 2) * (nt * channel_tiles(d) * 64 * 4 + nt * 64 * 2) * 4; }
+// LDS of a wave that runs a task on its own: its 16 partial rows, fp32, 16 bytes between rows (the 16
+// lanes of a row group then cover all banks).  256 channels: none (the rows go out as the lanes hold them).
+constexpr int solo_stage_pitch(int d) { return d * 4 + 16; }
+constexpr int solo_stage_bytes(int d) { return d <= 128 ? 16 * solo_stage_pitch(d) : 0; }
 
 template <int DT>
 __device__ __forceinline__ f32x4 mfma16(u32x4 a, u32x4 b, f32x4 c)
@@ -457,6 +461,46 @@ __device__ __forceinline__ void gather_q(const PacParams &P, const DevTask &t, i
     }
 }
 
+// The same for a wave that ran the task on its own, through its staging area in LDS.  In registers a
+// lane holds 16-byte pieces of one row, so a store instruction of the wave would carry 16 bytes for each
+// of 16 lines, and a task of `group` rows would take eight of them however few its rows; every
+// vector-memory instruction takes a place in the CU's queue of instructions in flight, and a short task
+// has few to spare.  Staged, the task's rows (they are neighbours in the partial array) go out 1 KB of
+// consecutive memory per instruction: two instructions for four rows of 128 channels.
+template <int D>
+__device__ __forceinline__ void store_partial_staged(const PacParams &P, const DevTask &t, int head, int rows,
+                                                     int lane, const RowState<1, D> &st, char *stage)
+{
+    static_assert(D <= 128, "staging area is sized for up to 128 channels");
+    constexpr int PITCH = solo_stage_pitch(D), ROW = D * 4;
+    const int l16 = lane & 15, grp = lane >> 4;
+    const bool coherent = P.arrive != nullptr;
+    char *put = stage + l16 * PITCH + grp * 128;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+        if (grp * 32 + e * 8 >= D) continue;            // channels the head does not have
+        const f32x4 lo = {st.o[0][0][e], st.o[0][1][e], st.o[0][2][e], st.o[0][3][e]};
+        const f32x4 hi = {st.o[0][4][e], st.o[0][5][e], st.o[0][6][e], st.o[0][7][e]};
+        *reinterpret_cast<f32x4 *>(put + e * 32) = lo;
+        *reinterpret_cast<f32x4 *>(put + e * 32 + 16) = hi;
+    }
+    const int64_t prow = int64_t(head) * P.part_rows + t.part_row_base;
+    if (grp == 0 && l16 < rows) st8_partial(P.part_ml + (prow + l16) * 2, st.m[0], st.l[0], coherent);
+    __builtin_amdgcn_wave_barrier();                    // LDS serves a wave's accesses in order: no wait needed
+    float *po = P.part_o + prow * D;
+    const int bytes = rows * ROW;
+#pragma unroll
+    for (int i = 0; i < 16 * ROW / 1024; ++i) {
+        if (i * 1024 >= bytes) break;                   // wave-uniform
+        const int off = i * 1024 + lane * 16;
+        if (off < bytes) {
+            const f32x4 x = *reinterpret_cast<const f32x4 *>(stage + (off / ROW) * PITCH + off % ROW);
+            st16_partial(po + off / 4, x, coherent);
+        }
+    }
+    __builtin_amdgcn_wave_barrier();                    // the area is read before the wave's next task writes it
+}
+
 // Write one wave's rows of the partial result: unnormalised output, (reference, sum) per row.
 template <int NT, int D>
 __device__ __forceinline__ void store_partial(const PacParams &P, const DevTask &t, int head, int row0, int rows,
@@ -506,7 +550,8 @@ __device__ __forceinline__ float weight(float a, float m) { return a == m ? 1.f 
 // `wave` is the wave's index in its team.  A team of one wave (W = 1) uses no LDS and no barrier, so
 // several such waves may work on different tasks at the same time.
 template <int DT, bool ONCE, int NT, int W, int D>
-__device__ void run_stream(const PacParams &P, const DevTask &t, int head, char *lds_raw, int wave)
+__device__ void run_stream(const PacParams &P, const DevTask &t, int head, char *lds_raw, int wave,
+                           char *stage = nullptr)      // W = 1, up to 128 channels: the wave's staging area
 {
     constexpr int KS = D / 32, CT = channel_tiles(D);
     const int lane = opaque_lane();
@@ -610,7 +655,11 @@ __device__ void run_stream(const PacParams &P, const DevTask &t, int head, char 
         }
         __syncthreads();
     }
-    if (wave == 0) store_partial<NT, D>(P, t, head, 0, rows, l16, grp, st);
+    if constexpr (W == 1 && NT == 1 && D <= 128) {
+        store_partial_staged<D>(P, t, head, rows, lane, st, stage);
+    } else {
+        if (wave == 0) store_partial<NT, D>(P, t, head, 0, rows, l16, grp, st);
+    }
 }
 
 // ---- dense path: 1..256 rows, the 8 waves split the rows (32 each) and share each block ------------
@@ -1395,12 +1444,16 @@ pac_kernel(const PacParams P)     // 256 channels: two blocks of K and V in regi
     if constexpr (WIDE != 0) {
         lds = dyn_lds;
     } else {
-        __shared__ __attribute__((aligned(16))) char static_lds[merge_bytes(kNarrowWaves, 1, D)];
+        __shared__ __attribute__((aligned(16))) char static_lds[merge_bytes(kNarrowWaves, 1, D) + kNarrowWaves * solo_stage_bytes(D)];
         lds = static_lds;
     }
     const int head = blockIdx.x % P.h_kv;
     const int slot = blockIdx.x / P.h_kv;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    // staging area of this wave for tasks it runs on its own: behind the area in which a team merges its
+    // states (in the wide variant both lie in the ring, which only dense tasks fill)
+    static_assert(merge_bytes(kWideWaves, 1, kHeadDim) + kWideWaves * solo_stage_bytes(kHeadDim) <= kRingBytes, "staging areas fit the ring");
+    char *stage = lds + merge_bytes(W, 1, D) + wave * solo_stage_bytes(D);
     // Runs the task records recs[t0 .. t1).  Tasks of more than 16 rows take the dense path (wide variant
     // only).  Tasks of at most 16 rows take the stream path, as a rule with all waves of the workgroup
     // as one team.  Runs of two or more short ones are handed out one wave each through a counter in
@@ -1427,8 +1480,8 @@ pac_kernel(const PacParams P)     // 256 channels: two blocks of K and V in regi
 #pragma unroll 1
                 while (k < n) {
                     const DevTask mine = recs[i + k];
-                    if (mine.flags & kTaskReadOnce) run_stream<DT, true, 1, 1, D>(P, mine, head, lds, 0);
-                    else                run_stream<DT, false, 1, 1, D>(P, mine, head, lds, 0);
+                    if (mine.flags & kTaskReadOnce) run_stream<DT, true, 1, 1, D>(P, mine, head, lds, 0, stage);
+                    else                run_stream<DT, false, 1, 1, D>(P, mine, head, lds, 0, stage);
                     if (P.arrive) task_delivered_by_wave<DT, D>(P, mine, head);
                     k = 0;
                     if ((threadIdx.x & 63) == 0) k = atomicAdd(next, 1);
