@@ -83,11 +83,16 @@ def test_head_layouts(hq, hkv):
 
 
 @pytest.mark.parametrize("d", [64, 256])
-@pytest.mark.parametrize("case", ["cfg2", "cfg3", "ragged", "mha-drafted-masked", "mqa", "queue-fused", "flat-fp16"])
+@pytest.mark.parametrize("case", ["cfg2", "cfg3", "ragged", "mha-drafted-masked", "mqa", "queue-fused", "flat-fp16",
+                                  "group2", "group6"])
 def test_other_head_dimensions(d, case):
     """64 and 256 channels per head: the 16-row task shape only (row tiles of at most 16 rows, whatever
-    max_rows asks for), every plan option, masks, the single-launch mode and the reduction kernel."""
-    if case == "cfg2":
+    max_rows asks for), every plan option, masks, the single-launch mode and the reduction kernel (groups
+    of 1, 2, 3 and 6 heads take its one-row form with 64 channels, groups of 4, 8 and 16 four rows a wave)."""
+    if case in ("group2", "group6"):
+        g = int(case[5:])
+        f, hq, hkv, dtype, opts = three_level_forest(50, [70, 33], 2, [9, 40, 1, 130]), 2 * g, 2, DTYPE_BF16, {}
+    elif case == "cfg2":
         f, hq, hkv, dtype, opts = make_small_config("cfg2", 8, 2).forest, 32, 8, DTYPE_BF16, {}
     elif case == "cfg3":
         f, hq, hkv, dtype, opts = make_small_config("cfg3", 16, 2).forest, 32, 8, DTYPE_BF16, {"extensions": 3}
