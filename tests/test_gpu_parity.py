@@ -653,3 +653,31 @@ def test_full_size_configurations(name, layout, n_pairs):
         assert not np.any(np.isnan(got))
         assert err.max() <= TOL
         assert np.all(err <= 2e-3 + 2.0 ** -7 * np.abs(ref))
+
+
+@pytest.mark.parametrize("sweep,point", [("draft_masked", "drafted=64"), ("draft", "drafted=16"), ("batch", "requests=64"),
+                                         ("depth", "levels=6"), ("shape", "DT"), ("ratio", "shared=0.9")])
+def test_full_size_sweep_points(sweep, point):
+    """Points of the synthetic sweeps that `bench.py --sweep` times, at full size in the benchmark's
+    layout, on 512 sampled (request, head) pairs: a masked node of 64 drafted tokens per sequence, one-token
+    draft nodes, a 122880-token root under 64 requests (256 rows per KV head), a six-level binary tree, the
+    degenerate tree, 90 % sharing."""
+    from workloads.sweeps import sweep_points, sweep_head, SWEEP_SEED
+    forest = dict(sweep_points(sweep))[point]
+    w = make_workload(f"{sweep}/{point}", forest, sweep_head(), seed=SWEEP_SEED, device="cuda:0", layout="htd")
+    C = _C()
+    print(f"[case] sweep {sweep} {point} unique_kv_bytes={w.unique_kv_bytes} requests={forest.num_requests}", flush=True)
+    sel = _sample_pairs(w, 512, seed=78)
+    ref, _ = A.decode_attention_workload(w, sel=sel)
+    for opts in ({"share": 1, "extensions": 3}, {"share": 2, "schedule": 2, "extensions": 3}, {"share": 0}):
+        pa = C.PlannedAttention(w.forest, w.paged, w.head, device="cuda:0", **opts)
+        out = pa.decode(w.q, w.k_pool, w.v_pool)
+        torch.cuda.synchronize()
+        got = out.to(torch.float64).cpu().numpy()
+        pa.close()
+        g = np.stack([got[r, h] for r, h in sel])
+        err = np.abs(g - ref)
+        print(f"[case] sweep {sweep} {point} {opts} max_err={err.max():.3e}", flush=True)
+        assert not np.any(np.isnan(got))
+        assert err.max() <= TOL
+        assert np.all(err <= 2e-3 + 2.0 ** -7 * np.abs(ref))
