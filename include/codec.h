@@ -51,10 +51,11 @@ typedef struct codec_plan codec_plan_t;         /* opaque, library-owned, immuta
 typedef struct {
     int32_t num_q_heads;
     int32_t num_kv_heads;       /* must divide num_q_heads; group = ratio, 1..64        */
-    int32_t head_dim;           /* 128; or 64 or 256, which run in the 16-row task shape
-                                   only: group <= 16, query sets are tiled 16 rows at a
-                                   time (max_rows is capped), so a shared node is read once
-                                   per 16 rows, the repeats from cache                  */
+    int32_t head_dim;           /* 128; or 64 or 256, which run in the task shape for few
+                                   rows only: group <= 16, query sets are tiled 32 (64
+                                   channels) or 16 (256 channels) rows at a time (max_rows
+                                   is capped), so a shared node is read once per tile, the
+                                   repeats from cache                                   */
     int32_t dtype;              /* CODEC_DTYPE_*: type of q, K, V and out               */
     int32_t page_size;          /* tokens per KV page, a power of two, 16..4096         */
     float   scale;              /* softmax scale, 1/sqrt(head_dim) in Eq. 1             */
@@ -114,7 +115,8 @@ typedef struct {
 
 typedef struct {
     int32_t num_slots;      /* m of Eq. 3: persistent workgroups per KV head; 0 = as many as run at once:
-                               256 / num_kv_heads if a task holds more than 16 rows, else 512 / num_kv_heads */
+                               256 / num_kv_heads if a task holds more than 16 rows of 128 channels, else
+                               512 / num_kv_heads                                                   */
     int32_t split_align;    /* KV slices start on multiples of this many tokens; a multiple of
                                max(32, page_size); 0 = 256                                          */
     int32_t max_rows;       /* most query rows (requests x group) one task may hold, 1..256,

@@ -304,16 +304,25 @@ def refresh(plan_out: Dict, table: Dict, new_node_len) -> Dict:
     return out
 
 
+def max_task_rows(head_dim: int) -> int:
+    """Most rows of a task: the dense task shape (up to 256 rows, the wide kernel variant) exists for
+    128 channels; the stream shape holds 32 rows of 64 channels and 16 of 256."""
+    return {128: 256, 64: 32, 256: 16}[head_dim]
+
+
 def plan_best(parent, node_len, req_node, group: int, align: int, max_rows: int, tables: Dict,
-              num_slots_of, slack: bool = False, diagonal: bool = False, masked_nodes=()) -> Dict:
+              num_slots_of, slack: bool = False, diagonal: bool = False, masked_nodes=(),
+              head_dim: int = 128) -> Dict:
     """share = 2 of the library: the candidate with the lowest estimated makespan, ties to the earlier.
 
     Candidates: the prefix-shared plan with row tiles of ``max_rows``; with row tiles of half that (if
     more than 16 rows); with row tiles of at most 16 rows (query-dimension splits, b_q > 1 in the terms
     of Sec. 5.1); the flat plan.
     ``tables`` = {"narrow": .., "wide": ..} and ``num_slots_of(wide)`` give each candidate the table and
-    slot count of the kernel variant its widest task selects, as the library does.
+    slot count of the kernel variant its widest task selects, as the library does (the wide variant
+    exists for 128 channels; with 64 or 256 the row tiles are capped by max_task_rows).
     """
+    cap = max(group, max_task_rows(head_dim) // group * group)      # every candidate's row tiles
     cands = [(True, max_rows)]
     half = max_rows // 2 // group * group
     if half > 16 and half >= group:
@@ -324,12 +333,13 @@ def plan_best(parent, node_len, req_node, group: int, align: int, max_rows: int,
     cands.append((False, max_rows))
     best = None
     for share, rows in cands:
+        rows = min(rows, cap)
         paths, node_q = build_index([int(x) for x in parent], [int(x) for x in node_len], [int(x) for x in req_node])
         qpt_all = max(1, rows // group) if share else 1
         tile = [min(qpt_all, max(1, 16 // group)) if n in set(masked_nodes) else qpt_all for n in range(len(node_q))]
         widest = max((min(tile[n], len(q) - a) * group for n, q in enumerate(node_q)
                       for a in range(0, len(q), tile[n])), default=0)
-        wide = widest > 16
+        wide = widest > 16 and head_dim == 128
         p = plan(parent, node_len, req_node, group, num_slots_of(wide), align, rows, share,
                  tables["wide" if wide else "narrow"], slack=slack, diagonal=diagonal, masked_nodes=masked_nodes)
         p["share"], p["max_rows"] = share, rows

@@ -52,6 +52,9 @@ constexpr int kHeadDim = 128;       // the dense path; the stream path and the r
                                     // dimension D (64, 128 or 256) as a template parameter
 constexpr int kNarrowWaves = 4;     // stream-only kernel variant: 4 waves, two workgroups per CU
 constexpr int kWideWaves = 8;       // all task shapes: 8 waves (two per SIMD), one workgroup per CU
+// Row tiles of the stream path in the narrow variant: one tile of 16 rows, or two (32 rows) with 64
+// channels, where the accumulators of a second tile still fit the registers.
+constexpr int stream_tiles(int d) { return d == 64 ? 2 : 1; }
 constexpr int kMergeWaves = 2;      // reduction kernel (workgroups of two waves: measured against one and four, the
                                     // launch that follows a reduction starts up to 3 us sooner)
 // Channel tiles of 16 that a stream task accumulates: 8 per 128 channels (with 64 channels half of each
@@ -546,7 +549,7 @@ __device__ __forceinline__ SliceCtx make_ctx(const PacParams &P, const DevTask &
 // (keeps "-inf minus -inf" of a wave that saw no token out of the arithmetic).
 __device__ __forceinline__ float weight(float a, float m) { return a == m ? 1.f : fast_exp2(a - m); }
 
-// ---- stream path: rows <= 16*NT (NT = 1 in use), a team of W waves splits the tokens ---------------
+// ---- stream path: rows <= 16*NT (NT = 2 for 17 .. 32 rows of 64 channels, else 1), a team of W waves splits the tokens
 // `wave` is the wave's index in its team.  A team of one wave (W = 1) uses no LDS and no barrier, so
 // several such waves may work on different tasks at the same time.
 template <int DT, bool ONCE, int NT, int W, int D>
@@ -592,7 +595,9 @@ __device__ void run_stream(const PacParams &P, const DevTask &t, int head, char 
             mask_scores<NT>(s, valid, grp);
             mask_values<BlockRegs<D>::VU>(r.v, valid, grp);
         }
-        if (masked) mask_invisible<NT>(s, r.visible, grp);
+        if constexpr (NT == 1) {            // tasks with masks are planned as tiles of at most 16 rows
+            if (masked) mask_invisible<NT>(s, r.visible, grp);
+        }
         float lm[NT];
         lane_maxima<NT>(s, P.scale_log2e, lm);
         if (__any(outgrown<NT, D>(lm, st))) raise_reference<NT, D>(lm, st);
@@ -1444,7 +1449,7 @@ pac_kernel(const PacParams P)     // 256 channels: two blocks of K and V in regi
     if constexpr (WIDE != 0) {
         lds = dyn_lds;
     } else {
-        __shared__ __attribute__((aligned(16))) char static_lds[merge_bytes(kNarrowWaves, 1, D) + kNarrowWaves * solo_stage_bytes(D)];
+        __shared__ __attribute__((aligned(16))) char static_lds[merge_bytes(kNarrowWaves, stream_tiles(D), D) + kNarrowWaves * solo_stage_bytes(D)];
         lds = static_lds;
     }
     const int head = blockIdx.x % P.h_kv;
@@ -1453,7 +1458,7 @@ pac_kernel(const PacParams P)     // 256 channels: two blocks of K and V in regi
     // staging area of this wave for tasks it runs on its own: behind the area in which a team merges its
     // states (in the wide variant both lie in the ring, which only dense tasks fill)
     static_assert(merge_bytes(kWideWaves, 1, kHeadDim) + kWideWaves * solo_stage_bytes(kHeadDim) <= kRingBytes, "staging areas fit the ring");
-    char *stage = lds + merge_bytes(W, 1, D) + wave * solo_stage_bytes(D);
+    char *stage = lds + merge_bytes(W, WIDE ? 1 : stream_tiles(D), D) + wave * solo_stage_bytes(D);
     // Runs the task records recs[t0 .. t1).  Tasks of more than 16 rows take the dense path (wide variant
     // only).  Tasks of at most 16 rows take the stream path, as a rule with all waves of the workgroup
     // as one team.  Runs of two or more short ones are handed out one wave each through a counter in
@@ -1495,6 +1500,10 @@ pac_kernel(const PacParams P)     // 256 channels: two blocks of K and V in regi
                     else             run_stream<DT, false, 1, W, D>(P, t, head, lds, wave);
                 }
                 else if constexpr (WIDE != 0) run_dense32<DT>(P, t, head, lds);
+                else if constexpr (stream_tiles(D) == 2) {      // 17 .. 32 rows of 64 channels: two row tiles
+                    if (t.flags & kTaskReadOnce) run_stream<DT, true, 2, W, D>(P, t, head, lds, wave);
+                    else             run_stream<DT, false, 2, W, D>(P, t, head, lds, wave);
+                }
                 if (P.arrive) task_delivered_by_workgroup<DT, D>(P, t, head, lds, W);
                 ++i;
             }
@@ -1607,8 +1616,10 @@ void launch_narrow(const PacParams &p, dim3 grid, hipStream_t s)
 
 int launch_pac(const PacParams &p, int dtype, int head_dim, int num_slots, int max_rows_in_plan, void *stream)
 {
-    const bool wide = max_rows_in_plan > 16;
-    if (wide && head_dim != kHeadDim) return int(hipErrorInvalidValue);     // the planner never builds such a plan
+    if (head_dim != 64 && head_dim != 128 && head_dim != 256) return int(hipErrorInvalidValue);
+    const bool wide = head_dim == kHeadDim && max_rows_in_plan > 16;
+    // the planner never builds a plan with more rows per task than the variant runs
+    if (!wide && max_rows_in_plan > 16 * stream_tiles(head_dim)) return int(hipErrorInvalidValue);
     const dim3 grid(unsigned(num_slots) * unsigned(p.h_kv)), block((wide ? kWideWaves : kNarrowWaves) * 64);
     hipStream_t s = static_cast<hipStream_t>(stream);
     const bool f16 = dtype == CODEC_DTYPE_FP16;

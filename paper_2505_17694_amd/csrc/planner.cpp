@@ -309,9 +309,10 @@ int build_plan(const codec_tree &tree, const codec_head_config &head,
     const int32_t align = opt.split_align > 0 ? opt.split_align : std::max(256, head.page_size);
     int32_t max_rows = opt.max_rows > 0 ? opt.max_rows : std::max(256, group);
     if (head.head_dim != 128) {
-        // 64 and 256 channels run in the 16-row task shape only: row tiles of at most 16 rows
+        // 64 and 256 channels run in the stream task shape only: row tiles of at most 32 and 16 rows
         if (group > kSoloMaxRows) return CODEC_ERR_UNSUPPORTED;
-        max_rows = std::min(max_rows, std::max(group, kSoloMaxRows / group * group));
+        const int32_t tile = max_task_rows(head.head_dim);
+        max_rows = std::min(max_rows, std::max(group, tile / group * group));
     }
     if (opt.num_slots < 0 || opt.split_align < 0 || opt.max_rows < 0) return CODEC_ERR_INVALID_ARGUMENT;
     if (opt.num_slots > (1 << 20)) return CODEC_ERR_INVALID_ARGUMENT;
@@ -449,7 +450,7 @@ int build_plan(const codec_tree &tree, const codec_head_config &head,
     // otherwise two narrow workgroups share a CU.  It fixes the default slot count and cost table.
     int32_t widest = 0;
     for (const codec_item &it : p.items) widest = std::max(widest, it.rows);
-    const bool wide = widest > 16;
+    const bool wide = widest > 16 && head.head_dim == 128;
     const int32_t m = opt.num_slots > 0 ? opt.num_slots : std::max(1, (wide ? 256 : 512) / head.num_kv_heads);
     p.num_slots = m;
     if (!table) table = &builtin_cost_table(wide);

@@ -22,6 +22,9 @@ struct CostTable {
 // A task of at most kSoloMaxRows rows and kSoloMaxLen tokens may be run by a single wave; the kernels
 // take runs of such tasks in a slot's list one wave each (see solo_run below).
 constexpr int32_t kSoloMaxRows = 16;
+// Most rows of a task with `head_dim` channels: 256 in the dense task shape, which exists for 128 channels;
+// otherwise what the stream shape holds, two row tiles of 16 with 64 channels and one with 256.
+constexpr int32_t max_task_rows(int32_t head_dim) { return head_dim == 128 ? 256 : head_dim == 64 ? 32 : 16; }
 constexpr int32_t kSoloMaxLen = 2048;
 // Most short tasks in one entry of the run-time queue (measured on cfg3/cfg4: 2 costs fetches, 8 and
 // more make the last entries long).

@@ -86,8 +86,8 @@ def test_head_layouts(hq, hkv):
 @pytest.mark.parametrize("case", ["cfg2", "cfg3", "ragged", "mha-drafted-masked", "mqa", "queue-fused", "flat-fp16",
                                   "group2", "group6"])
 def test_other_head_dimensions(d, case):
-    """64 and 256 channels per head: the 16-row task shape only (row tiles of at most 16 rows, whatever
-    max_rows asks for), every plan option, masks, the single-launch mode and the reduction kernel (groups
+    """64 and 256 channels per head: the stream task shape only (row tiles of at most 32 and 16 rows,
+    whatever max_rows asks for), every plan option, masks, the single-launch mode and the reduction kernel (groups
     of 1, 2, 3 and 6 heads take its one-row form with 64 channels, groups of 4, 8 and 16 four rows a wave)."""
     if case in ("group2", "group6"):
         g = int(case[5:])
@@ -112,7 +112,23 @@ def test_other_head_dimensions(d, case):
     w = make_workload(f"d{d}-{case}", f, HeadConfig(hq, hkv, d, dtype), seed=600 + d, poison=True,
                       layout="htd" if d == 64 else "thd")
     _, view = check(w, **opts)
-    assert max(t["n_req"] * (hq // hkv) for t in view["tasks"]) <= 16
+    assert max(t["n_req"] * (hq // hkv) for t in view["tasks"]) <= (32 if d == 64 else 16)
+
+
+@pytest.mark.parametrize("hq,hkv,requests", [(8, 2, 5), (8, 2, 7), (8, 2, 8), (4, 4, 17), (4, 4, 31), (4, 4, 33), (12, 4, 10)])
+@pytest.mark.parametrize("dtype", [DTYPE_BF16, DTYPE_FP16])
+def test_two_row_tiles_with_64_channels(hq, hkv, requests, dtype):
+    """Tasks of 17 .. 32 rows of 64 channels (two row tiles per wave): 20, 28, 32, 17, 31, 30 rows and a
+    33-row set that splits into 32 + 1; ragged nodes of one block and of many, long enough for a team of
+    waves and short enough for runs of single-wave tasks beside them."""
+    f = two_level_forest(1500, [1 + 37 * (i % 4) for i in range(requests)])
+    f = concat_forests(concat_forests(f, two_level_forest(33, [20] * requests)), unshared_forest([70, 2100, 5]))
+    w = make_workload(f"d64-rows-{hq}-{hkv}-{requests}", f, HeadConfig(hq, hkv, 64, dtype), seed=640 + requests, poison=True,
+                      layout="htd")
+    for opts in ({}, {"num_slots": 2, "split_align": 32}, {"fused": 1}, {"schedule": 1, "num_slots": 3}):
+        _, view = check(w, **opts)
+        rows = [t["n_req"] * (hq // hkv) for t in view["tasks"]]
+        assert max(rows) <= 32 and max(rows) > 16
 
 
 @pytest.mark.parametrize("max_rows", [8, 16, 32, 48, 64, 100, 128, 200, 256])

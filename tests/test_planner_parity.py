@@ -478,3 +478,30 @@ def test_refresh_keeps_masked_nodes_as_they_are():
     gp = build_paged_kv(g, head, seed=1)
     assert C.codec_plan_refresh_lengths(plan, grown, gp.node_page_off, gp.page_ids) == C.CODEC_ERR_INVALID_ARGUMENT
     C.codec_plan_destroy(plan)
+
+
+# ---- head dimensions 64 and 256: capped row tiles, the narrow kernel variant's table and slot count ----
+@pytest.mark.parametrize("head_dim", [64, 256])
+@pytest.mark.parametrize("name", ["docqa", "three", "random", "binary"])
+@pytest.mark.parametrize("hq,hkv", [(32, 8), (8, 8), (16, 1)])
+@pytest.mark.parametrize("share", [1, 0, 2])
+def test_other_head_dimensions_plan(head_dim, name, hq, hkv, share):
+    """With 64 (256) channels a task holds at most 32 (16) rows whatever max_rows asks for, and the plan
+    takes the slot count and cost table of the kernel variant that runs such tasks."""
+    f = FORESTS[name]()
+    head = HeadConfig(hq, hkv, head_dim)
+    group = hq // hkv
+    view = _lib_plan(f, head, 0, 0, 0, share, None, 3)
+    cap = max(group, P.max_task_rows(head_dim) // group * group)
+    assert max(t["n_req"] * group for t in view["tasks"]) <= cap
+    m = 512 // hkv
+    assert view["num_slots"] == m
+    if share == 2:
+        tables = {"narrow": _default_table(0), "wide": _default_table(1)}
+        ref = P.plan_best(f.parent, f.node_len, f.req_node, group, 256, 256, tables, lambda wide: (256 if wide else 512) // hkv,
+                          slack=True, diagonal=True, head_dim=head_dim)
+        assert (view["share"], view["max_rows"]) == (int(ref["share"]), ref["max_rows"])
+    else:
+        ref = P.plan(f.parent, f.node_len, f.req_node, group, m, 256, cap, bool(share), _default_table(0),
+                     slack=True, diagonal=True)
+    _compare(view, ref)
